@@ -1,0 +1,165 @@
+"""Pins for the oracle's STFT power, VTLP-warped mel bank (Eq. 1) and power law.  CPU only."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import aug_oracle as O
+from paper_1912_11040_amd.workloads import FrontendConfig
+
+FE = FrontendConfig()
+
+
+def test_frame_count():
+    assert O.frame_count(399, 400, 160) == 0
+    assert O.frame_count(400, 400, 160) == 1
+    assert O.frame_count(559, 400, 160) == 1
+    assert O.frame_count(560, 400, 160) == 2
+    assert [O.frame_count(n, 400, 160) for n in (16000, 64000, 128000, 160000)] == [98, 398, 798, 998]
+
+
+def test_hamming_is_symmetric_with_known_ends():
+    w = O.hamming(400)
+    np.testing.assert_allclose(w, w[::-1], atol=1e-15)
+    assert w[0] == pytest.approx(0.08) and w.max() < 1.0 and w[199] == pytest.approx(w[200])
+    assert O.hamming(401)[200] == pytest.approx(1.0)
+
+
+def test_parseval_on_full_spectrum():
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal(400 + 160 * 3)
+    p = O.stft_power(x, 400, 160, 512)
+    assert p.shape == (4, 257)
+    w = O.hamming(400)
+    for t in range(4):
+        frame = x[t * 160:t * 160 + 400] * w
+        # bins 1..255 appear twice in the 512-point spectrum of a real frame
+        full = p[t, 0] + p[t, 256] + 2 * p[t, 1:256].sum()
+        assert full / 512 == pytest.approx(np.sum(frame ** 2), rel=1e-12)
+
+
+def test_pure_tone_peaks_in_its_bin_and_matches_window_gain():
+    k0 = 37
+    n = np.arange(400 + 160)
+    x = np.cos(2 * np.pi * k0 * n / 512)
+    p = O.stft_power(x, 400, 160, 512)
+    assert np.all(np.argmax(p, axis=1) == k0)
+    # at the tone's own bin the DFT is (sum of window)/2 plus a small image term
+    assert math.sqrt(p[0, k0]) == pytest.approx(O.hamming(400).sum() / 2, rel=1e-2)
+
+
+def test_dft_matrix_equals_library_fft():
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal(2000)
+    np.testing.assert_allclose(O.stft_power(x, 400, 160, 512, "dft"),
+                               O.stft_power(x, 400, 160, 512, "fft"), rtol=1e-9, atol=1e-9)
+
+
+def test_no_scaling_no_normalisation():
+    # a unit impulse in the middle of the frame has a flat power spectrum w[i]^2
+    x = np.zeros(400); x[123] = 1.0
+    p = O.stft_power(x, 400, 160, 512)
+    np.testing.assert_allclose(p[0], O.hamming(400)[123] ** 2, rtol=1e-12)
+
+
+def test_warp_identity_endpoints_and_closed_form():
+    om = np.linspace(0, np.pi, 257)
+    np.testing.assert_array_equal(O.bilinear_warp(om, 1.0), om)           # alpha = 1: no warp
+    for alpha in (0.8, 0.9, 1.1, 1.2):
+        w = O.bilinear_warp(om, alpha)
+        assert w[0] == 0.0 and w[-1] == pytest.approx(np.pi, abs=1e-12)
+        assert np.all(np.diff(w) > 0)
+        # first-order all-pass: tan(w'/2) = ((1+a)/(1-a)) tan(w/2), a = 1 - alpha
+        ref = 2 * np.arctan((2 - alpha) / alpha * np.tan(om[:-1] / 2))
+        np.testing.assert_allclose(w[:-1], ref, atol=1e-12)
+    # alpha < 1 moves frequencies up
+    assert O.bilinear_warp(1.0, 0.8) > 1.0 > O.bilinear_warp(1.0, 1.2)
+
+
+def test_mel_edges():
+    e = O.mel_edges_hz(40, 0.0, 8000.0)
+    assert len(e) == 42 and e[0] == pytest.approx(0.0, abs=1e-9) and e[-1] == pytest.approx(8000.0)
+    mel = 2595 * np.log10(1 + e / 700)
+    np.testing.assert_allclose(np.diff(mel), mel[-1] / 41, rtol=1e-9)
+    # the scale is defined so that 1000 Hz is about 1000 mel
+    assert 2595 * math.log10(1 + 1000 / 700) == pytest.approx(1000, abs=0.1)
+
+
+def _plain_mel(n_mel, nfft, fs, f_lo, f_hi):
+    """Unwarped triangular bank built by linear interpolation between band edges."""
+    e = O.mel_edges_hz(n_mel, f_lo, f_hi)
+    f = np.arange(nfft // 2 + 1) * fs / nfft
+    w = np.zeros((n_mel, len(f)))
+    for m in range(n_mel):
+        w[m] = np.interp(f, [e[m], e[m + 1], e[m + 2]], [0.0, 1.0, 0.0], left=0.0, right=0.0)
+    return w
+
+
+def test_alpha_one_is_the_plain_mel_bank():
+    w = O.warped_mel_matrix(1.0, 40, 512, 16000.0, 0.0, 8000.0)
+    np.testing.assert_allclose(w, _plain_mel(40, 512, 16000.0, 0.0, 8000.0), atol=1e-12)
+
+
+def test_warped_bank_is_plain_bank_read_at_warped_frequencies():
+    e = O.mel_edges_hz(40, 0.0, 8000.0)
+    for alpha in (0.8, 1.2):
+        w = O.warped_mel_matrix(alpha, 40, 512, 16000.0, 0.0, 8000.0)
+        k = np.arange(257)
+        fw = 2 * np.arctan((2 - np.float64(np.float32(alpha))) / np.float64(np.float32(alpha))
+                           * np.tan(np.pi * k[:-1] / 512)) * 16000 / (2 * np.pi)
+        for m in (0, 7, 20, 39):
+            ref = np.interp(fw, [e[m], e[m + 1], e[m + 2]], [0, 1, 0], left=0, right=0)
+            np.testing.assert_allclose(w[m, :-1], ref, atol=1e-9)
+        assert w.min() >= 0 and w.max() <= 1
+        # partition of unity between the first and last filter centres
+        inside = (fw >= e[1]) & (fw <= e[40])
+        np.testing.assert_allclose(w[:, :-1].sum(0)[inside], 1.0, atol=1e-9)
+        # at most two filters are non-zero in any bin
+        assert (np.count_nonzero(w, axis=0) <= 2).all()
+
+
+def test_tone_lands_in_channel_of_warped_frequency():
+    e = O.mel_edges_hz(40, 0.0, 8000.0)
+    k0 = 64                                               # 2000 Hz
+    x = np.cos(2 * np.pi * k0 * np.arange(2000) / 512).astype(np.float32)
+    off = np.array([0, 2000], dtype=np.int64)
+    for alpha in (0.8, 1.0, 1.2):
+        f = O.vtlp_mel_batch(off, x, np.array([alpha], np.float32), FE)
+        fw = 2 * math.atan((2 - alpha) / alpha * math.tan(math.pi * k0 / 512)) * 16000 / (2 * math.pi)
+        centre = np.argmin(np.abs(e[1:41] - fw))
+        assert abs(int(np.argmax(f[0])) - centre) <= 1
+    hi = O.vtlp_mel_batch(off, x, np.array([0.8], np.float32), FE)[0].argmax()
+    lo = O.vtlp_mel_batch(off, x, np.array([1.2], np.float32), FE)[0].argmax()
+    assert hi > lo
+
+
+def test_power_law_and_scale_covariance():
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal(3000).astype(np.float32)
+    off = np.array([0, 3000], dtype=np.int64)
+    a = np.array([0.93], np.float32)
+    f1 = O.vtlp_mel_batch(off, x, a, FE)
+    assert f1.shape == (O.frame_count(3000, 400, 160), 40)
+    # exponent is exactly 1/15 of the mel energies
+    p = O.stft_power(x, 400, 160, 512)
+    w = O.warped_mel_matrix(a[0], 40, 512, 16000.0, 0.0, 8000.0)
+    np.testing.assert_allclose(f1 ** 15, p @ w.T, rtol=1e-10)
+    # no normalisation and no clipping: scaling the waveform by c scales features by c^(2/15)
+    f4 = O.vtlp_mel_batch(off, 4.0 * x, a, FE)
+    np.testing.assert_allclose(f4, 4.0 ** (2 / 15) * f1, rtol=1e-12)
+    big = O.vtlp_mel_batch(off, 1e4 * x, a, FE)
+    assert big.max() > 3.0
+    # silence maps to exactly zero
+    z = O.vtlp_mel_batch(off, np.zeros(3000, np.float32), a, FE)
+    np.testing.assert_array_equal(z, 0.0)
+
+
+def test_ragged_and_short_utterances():
+    rng = np.random.default_rng(3)
+    off = np.array([0, 399, 399, 1200, 1200 + 560], dtype=np.int64)
+    x = rng.standard_normal(off[-1]).astype(np.float32)
+    a = np.array([0.8, 1.0, 1.1, 1.2], np.float32)
+    f = O.vtlp_mel_batch(off, x, a, FE)
+    assert f.shape == (0 + 0 + 3 + 2, 40)
+    g = O.vtlp_mel_batch(np.array([0, 560], np.int64), x[1200:], a[3:], FE)
+    np.testing.assert_array_equal(f[3:], g)
