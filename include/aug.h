@@ -1,0 +1,199 @@
+/*
+ * aug.h -- C ABI of the on-the-fly speech augmentation + power-mel front end
+ * for AMD MI355X (gfx950).
+ *
+ * The library runs, on one GPU, the per-utterance work that the paper's
+ * example servers do before features reach the trainer (Sec. 2.3, "Data
+ * augmentation and feature extraction"): room impulse responses computed on
+ * the fly by the image method, reverberation of the speech and of every noise
+ * source with its own response, additive mixing at a drawn SNR, and
+ * power-mel filterbank features with the vocal-tract-length-perturbation
+ * warp of Eq. (1) and the (.)^(1/15) power law.
+ *
+ * Conventions (all entry points)
+ *   - Pointers marked DEVICE are HBM addresses on the context's GPU, owned by
+ *     the caller; the library reads inputs, writes outputs and never frees or
+ *     keeps them.  Pointers marked HOST are ordinary host memory, read before
+ *     the call returns.
+ *   - Work is enqueued on the context's HIP stream and the call returns
+ *     without waiting for it; the caller synchronises that stream before
+ *     reading outputs.  Calls on one context must not overlap in time from
+ *     several host threads.
+ *   - The context owns a private device workspace (impulse-response spectra,
+ *     reverberated signals, energies, warp tables); it grows on demand and is
+ *     released by aug_destroy.
+ *   - Every function returns AUG_OK (0) or a negative aug_status; nothing is
+ *     thrown across the boundary.  aug_last_error gives the message of the
+ *     last failure on that context.  Arguments are checked on the host before
+ *     anything is launched; a failed call launches nothing.
+ *   - All random draws (rooms, positions, SNRs, warp factors) are inputs.
+ */
+#ifndef AUG_H_
+#define AUG_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum aug_status {
+    AUG_OK = 0,
+    AUG_ERR_INVALID_ARG = -1,   /* null pointer, non-positive size, offsets not ascending, ... */
+    AUG_ERR_UNSUPPORTED = -2,   /* a size outside what the kernels are built for */
+    AUG_ERR_NOMEM = -3,         /* workspace allocation failed */
+    AUG_ERR_HIP = -4            /* a HIP runtime call failed */
+} aug_status;
+
+typedef struct aug_ctx aug_ctx;
+
+/* Largest impulse response, in taps, that aug_rir_batch / aug_convolve_mix_batch accept. */
+#define AUG_MAX_RIR_LEN 32768
+/* Largest number of noise sources per utterance. */
+#define AUG_MAX_NOISE 8
+/* Largest number of mel channels. */
+#define AUG_MAX_MEL 128
+
+/*
+ * Create a context bound to GPU `device_id` and to `hip_stream` (a hipStream_t
+ * passed as void*; NULL = the device's default stream).  *out receives the
+ * context.  The stream must outlive the context.
+ */
+int aug_create(aug_ctx** out, int device_id, void* hip_stream);
+
+/* Wait for the context's stream, free the workspace and the context. NULL is accepted. */
+int aug_destroy(aug_ctx* ctx);
+
+/* Message of the last failed call on `ctx` ("" if none); valid until the next call on it. */
+const char* aug_last_error(const aug_ctx* ctx);
+
+/*
+ * Number of analysis frames of an `n_samples` long signal: frames lie wholly
+ * inside the signal (no padding), 1 + (n_samples - win) / hop, or 0 when
+ * n_samples < win.  Host helper; returns -1 for win <= 0 or hop <= 0.
+ */
+int64_t aug_frame_count(int64_t n_samples, int win, int hop);
+
+/*
+ * Room impulse responses by the image method (the acoustic simulator of
+ * Sec. 2.3 computes them on the fly for every example).
+ *
+ *   geom           DEVICE float [n_rir][10]: room Lx,Ly,Lz (m), source x,y,z,
+ *                  microphone x,y,z, wall reflection coefficient beta.  The box
+ *                  is [0,Lx]x[0,Ly]x[0,Lz]; source and microphone must lie
+ *                  inside it and not coincide (not checked on the device).
+ *   rir_len        taps per response, 1..AUG_MAX_RIR_LEN.
+ *   fs, c          sample rate (Hz) and speed of sound (m/s), both > 0.
+ *   rir_out        DEVICE float [n_rir][rir_len], overwritten:
+ *                  h[n] = sum over image sources with round(d fs / c) == n of
+ *                  beta^(reflections) / (4 pi d), d = image-to-microphone
+ *                  distance.  The tap index is evaluated in fp64 as
+ *                  floor(sqrt((dx*dx + dy*dy) + dz*dz) * (fs / c) + 0.5).
+ *   tap_count_out  DEVICE int32 [n_rir][rir_len] or NULL: number of images
+ *                  that landed on each tap (exact, order independent).
+ *
+ * n_rir == 0 is a no-op.
+ */
+int aug_rir_batch(aug_ctx* ctx, int n_rir, const float* geom, int rir_len,
+                  float fs, float c, float* rir_out, int32_t* tap_count_out);
+
+/*
+ * Reverberation and additive noise (acoustic simulator, Sec. 2.3): every
+ * source is convolved with its own impulse response, then each noise is scaled
+ * to its SNR against the reverberated speech and added.
+ *
+ *   offsets     HOST int64 [n_utt+1], ascending, offsets[0] == 0: utterance u
+ *               occupies samples offsets[u] .. offsets[u+1]-1 of every packed
+ *               signal array.  Empty utterances are allowed.
+ *   speech      DEVICE float [total], total = offsets[n_utt].
+ *   n_noise     0..AUG_MAX_NOISE noise sources per utterance.
+ *   noise       DEVICE float [n_noise][total] (NULL iff n_noise == 0).
+ *   rir         DEVICE float [n_utt][1+n_noise][rir_len]; source 0 is the speech.
+ *   snr_db      DEVICE float [n_utt][n_noise] (NULL iff n_noise == 0).
+ *   mixed_out   DEVICE float [total], overwritten:
+ *               y_j[n] = sum_{k<=n, k<rir_len} h_j[k] x_j[n-k]  (causal, input
+ *               length kept, the tail past the end is dropped),
+ *               E_j = sum_n y_j[n]^2,  g_j = sqrt(E_0 / (E_j 10^(snr_j/10)))
+ *               (0 if E_0 or E_j is 0),  mixed = y_0 + sum_j g_j y_j.
+ *   gains_out   DEVICE float [n_utt][n_noise] or NULL: the g_j.
+ */
+int aug_convolve_mix_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets,
+                           const float* speech, int n_noise, const float* noise,
+                           const float* rir, int rir_len, const float* snr_db,
+                           float* mixed_out, float* gains_out);
+
+/* Front-end constants.  win <= nfft, nfft a power of two in 64..2048 (kernels
+ * are built for 512), hop >= 1, 1 <= n_mel <= AUG_MAX_MEL, 0 <= f_lo < f_hi <= fs/2. */
+typedef struct aug_frontend_cfg {
+    float fs;       /* sample rate, Hz */
+    int   win;      /* window length in samples (symmetric Hamming) */
+    int   hop;      /* frame shift in samples */
+    int   nfft;     /* DFT size K of Eq. (1) */
+    int   n_mel;    /* mel channels */
+    float f_lo;     /* lowest band edge, Hz */
+    float f_hi;     /* highest band edge, Hz */
+    float power;    /* power-law exponent, 1/15 in the paper */
+} aug_frontend_cfg;
+
+/*
+ * Power-mel features with the VTLP warp (Sec. 2.3, Eq. (1)).
+ *
+ *   offsets        HOST int64 [n_utt+1] as above.
+ *   wave           DEVICE float [total].
+ *   alpha          DEVICE float [n_utt]: warp factor of each utterance
+ *                  (1 = no warp; the paper's best range is [0.8, 1.2]).
+ *   frame_offsets  HOST int64 [n_utt+1]: prefix sum of
+ *                  aug_frame_count(length_u, win, hop); checked.
+ *   feats_out      DEVICE float [total_frames][n_mel], row major, overwritten:
+ *                  frame t of utterance u = (sum_k W[m][k] P_t[k])^power with
+ *                  P_t[k] = |DFT_nfft(hamming * x[t hop .. t hop + win))[k]|^2,
+ *                  k = 0..nfft/2, and W[m][k] the unit-peak triangular mel
+ *                  filter m (mel = 2595 log10(1 + f/700), n_mel + 2 edges
+ *                  equally spaced in mel on [f_lo, f_hi]) read at the warped
+ *                  frequency of bin k,
+ *                  w' = w + 2 atan((1-alpha) sin w / (1 - (1-alpha) cos w)),
+ *                  w = 2 pi k / nfft.  Zero energy gives zero.
+ */
+int aug_vtlp_mel_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, const float* wave,
+                       const float* alpha, const aug_frontend_cfg* cfg,
+                       const int64_t* frame_offsets, float* feats_out);
+
+/*
+ * The whole path in one call: aug_rir_batch on geom, aug_convolve_mix_batch
+ * with those responses, aug_vtlp_mel_batch on the mixture.  Arguments as in
+ * the three calls above; geom is DEVICE float [n_utt][1+n_noise][10].
+ * Responses and the mixture stay in the context's workspace unless asked for:
+ *   rir_out    DEVICE float [n_utt][1+n_noise][rir_len] or NULL
+ *   mixed_out  DEVICE float [total] or NULL
+ *   gains_out  DEVICE float [n_utt][n_noise] or NULL
+ */
+int aug_pipeline_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, const float* speech,
+                       int n_noise, const float* noise, const float* geom, int rir_len,
+                       float fs, float c, const float* snr_db, const float* alpha,
+                       const aug_frontend_cfg* cfg, const int64_t* frame_offsets,
+                       float* feats_out, float* rir_out, float* mixed_out, float* gains_out);
+
+/*
+ * Per-stage device timing, for measurement (the stages are those of Sec. 2.3's path).
+ * While enabled, every call records HIP events on the context's stream around each
+ * stage's kernels.  aug_profile_read waits for the stream, adds up the elapsed
+ * milliseconds of every stage recorded since the last read into
+ * ms_out[AUG_N_STAGES] (HOST float) and the number of times each stage ran into
+ * launches_out[AUG_N_STAGES] (HOST int32, may be NULL), then forgets them.
+ */
+enum {
+    AUG_STAGE_RIR = 0,        /* image-sum kernel */
+    AUG_STAGE_RIR_SPECTRUM,   /* transforms of the response partitions */
+    AUG_STAGE_CONVOLVE,       /* overlap-save reverberation + energies */
+    AUG_STAGE_MIX,            /* SNR gains and mixture */
+    AUG_STAGE_MEL,            /* STFT power, warped mel, power law */
+    AUG_STAGE_OTHER,          /* clears and small tables */
+    AUG_N_STAGES
+};
+int aug_profile_enable(aug_ctx* ctx, int on);
+int aug_profile_read(aug_ctx* ctx, float* ms_out, int32_t* launches_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AUG_H_ */

@@ -1,0 +1,206 @@
+"""ctypes binding of libaug.so: argument marshalling only.
+
+Every step of the path runs in the HIP kernels behind the C ABI declared in
+include/aug.h.  PyTorch tensors supply device memory and the stream.  There is
+no CPU fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libaug.so")
+
+AUG_OK = 0
+AUG_ERR_INVALID_ARG = -1
+AUG_ERR_UNSUPPORTED = -2
+AUG_ERR_NOMEM = -3
+AUG_ERR_HIP = -4
+
+EXPORTS = ("aug_create", "aug_destroy", "aug_last_error", "aug_frame_count", "aug_rir_batch",
+           "aug_convolve_mix_batch", "aug_vtlp_mel_batch", "aug_pipeline_batch",
+           "aug_profile_enable", "aug_profile_read")
+
+STAGES = ("rir", "rir_spectrum", "convolve", "mix", "mel", "other")
+
+
+class AugError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"libaug error {code}: {message}")
+        self.code = code
+
+
+class FrontendCfg(ctypes.Structure):
+    """Mirror of aug_frontend_cfg."""
+    _fields_ = [("fs", ctypes.c_float), ("win", ctypes.c_int), ("hop", ctypes.c_int),
+                ("nfft", ctypes.c_int), ("n_mel", ctypes.c_int), ("f_lo", ctypes.c_float),
+                ("f_hi", ctypes.c_float), ("power", ctypes.c_float)]
+
+    @classmethod
+    def of(cls, fe) -> "FrontendCfg":
+        return cls(float(fe.fs), int(fe.win), int(fe.hop), int(fe.nfft), int(fe.n_mel),
+                   float(fe.f_lo), float(fe.f_hi), float(fe.power))
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libaug.so (built in-tree by build.py); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build the HIP library first "
+            "(python -m paper_1912_11040_amd.build); there is no CPU fallback")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ci, cf, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_int64
+    p_i64 = ctypes.POINTER(ctypes.c_int64)
+    p_cfg = ctypes.POINTER(FrontendCfg)
+    lib.aug_create.argtypes = [ctypes.POINTER(vp), ci, vp]
+    lib.aug_create.restype = ci
+    lib.aug_destroy.argtypes = [vp]
+    lib.aug_destroy.restype = ci
+    lib.aug_last_error.argtypes = [vp]
+    lib.aug_last_error.restype = ctypes.c_char_p
+    lib.aug_frame_count.argtypes = [i64, ci, ci]
+    lib.aug_frame_count.restype = i64
+    lib.aug_rir_batch.argtypes = [vp, ci, vp, ci, cf, cf, vp, vp]
+    lib.aug_rir_batch.restype = ci
+    lib.aug_convolve_mix_batch.argtypes = [vp, ci, p_i64, vp, ci, vp, vp, ci, vp, vp, vp]
+    lib.aug_convolve_mix_batch.restype = ci
+    lib.aug_vtlp_mel_batch.argtypes = [vp, ci, p_i64, vp, vp, p_cfg, p_i64, vp]
+    lib.aug_vtlp_mel_batch.restype = ci
+    lib.aug_pipeline_batch.argtypes = [vp, ci, p_i64, vp, ci, vp, vp, ci, cf, cf, vp, vp, p_cfg,
+                                       p_i64, vp, vp, vp, vp]
+    lib.aug_pipeline_batch.restype = ci
+    lib.aug_profile_enable.argtypes = [vp, ci]
+    lib.aug_profile_enable.restype = ci
+    lib.aug_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int32)]
+    lib.aug_profile_read.restype = ci
+    _lib = lib
+    return lib
+
+
+def aug_frame_count(n_samples: int, win: int, hop: int) -> int:
+    return int(load_library().aug_frame_count(int(n_samples), int(win), int(hop)))
+
+
+def _host_i64(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int64))
+
+
+def _ptr(t, dtype=None):
+    """Device address of a contiguous CUDA/HIP torch tensor (None -> NULL)."""
+    if t is None:
+        return None
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("expected a torch tensor in device memory")
+    if not t.is_contiguous():
+        raise ValueError("device tensors must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected dtype {dtype}, got {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+class Augmenter:
+    """One library context bound to a device and a stream (torch's current stream by default)."""
+
+    def __init__(self, device: int = 0, stream=None):
+        import torch
+        self._lib = load_library()
+        if stream is None:
+            stream = torch.cuda.current_stream(device)
+        self.stream = stream
+        self.device = device
+        handle = ctypes.c_void_p()
+        rc = self._lib.aug_create(ctypes.byref(handle), int(device), ctypes.c_void_p(stream.cuda_stream))
+        if rc != AUG_OK:
+            raise AugError(rc, "aug_create failed")
+        self._h = handle
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.aug_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def _check(self, rc: int):
+        if rc != AUG_OK:
+            raise AugError(rc, self._lib.aug_last_error(self._h).decode())
+
+    def aug_profile_enable(self, on: bool):
+        self._check(self._lib.aug_profile_enable(self._h, int(bool(on))))
+
+    def aug_profile_read(self):
+        """Wait for the stream; {stage: (total ms, launches)} since the last read."""
+        ms = (ctypes.c_float * len(STAGES))()
+        n = (ctypes.c_int32 * len(STAGES))()
+        self._check(self._lib.aug_profile_read(self._h, ms, n))
+        return {name: (float(ms[i]), int(n[i])) for i, name in enumerate(STAGES)}
+
+    # ---- the four entry points, same names as the C ABI ----
+
+    def aug_rir_batch(self, geom, rir_len: int, fs: float, c: float, rir_out, tap_count_out=None):
+        import torch
+        n_rir = int(geom.numel() // 10) if geom is not None else 0
+        self._check(self._lib.aug_rir_batch(
+            self._h, n_rir, _ptr(geom, torch.float32), int(rir_len), float(fs), float(c),
+            _ptr(rir_out, torch.float32), _ptr(tap_count_out, torch.int32)))
+
+    def aug_convolve_mix_batch(self, offsets, speech, noise, rir, rir_len: int, snr_db, mixed_out,
+                               gains_out=None, n_noise: Optional[int] = None):
+        import torch
+        off = _host_i64(offsets)
+        if n_noise is None:
+            n_noise = 0 if noise is None else int(noise.shape[0])
+        self._check(self._lib.aug_convolve_mix_batch(
+            self._h, len(off) - 1, off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+            _ptr(speech, torch.float32), int(n_noise), _ptr(noise, torch.float32),
+            _ptr(rir, torch.float32), int(rir_len), _ptr(snr_db, torch.float32),
+            _ptr(mixed_out, torch.float32), _ptr(gains_out, torch.float32)))
+
+    def aug_vtlp_mel_batch(self, offsets, wave, alpha, cfg, frame_offsets, feats_out):
+        import torch
+        off = _host_i64(offsets)
+        foff = _host_i64(frame_offsets)
+        c = cfg if isinstance(cfg, FrontendCfg) else FrontendCfg.of(cfg)
+        self._check(self._lib.aug_vtlp_mel_batch(
+            self._h, len(off) - 1, off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+            _ptr(wave, torch.float32), _ptr(alpha, torch.float32), ctypes.byref(c),
+            foff.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), _ptr(feats_out, torch.float32)))
+
+    def aug_pipeline_batch(self, offsets, speech, noise, geom, rir_len: int, fs: float, c: float,
+                           snr_db, alpha, cfg, frame_offsets, feats_out, rir_out=None,
+                           mixed_out=None, gains_out=None, n_noise: Optional[int] = None):
+        import torch
+        off = _host_i64(offsets)
+        foff = _host_i64(frame_offsets)
+        fc = cfg if isinstance(cfg, FrontendCfg) else FrontendCfg.of(cfg)
+        if n_noise is None:
+            n_noise = 0 if noise is None else int(noise.shape[0])
+        self._check(self._lib.aug_pipeline_batch(
+            self._h, len(off) - 1, off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+            _ptr(speech, torch.float32), int(n_noise), _ptr(noise, torch.float32),
+            _ptr(geom, torch.float32), int(rir_len), float(fs), float(c),
+            _ptr(snr_db, torch.float32), _ptr(alpha, torch.float32), ctypes.byref(fc),
+            foff.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), _ptr(feats_out, torch.float32),
+            _ptr(rir_out, torch.float32), _ptr(mixed_out, torch.float32),
+            _ptr(gains_out, torch.float32)))

@@ -1,0 +1,466 @@
+// C ABI of the augmentation + feature library: argument checks, workspace and
+// work-item tables, and the order in which the kernels of Sec. 2.3's path are enqueued
+// (impulse responses -> their spectra -> overlap-save reverberation with energies ->
+// SNR gains and mixture -> warped power-mel features).  No arithmetic of the method
+// lives here.
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <new>
+#include <cstdio>
+#include <cstring>
+
+#include "aug_internal.h"
+
+namespace aug {
+
+hipError_t DeviceBuffer::reserve(size_t need) {
+    if (need <= bytes) return hipSuccess;
+    if (ptr) {
+        hipError_t e = hipFree(ptr);      // waits for work that may still use it
+        ptr = nullptr;
+        bytes = 0;
+        if (e != hipSuccess) return e;
+    }
+    const size_t want = need + need / 8;  // a little headroom so slowly growing batches do not thrash
+    hipError_t e = hipMalloc(&ptr, want);
+    if (e != hipSuccess) {
+        ptr = nullptr;
+        (void)hipGetLastError();
+        e = hipMalloc(&ptr, need);
+        if (e != hipSuccess) { ptr = nullptr; return e; }
+        bytes = need;
+        return hipSuccess;
+    }
+    bytes = want;
+    return hipSuccess;
+}
+
+void DeviceBuffer::release() {
+    if (ptr) (void)hipFree(ptr);
+    ptr = nullptr;
+    bytes = 0;
+}
+
+}  // namespace aug
+
+namespace {
+
+using aug::DeviceBuffer;
+
+int fail(aug_ctx* ctx, int code, const char* fmt, ...) {
+    if (ctx) {
+        char msg[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(msg, sizeof msg, fmt, ap);
+        va_end(ap);
+        ctx->last_error = msg;
+    }
+    return code;
+}
+
+int fail_hip(aug_ctx* ctx, hipError_t e, const char* what) {
+    (void)hipGetLastError();
+    if (e == hipErrorOutOfMemory) return fail(ctx, AUG_ERR_NOMEM, "%s: out of device memory", what);
+    return fail(ctx, AUG_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define AUG_HIP(expr, what)                                        \
+    do {                                                           \
+        hipError_t e__ = (expr);                                   \
+        if (e__ != hipSuccess) return fail_hip(ctx, e__, what);    \
+    } while (0)
+
+#define AUG_TRY(expr)                                              \
+    do {                                                           \
+        int rc__ = (expr);                                         \
+        if (rc__ != AUG_OK) return rc__;                           \
+    } while (0)
+
+int check_offsets(aug_ctx* ctx, int n_utt, const int64_t* offsets) {
+    if (n_utt < 0) return fail(ctx, AUG_ERR_INVALID_ARG, "n_utt is negative");
+    if (!offsets) return fail(ctx, AUG_ERR_INVALID_ARG, "offsets is null");
+    if (offsets[0] != 0) return fail(ctx, AUG_ERR_INVALID_ARG, "offsets[0] must be 0");
+    for (int u = 0; u < n_utt; ++u)
+        if (offsets[u + 1] < offsets[u])
+            return fail(ctx, AUG_ERR_INVALID_ARG, "offsets not ascending at utterance %d", u);
+    if (offsets[n_utt] > ((int64_t)1 << 40)) return fail(ctx, AUG_ERR_UNSUPPORTED, "packed signal too long");
+    return AUG_OK;
+}
+
+int check_frontend(aug_ctx* ctx, const aug_frontend_cfg* cfg) {
+    if (!cfg) return fail(ctx, AUG_ERR_INVALID_ARG, "front-end config is null");
+    if (!(cfg->fs > 0.f)) return fail(ctx, AUG_ERR_INVALID_ARG, "fs must be positive");
+    if (cfg->win < 2 || cfg->hop < 1) return fail(ctx, AUG_ERR_INVALID_ARG, "win must be >= 2 and hop >= 1");
+    if (cfg->nfft < cfg->win) return fail(ctx, AUG_ERR_INVALID_ARG, "nfft is smaller than win");
+    if (cfg->n_mel < 1 || cfg->n_mel > AUG_MAX_MEL)
+        return fail(ctx, AUG_ERR_INVALID_ARG, "n_mel must be in 1..%d", AUG_MAX_MEL);
+    if (!(cfg->f_lo >= 0.f) || !(cfg->f_hi > cfg->f_lo) || !(cfg->f_hi <= 0.5f * cfg->fs))
+        return fail(ctx, AUG_ERR_INVALID_ARG, "need 0 <= f_lo < f_hi <= fs/2");
+    if (!(cfg->power > 0.f)) return fail(ctx, AUG_ERR_INVALID_ARG, "power must be positive");
+    if (cfg->nfft != 512) return fail(ctx, AUG_ERR_UNSUPPORTED, "kernels are built for nfft = 512");
+    return AUG_OK;
+}
+
+int check_frame_offsets(aug_ctx* ctx, int n_utt, const int64_t* offsets, const int64_t* frame_offsets,
+                        const aug_frontend_cfg* cfg) {
+    if (!frame_offsets) return fail(ctx, AUG_ERR_INVALID_ARG, "frame_offsets is null");
+    if (frame_offsets[0] != 0) return fail(ctx, AUG_ERR_INVALID_ARG, "frame_offsets[0] must be 0");
+    for (int u = 0; u < n_utt; ++u) {
+        const int64_t want = aug_frame_count(offsets[u + 1] - offsets[u], cfg->win, cfg->hop);
+        if (frame_offsets[u + 1] - frame_offsets[u] != want)
+            return fail(ctx, AUG_ERR_INVALID_ARG, "frame_offsets disagrees with the frame count of utterance %d", u);
+    }
+    return AUG_OK;
+}
+
+// Device copies of the offsets and the (utterance, block) / (utterance, frame group) tables.
+// Rebuilt only when the host arrays differ from the cached ones.
+int sync_packing(aug_ctx* ctx, int n_utt, const int64_t* offsets, const int64_t* frame_offsets,
+                 int conv_block, int frames_per_group) {
+    aug::Packing& pk = ctx->packing;
+    const size_t n = (size_t)n_utt + 1;
+    const bool same_off = pk.offsets.size() == n && !memcmp(pk.offsets.data(), offsets, n * sizeof(int64_t));
+    const bool need_conv = conv_block > 0 && !(same_off && pk.conv_block == conv_block);
+    const bool same_fr = !frame_offsets || (same_off && pk.frame_offsets.size() == n &&
+                          !memcmp(pk.frame_offsets.data(), frame_offsets, n * sizeof(int64_t)) &&
+                          pk.frames_per_group == frames_per_group);
+    if (same_off && !need_conv && same_fr) return AUG_OK;
+
+    // earlier work may still read the old tables
+    AUG_HIP(hipStreamSynchronize(ctx->stream), "stream synchronize");
+    if (!same_off) {
+        pk.offsets.assign(offsets, offsets + n);
+        pk.conv_block = 0;
+        pk.frame_offsets.clear();
+        AUG_HIP(ctx->d_offsets.reserve(n * sizeof(int64_t)), "offsets buffer");
+        AUG_HIP(hipMemcpy(ctx->d_offsets.ptr, offsets, n * sizeof(int64_t), hipMemcpyHostToDevice), "offsets copy");
+    }
+    if (conv_block > 0 && pk.conv_block != conv_block) {
+        std::vector<int2> items;
+        for (int u = 0; u < n_utt; ++u) {
+            const int64_t len = offsets[u + 1] - offsets[u];
+            const int64_t nb = (len + conv_block - 1) / conv_block;
+            for (int64_t b = 0; b < nb; ++b) items.push_back(make_int2(u, (int)b));
+        }
+        pk.conv_block = conv_block;
+        pk.n_conv_blocks = (int64_t)items.size();
+        if (!items.empty()) {
+            AUG_HIP(ctx->d_conv_items.reserve(items.size() * sizeof(int2)), "block table");
+            AUG_HIP(hipMemcpy(ctx->d_conv_items.ptr, items.data(), items.size() * sizeof(int2), hipMemcpyHostToDevice),
+                    "block table copy");
+        }
+    }
+    if (frame_offsets && !same_fr) {
+        pk.frame_offsets.assign(frame_offsets, frame_offsets + n);
+        pk.frames_per_group = frames_per_group;
+        std::vector<int2> items;
+        for (int u = 0; u < n_utt; ++u) {
+            const int64_t nf = frame_offsets[u + 1] - frame_offsets[u];
+            for (int64_t f = 0; f < nf; f += frames_per_group) items.push_back(make_int2(u, (int)f));
+        }
+        pk.n_frame_groups = (int64_t)items.size();
+        AUG_HIP(ctx->d_frame_offsets.reserve(n * sizeof(int64_t)), "frame offsets buffer");
+        AUG_HIP(hipMemcpy(ctx->d_frame_offsets.ptr, frame_offsets, n * sizeof(int64_t), hipMemcpyHostToDevice),
+                "frame offsets copy");
+        if (!items.empty()) {
+            AUG_HIP(ctx->d_frame_items.reserve(items.size() * sizeof(int2)), "frame group table");
+            AUG_HIP(hipMemcpy(ctx->d_frame_items.ptr, items.data(), items.size() * sizeof(int2), hipMemcpyHostToDevice),
+                    "frame group table copy");
+        }
+    }
+    return AUG_OK;
+}
+
+int ensure_twiddle(aug_ctx* ctx, int n, const float2** out) {
+    int lg = 0;
+    while ((1 << lg) < n) ++lg;
+    DeviceBuffer& b = ctx->twiddle[lg];
+    if (!b.ptr) {
+        AUG_HIP(b.reserve(sizeof(float2) * (size_t)(n + n / 2 + 1)), "twiddle table");
+        AUG_HIP(aug::launch_twiddle(ctx->stream, n, b.as<float2>()), "twiddle kernel");
+    }
+    *out = b.as<float2>();
+    return AUG_OK;
+}
+
+// Record an event that closes stage `stage` (or opens a timed span when stage < 0).
+int mark(aug_ctx* ctx, int stage) {
+    if (!ctx->profiling) return AUG_OK;
+    hipEvent_t ev;
+    AUG_HIP(hipEventCreate(&ev), "event create");
+    hipError_t e = hipEventRecord(ev, ctx->stream);
+    if (e != hipSuccess) {
+        (void)hipEventDestroy(ev);
+        return fail_hip(ctx, e, "event record");
+    }
+    ctx->marks.emplace_back(ev, stage);
+    return AUG_OK;
+}
+
+// ---- stage drivers: arguments already validated, packing already synchronised ----
+
+int run_rir(aug_ctx* ctx, int n_rir, const float* geom, int rir_len, float fs, float c, float* rir_out,
+            int32_t* tap_count_out) {
+    const double k = (double)fs / (double)c;
+    AUG_TRY(mark(ctx, -1));
+    AUG_HIP(aug::launch_fill_u32(ctx->stream, rir_out, 0u, (int64_t)n_rir * rir_len), "response clear");
+    if (tap_count_out)
+        AUG_HIP(aug::launch_fill_u32(ctx->stream, tap_count_out, 0u, (int64_t)n_rir * rir_len), "count clear");
+    AUG_TRY(mark(ctx, AUG_STAGE_OTHER));
+    AUG_HIP(aug::launch_rir(ctx->stream, n_rir, geom, rir_len, k, rir_out, nullptr), "rir kernel");
+    AUG_TRY(mark(ctx, AUG_STAGE_RIR));
+    if (tap_count_out) {
+        AUG_HIP(aug::launch_rir(ctx->stream, n_rir, geom, rir_len, k, nullptr, tap_count_out), "rir count kernel");
+        AUG_TRY(mark(ctx, AUG_STAGE_OTHER));
+    }
+    return AUG_OK;
+}
+
+int run_convolve_mix(aug_ctx* ctx, int n_utt, int n_noise, const float* speech, const float* noise,
+                     const float* rir, int rir_len, const float* snr_db, float* mixed_out, float* gains_out) {
+    const aug::Packing& pk = ctx->packing;
+    const int64_t total = pk.offsets[n_utt];
+    const int n_src = 1 + n_noise;
+    const int fft_n = aug::conv_fft_size(rir_len);
+    const int n_part = (rir_len + fft_n - 1) / fft_n;
+    const float2* tw = nullptr;
+    AUG_TRY(ensure_twiddle(ctx, fft_n, &tw));
+    if (total == 0 || n_utt == 0) return AUG_OK;
+    int64_t max_len = 0;
+    for (int u = 0; u < n_utt; ++u) max_len = std::max(max_len, pk.offsets[u + 1] - pk.offsets[u]);
+
+    AUG_HIP(ctx->rir_spec.reserve(sizeof(float2) * (size_t)n_utt * n_src * n_part * (fft_n + 1)), "spectrum workspace");
+    AUG_HIP(ctx->reverb.reserve(sizeof(float) * (size_t)n_src * total), "reverberation workspace");
+    AUG_HIP(ctx->energy.reserve(sizeof(double) * (size_t)n_utt * n_src), "energy workspace");
+
+    AUG_TRY(mark(ctx, -1));
+    AUG_HIP(aug::launch_fill_u32(ctx->stream, ctx->energy.ptr, 0u, (int64_t)n_utt * n_src * 2), "energy clear");
+    AUG_TRY(mark(ctx, AUG_STAGE_OTHER));
+    AUG_HIP(aug::launch_rir_spectrum(ctx->stream, n_utt * n_src, rir, rir_len, fft_n, tw, ctx->rir_spec.as<float2>()),
+            "spectrum kernel");
+    AUG_TRY(mark(ctx, AUG_STAGE_RIR_SPECTRUM));
+    aug::ConvArgs ca;
+    ca.offsets = ctx->d_offsets.as<int64_t>();
+    ca.items = ctx->d_conv_items.as<int2>();
+    ca.n_items = pk.n_conv_blocks;
+    ca.n_src = n_src;
+    ca.speech = speech;
+    ca.noise = noise;
+    ca.total = total;
+    ca.spec = ctx->rir_spec.as<float2>();
+    ca.n_part = n_part;
+    ca.reverb = ctx->reverb.as<float>();
+    ca.energy = ctx->energy.as<double>();
+    AUG_HIP(aug::launch_convolve(ctx->stream, fft_n, tw, ca), "convolution kernel");
+    AUG_TRY(mark(ctx, AUG_STAGE_CONVOLVE));
+    AUG_HIP(aug::launch_mix(ctx->stream, n_utt, ctx->d_offsets.as<int64_t>(), total, n_src, ctx->reverb.as<float>(),
+                            ctx->energy.as<double>(), snr_db, mixed_out, gains_out, max_len),
+            "mix kernel");
+    AUG_TRY(mark(ctx, AUG_STAGE_MIX));
+    return AUG_OK;
+}
+
+int run_mel(aug_ctx* ctx, int n_utt, const float* wave, const float* alpha, const aug_frontend_cfg* cfg,
+            float* feats_out) {
+    const aug::Packing& pk = ctx->packing;
+    if (n_utt == 0 || pk.n_frame_groups == 0) return AUG_OK;
+    const float2* tw = nullptr;
+    AUG_TRY(ensure_twiddle(ctx, cfg->nfft / 2, &tw));
+    if (ctx->window_n != cfg->win) {
+        AUG_HIP(ctx->window.reserve(sizeof(float) * (size_t)cfg->win), "window table");
+        AUG_HIP(aug::launch_window(ctx->stream, cfg->win, ctx->window.as<float>()), "window kernel");
+        ctx->window_n = cfg->win;
+    }
+    AUG_HIP(ctx->mel_tab.reserve(sizeof(float2) * (size_t)n_utt * (cfg->nfft / 2 + 1)), "mel table");
+    AUG_TRY(mark(ctx, -1));
+    AUG_HIP(aug::launch_mel_table(ctx->stream, n_utt, alpha, *cfg, ctx->mel_tab.as<float2>()), "mel table kernel");
+    aug::MelArgs ma;
+    ma.offsets = ctx->d_offsets.as<int64_t>();
+    ma.frame_offsets = ctx->d_frame_offsets.as<int64_t>();
+    ma.items = ctx->d_frame_items.as<int2>();
+    ma.n_items = pk.n_frame_groups;
+    ma.frames_per_group = pk.frames_per_group;
+    ma.wave = wave;
+    ma.mel_tab = ctx->mel_tab.as<float2>();
+    ma.window = ctx->window.as<float>();
+    ma.twiddle = tw;
+    ma.cfg = *cfg;
+    ma.feats = feats_out;
+    AUG_HIP(aug::launch_mel(ctx->stream, ma), "mel kernel");
+    AUG_TRY(mark(ctx, AUG_STAGE_MEL));
+    return AUG_OK;
+}
+
+int check_rir_args(aug_ctx* ctx, int rir_len, float fs, float c) {
+    if (rir_len < 1 || rir_len > AUG_MAX_RIR_LEN)
+        return fail(ctx, rir_len < 1 ? AUG_ERR_INVALID_ARG : AUG_ERR_UNSUPPORTED,
+                    "rir_len must be in 1..%d", AUG_MAX_RIR_LEN);
+    if (!(fs > 0.f) || !(c > 0.f)) return fail(ctx, AUG_ERR_INVALID_ARG, "fs and c must be positive");
+    return AUG_OK;
+}
+
+int check_mix_args(aug_ctx* ctx, int n_noise, const void* speech, const void* noise, const void* snr_db) {
+    if (n_noise < 0 || n_noise > AUG_MAX_NOISE)
+        return fail(ctx, AUG_ERR_INVALID_ARG, "n_noise must be in 0..%d", AUG_MAX_NOISE);
+    if (!speech) return fail(ctx, AUG_ERR_INVALID_ARG, "speech is null");
+    if (n_noise > 0 && (!noise || !snr_db)) return fail(ctx, AUG_ERR_INVALID_ARG, "noise or snr_db is null");
+    return AUG_OK;
+}
+
+int enter(aug_ctx* ctx) {
+    if (!ctx) return AUG_ERR_INVALID_ARG;
+    ctx->last_error.clear();
+    AUG_HIP(hipSetDevice(ctx->device), "set device");
+    return AUG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int aug_create(aug_ctx** out, int device_id, void* hip_stream) {
+    if (!out) return AUG_ERR_INVALID_ARG;
+    *out = nullptr;
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) != hipSuccess || device_id < 0 || device_id >= n_dev) {
+        (void)hipGetLastError();
+        return AUG_ERR_INVALID_ARG;
+    }
+    if (hipSetDevice(device_id) != hipSuccess) {
+        (void)hipGetLastError();
+        return AUG_ERR_HIP;
+    }
+    aug_ctx* ctx = new (std::nothrow) aug_ctx();
+    if (!ctx) return AUG_ERR_NOMEM;
+    ctx->device = device_id;
+    ctx->stream = static_cast<hipStream_t>(hip_stream);
+    *out = ctx;
+    return AUG_OK;
+}
+
+int aug_destroy(aug_ctx* ctx) {
+    if (!ctx) return AUG_OK;
+    int rc = AUG_OK;
+    if (hipSetDevice(ctx->device) != hipSuccess || hipStreamSynchronize(ctx->stream) != hipSuccess) {
+        (void)hipGetLastError();
+        rc = AUG_ERR_HIP;
+    }
+    DeviceBuffer* bufs[] = {&ctx->d_offsets, &ctx->d_frame_offsets, &ctx->d_conv_items, &ctx->d_frame_items,
+                            &ctx->rir, &ctx->rir_spec, &ctx->reverb, &ctx->energy, &ctx->mixed, &ctx->mel_tab,
+                            &ctx->window};
+    for (DeviceBuffer* b : bufs) b->release();
+    for (DeviceBuffer& b : ctx->twiddle) b.release();
+    for (auto& m : ctx->marks) (void)hipEventDestroy(m.first);
+    delete ctx;
+    return rc;
+}
+
+const char* aug_last_error(const aug_ctx* ctx) { return ctx ? ctx->last_error.c_str() : "context is null"; }
+
+int64_t aug_frame_count(int64_t n_samples, int win, int hop) {
+    if (win <= 0 || hop <= 0) return -1;
+    return n_samples < win ? 0 : 1 + (n_samples - win) / hop;
+}
+
+int aug_profile_enable(aug_ctx* ctx, int on) {
+    AUG_TRY(enter(ctx));
+    ctx->profiling = on != 0;
+    return AUG_OK;
+}
+
+int aug_profile_read(aug_ctx* ctx, float* ms_out, int32_t* launches_out) {
+    AUG_TRY(enter(ctx));
+    if (!ms_out) return fail(ctx, AUG_ERR_INVALID_ARG, "ms_out is null");
+    for (int i = 0; i < AUG_N_STAGES; ++i) {
+        ms_out[i] = 0.f;
+        if (launches_out) launches_out[i] = 0;
+    }
+    AUG_HIP(hipStreamSynchronize(ctx->stream), "stream synchronize");
+    int rc = AUG_OK;
+    for (size_t i = 1; i < ctx->marks.size(); ++i) {
+        const int stage = ctx->marks[i].second;
+        if (stage < 0 || stage >= AUG_N_STAGES) continue;
+        float ms = 0.f;
+        hipError_t e = hipEventElapsedTime(&ms, ctx->marks[i - 1].first, ctx->marks[i].first);
+        if (e != hipSuccess) { rc = fail_hip(ctx, e, "event elapsed time"); break; }
+        ms_out[stage] += ms;
+        if (launches_out) launches_out[stage] += 1;
+    }
+    for (auto& m : ctx->marks) (void)hipEventDestroy(m.first);
+    ctx->marks.clear();
+    return rc;
+}
+
+int aug_rir_batch(aug_ctx* ctx, int n_rir, const float* geom, int rir_len, float fs, float c,
+                  float* rir_out, int32_t* tap_count_out) {
+    AUG_TRY(enter(ctx));
+    if (n_rir < 0) return fail(ctx, AUG_ERR_INVALID_ARG, "n_rir is negative");
+    AUG_TRY(check_rir_args(ctx, rir_len, fs, c));
+    if (n_rir == 0) return AUG_OK;
+    if (!geom || !rir_out) return fail(ctx, AUG_ERR_INVALID_ARG, "geom or rir_out is null");
+    if ((int64_t)n_rir * 64 > 0x7fffffffLL) return fail(ctx, AUG_ERR_UNSUPPORTED, "too many responses in one call");
+    return run_rir(ctx, n_rir, geom, rir_len, fs, c, rir_out, tap_count_out);
+}
+
+int aug_convolve_mix_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, const float* speech, int n_noise,
+                           const float* noise, const float* rir, int rir_len, const float* snr_db,
+                           float* mixed_out, float* gains_out) {
+    AUG_TRY(enter(ctx));
+    AUG_TRY(check_offsets(ctx, n_utt, offsets));
+    AUG_TRY(check_mix_args(ctx, n_noise, speech, noise, snr_db));
+    if (rir_len < 1 || rir_len > AUG_MAX_RIR_LEN)
+        return fail(ctx, rir_len < 1 ? AUG_ERR_INVALID_ARG : AUG_ERR_UNSUPPORTED,
+                    "rir_len must be in 1..%d", AUG_MAX_RIR_LEN);
+    if (!rir || !mixed_out) return fail(ctx, AUG_ERR_INVALID_ARG, "rir or mixed_out is null");
+    AUG_TRY(sync_packing(ctx, n_utt, offsets, nullptr, aug::conv_fft_size(rir_len), 0));
+    return run_convolve_mix(ctx, n_utt, n_noise, speech, noise, rir, rir_len, snr_db, mixed_out, gains_out);
+}
+
+int aug_vtlp_mel_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, const float* wave, const float* alpha,
+                       const aug_frontend_cfg* cfg, const int64_t* frame_offsets, float* feats_out) {
+    AUG_TRY(enter(ctx));
+    AUG_TRY(check_offsets(ctx, n_utt, offsets));
+    AUG_TRY(check_frontend(ctx, cfg));
+    AUG_TRY(check_frame_offsets(ctx, n_utt, offsets, frame_offsets, cfg));
+    if (!wave || !alpha || !feats_out) return fail(ctx, AUG_ERR_INVALID_ARG, "wave, alpha or feats_out is null");
+    AUG_TRY(sync_packing(ctx, n_utt, offsets, frame_offsets, 0, aug::mel_frames_per_group()));
+    return run_mel(ctx, n_utt, wave, alpha, cfg, feats_out);
+}
+
+int aug_pipeline_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, const float* speech, int n_noise,
+                       const float* noise, const float* geom, int rir_len, float fs, float c,
+                       const float* snr_db, const float* alpha, const aug_frontend_cfg* cfg,
+                       const int64_t* frame_offsets, float* feats_out, float* rir_out, float* mixed_out,
+                       float* gains_out) {
+    AUG_TRY(enter(ctx));
+    AUG_TRY(check_offsets(ctx, n_utt, offsets));
+    AUG_TRY(check_mix_args(ctx, n_noise, speech, noise, snr_db));
+    AUG_TRY(check_rir_args(ctx, rir_len, fs, c));
+    AUG_TRY(check_frontend(ctx, cfg));
+    AUG_TRY(check_frame_offsets(ctx, n_utt, offsets, frame_offsets, cfg));
+    if (!geom || !alpha || !feats_out) return fail(ctx, AUG_ERR_INVALID_ARG, "geom, alpha or feats_out is null");
+    const int n_src = 1 + n_noise;
+    if ((int64_t)n_utt * n_src * 64 > 0x7fffffffLL)
+        return fail(ctx, AUG_ERR_UNSUPPORTED, "too many responses in one call");
+    AUG_TRY(sync_packing(ctx, n_utt, offsets, frame_offsets, aug::conv_fft_size(rir_len),
+                         aug::mel_frames_per_group()));
+    const int64_t total = offsets[n_utt];
+    float* rir = rir_out;
+    if (!rir) {
+        AUG_HIP(ctx->rir.reserve(sizeof(float) * (size_t)n_utt * n_src * rir_len), "response workspace");
+        rir = ctx->rir.as<float>();
+    }
+    float* mixed = mixed_out;
+    if (!mixed) {
+        AUG_HIP(ctx->mixed.reserve(sizeof(float) * (size_t)std::max<int64_t>(total, 1)), "mixture workspace");
+        mixed = ctx->mixed.as<float>();
+    }
+    AUG_TRY(run_rir(ctx, n_utt * n_src, geom, rir_len, fs, c, rir, nullptr));
+    AUG_TRY(run_convolve_mix(ctx, n_utt, n_noise, speech, noise, rir, rir_len, snr_db, mixed, gains_out));
+    return run_mel(ctx, n_utt, mixed, alpha, cfg, feats_out);
+}
+
+}  // extern "C"

@@ -1,0 +1,133 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <utility>
+#include <vector>
+
+#include "aug.h"
+
+namespace aug {
+
+// A grow-only device buffer owned by the context.
+struct DeviceBuffer {
+    void* ptr = nullptr;
+    size_t bytes = 0;
+    hipError_t reserve(size_t need);
+    void release();
+    template <class T> T* as() const { return static_cast<T*>(ptr); }
+};
+
+// Host-side description of how the packed utterances are cut into work items;
+// rebuilt only when the offsets of a call differ from the cached ones.
+struct Packing {
+    std::vector<int64_t> offsets;        // n_utt + 1
+    std::vector<int64_t> frame_offsets;  // n_utt + 1 (empty if not a front-end call)
+    int conv_block = 0;                  // output samples per convolution block the tables were built for
+    int frames_per_group = 0;            // frames per front-end work group the tables were built for
+    int64_t n_conv_blocks = 0;           // sum over utterances of ceil(len / conv_block)
+    int64_t n_frame_groups = 0;
+};
+
+}  // namespace aug
+
+struct aug_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    std::string last_error;
+
+    // device copies of the host offset arrays and the work-item tables derived from them
+    aug::Packing packing;
+    aug::DeviceBuffer d_offsets;         // int64 [n_utt+1]
+    aug::DeviceBuffer d_frame_offsets;   // int64 [n_utt+1]
+    aug::DeviceBuffer d_conv_items;      // int2 [n_conv_blocks]: (utterance, block)
+    aug::DeviceBuffer d_frame_items;     // int2 [n_frame_groups]: (utterance, first frame)
+
+    // intermediate results
+    aug::DeviceBuffer rir;               // float [n_rir][rir_len]            (pipeline only)
+    aug::DeviceBuffer rir_spec;          // float2 [n_rir][n_part][P+1]
+    aug::DeviceBuffer reverb;            // float [1+n_noise][total]
+    aug::DeviceBuffer energy;            // double [n_utt][1+n_noise]
+    aug::DeviceBuffer mixed;             // float [total]                     (pipeline only)
+    aug::DeviceBuffer mel_tab;           // float2 [n_utt][nfft/2+1]: (channel, weight) per bin
+    aug::DeviceBuffer twiddle[16];       // per log2(n): float2 [n + n/2 + 1] FFT twiddles
+    aug::DeviceBuffer window;            // float [win]
+    int window_n = 0;
+
+    // stage timing: events recorded in stream order, each tagged with the stage it ends (-1 = a start mark)
+    bool profiling = false;
+    std::vector<std::pair<hipEvent_t, int>> marks;
+};
+
+namespace aug {
+
+// ---- kernels' host launchers (each checks nothing; arguments are validated by the API layer) ----
+
+// Image-method impulse responses into rir_out float [n_rir][rir_len] and/or tap counts into
+// cnt_out int32 [n_rir][rir_len] (either may be null); both must be zero on entry.
+hipError_t launch_rir(hipStream_t s, int n_rir, const float* geom, int rir_len, double fs_over_c,
+                      float* rir_out, int32_t* cnt_out);
+
+// Largest complex FFT size the convolution kernels are built for, and the size chosen for a response length.
+int conv_fft_size(int rir_len);
+
+// Spectra of the zero-padded partitions of each response: spec float2 [n_rir][n_part][P+1], P = fft_n.
+hipError_t launch_rir_spectrum(hipStream_t s, int n_rir, const float* rir, int rir_len, int fft_n,
+                               const float2* twiddle, float2* spec);
+
+// Overlap-save convolution of every (utterance, source) with its response; adds the block's energy
+// to energy[u][j] (double, must be zero on entry).  src_base[j] points at source j's packed signal.
+struct ConvArgs {
+    const int64_t* offsets;      // device
+    const int2* items;           // device (utterance, block)
+    int64_t n_items;
+    int n_src;
+    const float* speech;
+    const float* noise;          // [n_src-1][total]
+    int64_t total;
+    const float2* spec;          // [n_utt][n_src][n_part][P+1]
+    int n_part;
+    float* reverb;               // [n_src][total]
+    double* energy;              // [n_utt][n_src]
+};
+hipError_t launch_convolve(hipStream_t s, int fft_n, const float2* twiddle, const ConvArgs& a);
+
+// mixed = y_0 + sum_j g_j y_j with g_j from the energies; writes gains if asked.
+hipError_t launch_mix(hipStream_t s, int n_utt, const int64_t* d_offsets, int64_t total, int n_src,
+                      const float* reverb, const double* energy, const float* snr_db,
+                      float* mixed_out, float* gains_out, int64_t max_len);
+
+// Per-utterance (channel, weight) table of the warped mel bank: tab float2 [n_utt][nfft/2+1].
+hipError_t launch_mel_table(hipStream_t s, int n_utt, const float* alpha, const aug_frontend_cfg& cfg,
+                            float2* tab);
+
+// Hamming window, float [win].
+hipError_t launch_window(hipStream_t s, int win, float* w);
+
+// tw[t] = exp(-2 pi i t / n), t < n, then tw[n + k] = exp(-i pi k / n), k <= n/2; fp64 rounded once.
+hipError_t launch_twiddle(hipStream_t s, int n, float2* tw);
+
+// STFT power -> warped mel -> power law.
+struct MelArgs {
+    const int64_t* offsets;        // device
+    const int64_t* frame_offsets;  // device
+    const int2* items;             // device (utterance, first frame of the group)
+    int64_t n_items;
+    int frames_per_group;
+    const float* wave;
+    const float2* mel_tab;
+    const float* window;
+    const float2* twiddle;         // table for the nfft/2-point complex transform
+    aug_frontend_cfg cfg;
+    float* feats;
+};
+int mel_frames_per_group();
+hipError_t launch_mel(hipStream_t s, const MelArgs& a);
+
+// fill n 32-bit words with a value (used instead of memset so that calls stay graph-capturable)
+hipError_t launch_fill_u32(hipStream_t s, void* p, uint32_t v, int64_t n);
+
+}  // namespace aug

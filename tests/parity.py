@@ -1,0 +1,65 @@
+"""Comparators and device helpers shared by the GPU parity tests."""
+import numpy as np
+
+WAVE_TOL = 1e-4      # max-abs error <= WAVE_TOL * RMS of the oracle signal, per utterance
+FEAT_TOL = 1e-3      # relative error of features, denominators floored at 1e-3 * RMS
+RIR_TOL = 1e-5       # relative error of summed tap amplitudes
+GAIN_TOL = 1e-4      # relative error of SNR gains
+
+
+def wave_err(got, ref, offsets):
+    """Largest per-utterance max|got - ref| / RMS(ref)."""
+    worst = 0.0
+    for u in range(len(offsets) - 1):
+        a, b = int(offsets[u]), int(offsets[u + 1])
+        if b == a:
+            continue
+        rms = np.sqrt(np.mean(ref[a:b] ** 2))
+        err = np.max(np.abs(got[a:b].astype(np.float64) - ref[a:b]))
+        worst = max(worst, err / rms if rms > 0 else (0.0 if err == 0 else np.inf))
+    return worst
+
+
+def feat_err(got, ref):
+    """max |got - ref| / max(|ref|, 1e-3 RMS(ref))."""
+    if ref.size == 0:
+        return 0.0
+    rms = np.sqrt(np.mean(ref ** 2))
+    den = np.maximum(np.abs(ref), 1e-3 * rms)
+    den = np.where(den > 0, den, 1.0)
+    return float(np.max(np.abs(got.astype(np.float64) - ref) / den))
+
+
+def rir_err(got, ref):
+    """max |got - ref| / max(|ref|, 1e-6 max|ref|) over taps (all amplitudes are >= 0)."""
+    den = np.maximum(np.abs(ref), 1e-6 * np.max(np.abs(ref)) if ref.size else 1.0)
+    den = np.where(den > 0, den, 1.0)
+    return float(np.max(np.abs(got.astype(np.float64) - ref) / den)) if ref.size else 0.0
+
+
+def dev(a, dtype=None):
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+class DeviceWorkload:
+    """A workload's arrays resident on the GPU."""
+
+    def __init__(self, w):
+        import torch
+        self.w = w
+        self.speech = dev(w.speech)
+        self.noise = None if w.noise is None else dev(w.noise)
+        self.geom = None if w.geom is None else dev(w.geom)
+        self.snr_db = None if w.snr_db is None else dev(w.snr_db)
+        self.alpha = dev(w.alpha)
+        self.frame_offsets = w.frame_offsets()
+        self.n_frames = int(self.frame_offsets[-1])
+        self.torch = torch
+
+    def empty_feats(self):
+        return self.torch.full((self.n_frames, self.w.frontend.n_mel), float("nan"),
+                               dtype=self.torch.float32, device="cuda")

@@ -1,0 +1,63 @@
+"""The C-ABI library builds, loads and exports what include/aug.h declares.  CPU only:
+no kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1912_11040_amd import binding, build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
+    return binding.load_library()
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "aug.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(aug_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_four_entry_points():
+    names = _declared()
+    for n in ("aug_rir_batch", "aug_convolve_mix_batch", "aug_vtlp_mel_batch", "aug_pipeline_batch",
+              "aug_create", "aug_destroy", "aug_last_error", "aug_frame_count"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in _declared():
+        assert hasattr(lib, name), name
+    assert sorted(binding.EXPORTS) == _declared()
+
+
+def test_frame_count_helper(lib):
+    assert binding.aug_frame_count(16000, 400, 160) == 98
+    assert binding.aug_frame_count(399, 400, 160) == 0
+    assert binding.aug_frame_count(400, 400, 160) == 1
+    assert binding.aug_frame_count(100, 0, 160) == -1
+
+
+def test_frontend_struct_matches_header():
+    assert ctypes.sizeof(binding.FrontendCfg) == 32
+    assert [f[0] for f in binding.FrontendCfg._fields_] == \
+        ["fs", "win", "hop", "nfft", "n_mel", "f_lo", "f_hi", "power"]
+
+
+def test_null_context_is_rejected(lib):
+    assert lib.aug_rir_batch(None, 1, None, 16, 16000.0, 343.0, None, None) == binding.AUG_ERR_INVALID_ARG
+    assert lib.aug_destroy(None) == binding.AUG_OK
+    assert lib.aug_last_error(None) == b"context is null"
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "libaug.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        binding.load_library()

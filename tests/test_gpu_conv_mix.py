@@ -1,0 +1,139 @@
+"""aug_convolve_mix_batch against the oracle's direct convolution and SNR mix."""
+import numpy as np
+import pytest
+
+from oracle import aug_oracle as O
+from paper_1912_11040_amd import workloads as W
+from tests.parity import GAIN_TOL, WAVE_TOL, dev, wave_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def aug():
+    from paper_1912_11040_amd.binding import Augmenter
+    a = Augmenter(0)
+    yield a
+    a.close()
+
+
+def _decaying_rirs(rng, n_utt, n_src, L):
+    t = np.arange(L)
+    h = rng.standard_normal((n_utt, n_src, L)) * np.exp(-t / (0.25 * L + 1.0))
+    h[:, :, : min(8, L)] += 1.0
+    return h.astype(np.float32)
+
+
+def _run(aug, offsets, speech, noise, rir, snr):
+    import torch
+    n_utt = len(offsets) - 1
+    n_noise = 0 if noise is None else noise.shape[0]
+    mixed = torch.full((int(offsets[-1]),), float("nan"), dtype=torch.float32, device="cuda")
+    gains = torch.full((n_utt, max(n_noise, 1)), float("nan"), dtype=torch.float32, device="cuda")
+    aug.aug_convolve_mix_batch(offsets, dev(speech), None if noise is None else dev(noise), dev(rir),
+                               rir.shape[-1], None if snr is None else dev(snr), mixed,
+                               gains if n_noise else None)
+    torch.cuda.synchronize()
+    return mixed.cpu().numpy(), gains.cpu().numpy()[:, :n_noise]
+
+
+def _check(aug, offsets, speech, noise, rir, snr, method="direct"):
+    mixed, gains = _run(aug, offsets, speech, noise, rir, snr)
+    ref, g_ref = O.convolve_mix_batch(offsets, speech, noise, rir.astype(np.float64), snr, method)
+    assert not np.isnan(mixed).any()
+    assert wave_err(mixed, ref, offsets) <= WAVE_TOL
+    if g_ref.size:
+        np.testing.assert_allclose(gains, g_ref, rtol=GAIN_TOL)
+    return mixed, ref
+
+
+def test_tiny_config_with_oracle_rirs(aug):
+    w = W.tiny()
+    h, _ = O.rir_batch(w.geom.reshape(-1, 10), w.rir_len, w.fs, w.c)
+    rir = h.reshape(w.n_utt, 2, w.rir_len).astype(np.float32)
+    print("case: tiny, L=4096, direct oracle", flush=True)
+    _check(aug, w.offsets, w.speech, w.noise, rir, w.snr_db)
+
+
+def test_delta_response_is_a_shift(aug):
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal(3000).astype(np.float32)
+    rir = np.zeros((1, 1, 300), np.float32)
+    rir[0, 0, 123] = 1.0
+    mixed, _ = _run(aug, np.array([0, 3000]), x, None, rir, None)
+    np.testing.assert_allclose(mixed[123:], x[:-123], atol=2e-6)
+    np.testing.assert_allclose(mixed[:123], 0.0, atol=2e-6)
+
+
+@pytest.mark.parametrize("L", [1, 17, 256, 700, 8000])
+def test_ragged_lengths_and_response_sizes(aug, L):
+    rng = np.random.default_rng(L)
+    lens = [0, 1, 399, 5000, 0, 16384, 16385, 777]
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    total = int(offsets[-1])
+    speech = rng.standard_normal(total).astype(np.float32)
+    noise = rng.standard_normal((2, total)).astype(np.float32)
+    rir = _decaying_rirs(rng, len(lens), 3, L)
+    snr = rng.uniform(0, 30, (len(lens), 2)).astype(np.float32)
+    print(f"case: ragged lens, L={L}", flush=True)
+    _check(aug, offsets, speech, noise, rir, snr)
+
+
+def test_partitioned_response_32768_taps(aug):
+    # responses longer than one LDS-resident transform are cut into partitions
+    rng = np.random.default_rng(7)
+    lens = [40000, 9000, 70001]
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    total = int(offsets[-1])
+    speech = rng.standard_normal(total).astype(np.float32)
+    noise = rng.standard_normal((1, total)).astype(np.float32)
+    rir = _decaying_rirs(rng, 3, 2, 32768)
+    snr = np.array([[5.0], [0.0], [17.0]], np.float32)
+    print("case: L=32768 partitioned, fft oracle + sampled direct sums", flush=True)
+    mixed, ref = _check(aug, offsets, speech, noise, rir, snr, method="fft")
+    # the fft oracle itself is tied to the direct sum at sampled positions of the speech path
+    y_gpu, _ = _run(aug, offsets, speech, None, rir[:, :1], None)
+    for u in range(3):
+        a, b = offsets[u], offsets[u + 1]
+        pos = rng.integers(0, b - a, 48)
+        direct = O.convolve_at(speech[a:b], rir[u, 0], pos)
+        rms = np.sqrt(np.mean(O.convolve_fft(speech[a:b], rir[u, 0]) ** 2))
+        assert np.max(np.abs(y_gpu[a:b][pos] - direct)) <= WAVE_TOL * rms
+
+
+def test_three_noise_sources_16000_taps(aug):
+    rng = np.random.default_rng(11)
+    lens = [20000, 33000]
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    total = int(offsets[-1])
+    speech = rng.standard_normal(total).astype(np.float32)
+    noise = rng.standard_normal((3, total)).astype(np.float32)
+    rir = _decaying_rirs(rng, 2, 4, 16000)
+    snr = rng.uniform(0, 30, (2, 3)).astype(np.float32)
+    print("case: L=16000, 3 noises, direct oracle", flush=True)
+    _check(aug, offsets, speech, noise, rir, snr)
+
+
+def test_silent_noise_gets_zero_gain(aug):
+    rng = np.random.default_rng(3)
+    offsets = np.array([0, 2000], np.int64)
+    speech = rng.standard_normal(2000).astype(np.float32)
+    noise = np.zeros((1, 2000), np.float32)
+    rir = _decaying_rirs(rng, 1, 2, 64)
+    mixed, gains = _run(aug, offsets, speech, noise, rir, np.array([[10.0]], np.float32))
+    assert gains[0, 0] == 0.0
+    ref = O.convolve_direct(speech, rir[0, 0])
+    assert wave_err(mixed, ref, offsets) <= WAVE_TOL
+
+
+def test_measured_snr_equals_target(aug):
+    rng = np.random.default_rng(5)
+    offsets = np.array([0, 30000], np.int64)
+    speech = rng.standard_normal(30000).astype(np.float32)
+    noise = 4.0 * rng.standard_normal((1, 30000)).astype(np.float32)
+    rir = _decaying_rirs(rng, 1, 2, 1000)
+    snr = np.array([[7.5]], np.float32)
+    mixed, gains = _run(aug, offsets, speech, noise, rir, snr)
+    y = O.reverberate(offsets, speech, noise, rir.astype(np.float64))
+    got = 10 * np.log10(np.sum(y[0] ** 2) / np.sum((gains[0, 0] * y[1]) ** 2))
+    assert got == pytest.approx(7.5, abs=1e-3)

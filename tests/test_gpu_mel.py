@@ -1,0 +1,93 @@
+"""aug_vtlp_mel_batch against the oracle's DFT-matrix front end."""
+import numpy as np
+import pytest
+
+from oracle import aug_oracle as O
+from paper_1912_11040_amd import workloads as W
+from tests.parity import FEAT_TOL, DeviceWorkload, dev, feat_err
+
+pytestmark = pytest.mark.gpu
+FE = W.FrontendConfig()
+
+
+@pytest.fixture(scope="module")
+def aug():
+    from paper_1912_11040_amd.binding import Augmenter
+    a = Augmenter(0)
+    yield a
+    a.close()
+
+
+def _run(aug, offsets, wave, alpha, fe=FE):
+    import torch
+    n = np.diff(offsets)
+    t = np.where(n >= fe.win, 1 + (n - fe.win) // fe.hop, 0)
+    foff = np.concatenate([[0], np.cumsum(t)]).astype(np.int64)
+    feats = torch.full((int(foff[-1]), fe.n_mel), float("nan"), dtype=torch.float32, device="cuda")
+    aug.aug_vtlp_mel_batch(offsets, dev(wave), dev(alpha), fe, foff, feats)
+    torch.cuda.synchronize()
+    return feats.cpu().numpy()
+
+
+def test_tiny_speech(aug):
+    w = W.tiny()
+    print("case: tiny speech, 8 x 98 frames", flush=True)
+    f = _run(aug, w.offsets, w.speech, w.alpha)
+    ref = O.vtlp_mel_batch(w.offsets, w.speech, w.alpha, FE)
+    assert f.shape == ref.shape == (784, 40)
+    assert feat_err(f, ref) <= FEAT_TOL
+
+
+def test_features_config_subset(aug):
+    w = W.features_only(n_utt=12, seconds=8.0)
+    print("case: features-only, 12 x 798 frames", flush=True)
+    f = _run(aug, w.offsets, w.speech, w.alpha)
+    ref = O.vtlp_mel_batch(w.offsets, w.speech, w.alpha, FE)
+    assert feat_err(f, ref) <= FEAT_TOL
+
+
+def test_ragged_short_and_empty_utterances(aug):
+    rng = np.random.default_rng(0)
+    lens = [0, 399, 400, 559, 560, 12345, 1, 400 + 160 * 63, 400 + 160 * 64, 400 + 160 * 65]
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    x = rng.standard_normal(int(offsets[-1])).astype(np.float32)
+    alpha = rng.uniform(0.8, 1.2, len(lens)).astype(np.float32)
+    print("case: ragged lengths", flush=True)
+    f = _run(aug, offsets, x, alpha)
+    ref = O.vtlp_mel_batch(offsets, x, alpha, FE)
+    assert f.shape == ref.shape
+    assert not np.isnan(f).any()
+    assert feat_err(f, ref) <= FEAT_TOL
+
+
+@pytest.mark.parametrize("alpha", [0.8, 1.0, 1.2])
+def test_pure_tone_and_alpha_extremes(aug, alpha):
+    x = np.cos(2 * np.pi * 64 * np.arange(4000) / 512).astype(np.float32)
+    offsets = np.array([0, 4000], np.int64)
+    a = np.array([alpha], np.float32)
+    f = _run(aug, offsets, x, a)
+    ref = O.vtlp_mel_batch(offsets, x, a, FE)
+    assert feat_err(f, ref) <= FEAT_TOL
+    assert (np.argmax(f, axis=1) == np.argmax(ref, axis=1)).all()
+
+
+def test_silence_gives_zero_and_loud_input_is_not_clipped(aug):
+    offsets = np.array([0, 2000, 4000], np.int64)
+    rng = np.random.default_rng(1)
+    x = np.concatenate([np.zeros(2000), 3e4 * rng.standard_normal(2000)]).astype(np.float32)
+    a = np.array([0.9, 1.1], np.float32)
+    f = _run(aug, offsets, x, a)
+    ref = O.vtlp_mel_batch(offsets, x, a, FE)
+    np.testing.assert_array_equal(f[:11], 0.0)
+    assert f.max() > 3.0
+    assert feat_err(f, ref) <= FEAT_TOL
+
+
+def test_other_mel_counts_and_band(aug):
+    import dataclasses
+    fe = dataclasses.replace(FE, n_mel=23, f_lo=100.0, f_hi=7000.0, power=0.1)
+    w = W.tiny(n_utt=2)
+    f = _run(aug, w.offsets, w.speech, w.alpha, fe)
+    ref = O.vtlp_mel_batch(w.offsets, w.speech, w.alpha, fe)
+    assert f.shape == ref.shape == (196, 23)
+    assert feat_err(f, ref) <= FEAT_TOL

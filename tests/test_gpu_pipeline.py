@@ -1,0 +1,103 @@
+"""aug_pipeline_batch (the fused path) against the oracle, small and sampled-at-scale."""
+import numpy as np
+import pytest
+
+from oracle import aug_oracle as O
+from paper_1912_11040_amd import workloads as W
+from tests.parity import FEAT_TOL, GAIN_TOL, RIR_TOL, WAVE_TOL, DeviceWorkload, feat_err, rir_err, wave_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def aug():
+    from paper_1912_11040_amd.binding import Augmenter
+    a = Augmenter(0)
+    yield a
+    a.close()
+
+
+def _run(aug, w, want_rir=True, want_mixed=True):
+    import torch
+    d = DeviceWorkload(w)
+    feats = d.empty_feats()
+    n_src = 1 + w.n_noise
+    rir = torch.full((w.n_utt, n_src, w.rir_len), float("nan"), dtype=torch.float32, device="cuda") \
+        if want_rir else None
+    mixed = torch.full((w.total,), float("nan"), dtype=torch.float32, device="cuda") if want_mixed else None
+    gains = torch.full((w.n_utt, max(w.n_noise, 1)), float("nan"), dtype=torch.float32, device="cuda")
+    aug.aug_pipeline_batch(w.offsets, d.speech, d.noise, d.geom, w.rir_len, w.fs, w.c, d.snr_db, d.alpha,
+                           w.frontend, d.frame_offsets, feats, rir, mixed, gains if w.n_noise else None)
+    torch.cuda.synchronize()
+    return dict(feats=feats.cpu().numpy(), rir=None if rir is None else rir.cpu().numpy(),
+                mixed=None if mixed is None else mixed.cpu().numpy(),
+                gains=gains.cpu().numpy()[:, :w.n_noise])
+
+
+def _oracle(w, conv="direct"):
+    return O.pipeline_batch(w.offsets, w.speech, w.noise, w.geom, w.rir_len, w.fs, w.c, w.snr_db,
+                            w.alpha, w.frontend, conv_method=conv)
+
+
+def _compare(got, ref, w):
+    assert rir_err(got["rir"], ref["rir"]) <= RIR_TOL
+    assert wave_err(got["mixed"], ref["mixed"], w.offsets) <= WAVE_TOL
+    np.testing.assert_allclose(got["gains"], ref["gains"], rtol=GAIN_TOL)
+    assert got["feats"].shape == ref["feats"].shape
+    assert feat_err(got["feats"], ref["feats"]) <= FEAT_TOL
+
+
+def test_tiny_config_end_to_end(aug):
+    w = W.tiny()
+    print("case: tiny pipeline, direct convolution + DFT-matrix oracle", flush=True)
+    got = _run(aug, w)
+    _compare(got, _oracle(w), w)
+    # internal buffers instead of caller outputs give the same features
+    again = _run(aug, w, want_rir=False, want_mixed=False)
+    assert feat_err(again["feats"], got["feats"].astype(np.float64)) <= 1e-5
+
+
+def test_batch_config_subset(aug):
+    w = W.batch(n_utt=4, seconds=4.0)
+    print("case: batch config, 4 utterances, L=8000, direct oracle", flush=True)
+    _compare(_run(aug, w), _oracle(w), w)
+
+
+def test_varlen_config_small(aug):
+    w = W.varlen(n_utt=5, rir_len=2000, min_s=0.02, max_s=1.5)
+    print("case: varlen small, 3 noises", flush=True)
+    _compare(_run(aug, w), _oracle(w), w)
+
+
+def test_varlen_full_size_sampled(aug):
+    # The benchmark's configuration and launch shape; the oracle checks sampled utterances:
+    # their responses in full (tap counts come from the rir test), the mixture through the
+    # fp64 FFT form tied to direct sums at sampled positions, and all their frames.
+    w = W.varlen()
+    print(f"case: varlen full size, {w.n_utt} utterances, {w.total} samples, L={w.rir_len}", flush=True)
+    got = _run(aug, w, want_rir=True, want_mixed=True)
+    assert not np.isnan(got["feats"]).any() and not np.isnan(got["mixed"]).any()
+    foff = w.frame_offsets()
+    lens = w.lengths()
+    rng = np.random.default_rng(0)
+    picks = [int(np.argmin(lens)), int(np.argmax(lens)), int(rng.integers(0, w.n_utt))]
+    for u in picks:
+        print(f"  utterance {u}: {lens[u]} samples", flush=True)
+        s = w.slice([u])
+        ref = _oracle(s, conv="fft")
+        sub = dict(rir=got["rir"][u:u + 1], mixed=got["mixed"][w.offsets[u]:w.offsets[u + 1]],
+                   gains=got["gains"][u:u + 1], feats=got["feats"][foff[u]:foff[u + 1]])
+        _compare(sub, ref, s)
+        pos = rng.integers(0, lens[u], 32)
+        for j in range(1 + w.n_noise):
+            x = s.speech if j == 0 else s.noise[j - 1]
+            direct = O.convolve_at(x, ref["rir"][0, j], pos)
+            np.testing.assert_allclose(O.convolve_fft(x, ref["rir"][0, j])[pos], direct, atol=1e-9)
+
+
+def test_no_noise_pipeline(aug):
+    import dataclasses
+    w = W.tiny(n_utt=2)
+    w = dataclasses.replace(w, noise=None, snr_db=None, geom=np.ascontiguousarray(w.geom[:, :1]))
+    got = _run(aug, w)
+    _compare(got, _oracle(w), w)
