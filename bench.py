@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Throughput of the augmentation + feature path on one MI355X.
+
+A step is one aug_pipeline_batch call (impulse responses, reverberation, SNR mix,
+warped power-mel features) over one batch of seeded synthetic utterances that is
+already resident in HBM.  Prints one JSON line with the whole-call throughput in
+audio-seconds per second, the roofline of the dominant kernel (timed with HIP
+events on the library's stream inside the timed region) and the CPU oracle timed
+on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "augmented audio-sec/sec (RIR+conv+mix+VTLP mel) on 1 GPU"
+PEAK_HBM_GBS = 8000.0
+PEAK_FP32_TFLOPS = 157.3
+PEAK_FP64_TFLOPS = 78.6
+RIR_FLOP_PER_IMAGE = 12.0     # 2 add, sqrt, mul, add, floor, table product, divide, scale, accumulate ...
+
+
+def describe(w) -> str:
+    n = w.lengths()
+    return (f"{w.name}: {w.n_utt} utterances, {n.min() / w.fs:.1f}-{n.max() / w.fs:.1f} s at 16 kHz fp32 "
+            f"({w.audio_seconds:.0f} audio-s), {w.n_noise} noise sources, RIR {w.rir_len} taps, "
+            f"seed {w.seed}")
+
+
+def conv_flop_per_sample(rir_len: int) -> float:
+    """One forward and one inverse real FFT of nfft = next pow2 >= 2 L plus the spectrum product,
+    per output sample of a classical overlap-save block (2.5 nfft log2 nfft flop per real FFT)."""
+    nfft = 1 << (2 * rir_len - 1).bit_length()
+    return (2 * 2.5 * nfft * math.log2(nfft) + 6 * (nfft / 2 + 1)) / (nfft - rir_len + 1)
+
+
+def stage_work(w, n_images: float):
+    """Algorithmic work of each stage for one step: (bound, amount, unit of amount)."""
+    n_src = 1 + w.n_noise
+    frames = int(w.frame_offsets()[-1])
+    fe = w.frontend
+    work = {
+        "mel": ("hbm", 4.0 * w.total + 4.0 * fe.n_mel * frames),
+        "mix": ("hbm", 4.0 * w.total * (n_src + 1)),
+    }
+    if w.geom is not None:
+        work["rir"] = ("alu", RIR_FLOP_PER_IMAGE * n_images)
+        work["convolve"] = ("alu32", conv_flop_per_sample(w.rir_len) * w.total * n_src)
+        work["rir_spectrum"] = ("alu32", 2.5 * (2 * w.rir_len) * math.log2(2 * w.rir_len) * w.n_utt * n_src)
+    return work
+
+
+def roofline_for(stage: str, work, ms: float):
+    bound, amount = work[stage]
+    sec = ms * 1e-3
+    if bound == "hbm":
+        achieved, peak, unit, b = amount / sec / 1e9, PEAK_HBM_GBS, "GB/s", "hbm"
+    elif bound == "alu":
+        achieved, peak, unit, b = amount / sec / 1e12, PEAK_FP64_TFLOPS, "TFLOP/s", "alu"
+    else:
+        achieved, peak, unit, b = amount / sec / 1e12, PEAK_FP32_TFLOPS, "TFLOP/s", "alu"
+    return {"bound": b, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
+            "traffic": None}
+
+
+def cpu_baseline(w, budget_s: float = 20.0):
+    """The oracle as it stands, one thread, on the first utterances of the workload."""
+    from oracle import aug_oracle as O
+    try:
+        from threadpoolctl import threadpool_limits
+    except Exception:                                  # pragma: no cover
+        threadpool_limits = None
+    n = w.lengths()
+    n_src = 1 + w.n_noise
+    picks, est = [], 0.0
+    for u in range(w.n_utt):
+        cost = 0.3 + n[u] * 3e-6                        # front end
+        if w.geom is not None:
+            images = 4.19 * (w.rir_len * w.c / w.fs) ** 3 / 100.0
+            cost += n_src * (n[u] * w.rir_len / 4.0e9 + images / 1.0e7)
+        if picks and est + cost > budget_s:
+            break
+        picks.append(u)
+        est += cost
+    s = w.slice(picks)
+
+    def run():
+        t0 = time.perf_counter()
+        if s.geom is not None:
+            O.pipeline_batch(s.offsets, s.speech, s.noise, s.geom, s.rir_len, s.fs, s.c, s.snr_db,
+                             s.alpha, s.frontend)
+        else:
+            O.vtlp_mel_batch(s.offsets, s.speech, s.alpha, s.frontend)
+        return time.perf_counter() - t0
+
+    if threadpool_limits is not None:
+        with threadpool_limits(limits=1):
+            dt = run()
+    else:
+        dt = run()
+    return {"value": s.audio_seconds / dt, "unit": "audio-s/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {len(picks)} utterance(s) of the workload ({s.audio_seconds:.1f} audio-s), "
+                      f"direct time-domain convolution + DFT-matrix front end, {dt:.1f} s"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="varlen",
+                    choices=["tiny", "features", "batch", "varlen", "throughput"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this path runs on one GPU (utterances are independent; there is nothing to "
+              "exchange), so --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_1912_11040_amd import workloads as W
+    from paper_1912_11040_amd.binding import Augmenter
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+
+    w = W.WORKLOADS[args.workload]()
+    dev = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    speech, noise, geom = dev(w.speech), dev(w.noise), dev(w.geom)
+    snr, alpha = dev(w.snr_db), dev(w.alpha)
+    foff = w.frame_offsets()
+    feats = torch.empty((int(foff[-1]), w.frontend.n_mel), dtype=torch.float32, device="cuda")
+    full = w.geom is not None
+
+    aug = Augmenter(0)
+
+    def step():
+        if full:
+            aug.aug_pipeline_batch(w.offsets, speech, noise, geom, w.rir_len, w.fs, w.c, snr, alpha,
+                                   w.frontend, foff, feats)
+        else:
+            aug.aug_vtlp_mel_batch(w.offsets, speech, alpha, w.frontend, foff, feats)
+
+    # images per step, for the image-sum kernel's algorithmic work (counted once, untimed)
+    n_images = 0.0
+    if full:
+        n_rir = w.n_utt * (1 + w.n_noise)
+        chunk = max(1, min(n_rir, (1 << 28) // w.rir_len))
+        g2 = geom.reshape(-1, 10)
+        for a in range(0, n_rir, chunk):
+            b = min(n_rir, a + chunk)
+            h = torch.empty((b - a, w.rir_len), dtype=torch.float32, device="cuda")
+            cnt = torch.empty((b - a, w.rir_len), dtype=torch.int32, device="cuda")
+            aug.aug_rir_batch(g2[a:b].contiguous(), w.rir_len, w.fs, w.c, h, cnt)
+            n_images += float(cnt.sum(dtype=torch.int64).item())
+            del h, cnt
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    aug.aug_profile_read()
+    aug.aug_profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = aug.aug_profile_read()
+    aug.aug_profile_enable(False)
+
+    ms_per_step = dt * 1e3 / args.steps
+    stages = {k: (ms / max(n, 1), n) for k, (ms, n) in prof.items() if n > 0}
+    work = stage_work(w, n_images)
+    dominant = max((k for k in stages if k in work), key=lambda k: stages[k][0] * stages[k][1])
+    per_step_launches = stages[dominant][1] / args.steps
+    roof = roofline_for(dominant, work, stages[dominant][0] * per_step_launches)
+    roof["kernel"] = {"rir": "rir_image_kernel", "convolve": "convolve_kernel", "mel": "mel_kernel",
+                      "mix": "mix_kernel", "rir_spectrum": "rir_spectrum_kernel"}[dominant]
+    roof["avg_launch_ms"] = stages[dominant][0]
+
+    out = {
+        "metric": METRIC,
+        "value": w.audio_seconds / (ms_per_step * 1e-3),
+        "unit": "audio-s/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": describe(w), "entry_point": "aug_pipeline_batch" if full else "aug_vtlp_mel_batch",
+                   "images_per_step": n_images},
+        "roofline": roof,
+        "stage_ms": {k: round(v[0] * v[1] / args.steps, 4) for k, v in stages.items()},
+        "stage_roofline_frac": {k: round(roofline_for(k, work, stages[k][0] * stages[k][1] / args.steps)["frac"], 4)
+                                for k in stages if k in work},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    aug.close()
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

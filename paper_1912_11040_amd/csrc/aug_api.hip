@@ -205,15 +205,22 @@ int mark(aug_ctx* ctx, int stage) {
 int run_rir(aug_ctx* ctx, int n_rir, const float* geom, int rir_len, float fs, float c, float* rir_out,
             int32_t* tap_count_out) {
     const double k = (double)fs / (double)c;
+    AUG_HIP(ctx->rir_items.reserve(aug::rir_item_bytes() * (size_t)n_rir * aug::rir_items_per_response(rir_len)),
+            "response item table");
+    AUG_HIP(ctx->rir_ctrl.reserve(2 * sizeof(int)), "response item counter");
+    AUG_HIP(ctx->rir_pow.reserve(sizeof(float) * (size_t)n_rir * aug::rir_pow_entries()), "reflection table");
+    const int n_groups = 2 * ctx->n_cu;
     AUG_TRY(mark(ctx, -1));
-    AUG_HIP(aug::launch_fill_u32(ctx->stream, rir_out, 0u, (int64_t)n_rir * rir_len), "response clear");
-    if (tap_count_out)
-        AUG_HIP(aug::launch_fill_u32(ctx->stream, tap_count_out, 0u, (int64_t)n_rir * rir_len), "count clear");
+    AUG_HIP(aug::launch_rir_plan(ctx->stream, n_rir, geom, rir_len, k, ctx->rir_items.ptr,
+                                 ctx->rir_ctrl.as<int>(), ctx->rir_pow.as<float>()), "rir plan kernel");
     AUG_TRY(mark(ctx, AUG_STAGE_OTHER));
-    AUG_HIP(aug::launch_rir(ctx->stream, n_rir, geom, rir_len, k, rir_out, nullptr), "rir kernel");
+    AUG_HIP(aug::launch_rir(ctx->stream, n_groups, n_rir, geom, rir_len, k, ctx->rir_items.ptr,
+                            ctx->rir_ctrl.as<int>(), ctx->rir_pow.as<float>(), rir_out, nullptr), "rir kernel");
     AUG_TRY(mark(ctx, AUG_STAGE_RIR));
     if (tap_count_out) {
-        AUG_HIP(aug::launch_rir(ctx->stream, n_rir, geom, rir_len, k, nullptr, tap_count_out), "rir count kernel");
+        AUG_HIP(aug::launch_rir(ctx->stream, n_groups, n_rir, geom, rir_len, k, ctx->rir_items.ptr,
+                                ctx->rir_ctrl.as<int>(), ctx->rir_pow.as<float>(), nullptr, tap_count_out),
+                "rir count kernel");
         AUG_TRY(mark(ctx, AUG_STAGE_OTHER));
     }
     return AUG_OK;
@@ -337,6 +344,12 @@ int aug_create(aug_ctx** out, int device_id, void* hip_stream) {
     if (!ctx) return AUG_ERR_NOMEM;
     ctx->device = device_id;
     ctx->stream = static_cast<hipStream_t>(hip_stream);
+    if (hipDeviceGetAttribute(&ctx->n_cu, hipDeviceAttributeMultiprocessorCount, device_id) != hipSuccess ||
+        ctx->n_cu < 1) {
+        (void)hipGetLastError();
+        delete ctx;
+        return AUG_ERR_HIP;
+    }
     *out = ctx;
     return AUG_OK;
 }
@@ -349,7 +362,7 @@ int aug_destroy(aug_ctx* ctx) {
         rc = AUG_ERR_HIP;
     }
     DeviceBuffer* bufs[] = {&ctx->d_offsets, &ctx->d_frame_offsets, &ctx->d_conv_items, &ctx->d_frame_items,
-                            &ctx->rir, &ctx->rir_spec, &ctx->reverb, &ctx->energy, &ctx->mixed, &ctx->mel_tab,
+                            &ctx->rir_items, &ctx->rir_ctrl, &ctx->rir_pow, &ctx->rir, &ctx->rir_spec, &ctx->reverb, &ctx->energy, &ctx->mixed, &ctx->mel_tab,
                             &ctx->window};
     for (DeviceBuffer* b : bufs) b->release();
     for (DeviceBuffer& b : ctx->twiddle) b.release();
@@ -401,7 +414,8 @@ int aug_rir_batch(aug_ctx* ctx, int n_rir, const float* geom, int rir_len, float
     AUG_TRY(check_rir_args(ctx, rir_len, fs, c));
     if (n_rir == 0) return AUG_OK;
     if (!geom || !rir_out) return fail(ctx, AUG_ERR_INVALID_ARG, "geom or rir_out is null");
-    if ((int64_t)n_rir * 64 > 0x7fffffffLL) return fail(ctx, AUG_ERR_UNSUPPORTED, "too many responses in one call");
+    if ((int64_t)n_rir * aug::rir_items_per_response(rir_len) > 0x7fffffffLL)
+        return fail(ctx, AUG_ERR_UNSUPPORTED, "too many responses in one call");
     return run_rir(ctx, n_rir, geom, rir_len, fs, c, rir_out, tap_count_out);
 }
 
@@ -443,7 +457,7 @@ int aug_pipeline_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, const fl
     AUG_TRY(check_frame_offsets(ctx, n_utt, offsets, frame_offsets, cfg));
     if (!geom || !alpha || !feats_out) return fail(ctx, AUG_ERR_INVALID_ARG, "geom, alpha or feats_out is null");
     const int n_src = 1 + n_noise;
-    if ((int64_t)n_utt * n_src * 64 > 0x7fffffffLL)
+    if ((int64_t)n_utt * n_src * aug::rir_items_per_response(rir_len) > 0x7fffffffLL)
         return fail(ctx, AUG_ERR_UNSUPPORTED, "too many responses in one call");
     AUG_TRY(sync_packing(ctx, n_utt, offsets, frame_offsets, aug::conv_fft_size(rir_len),
                          aug::mel_frames_per_group()));

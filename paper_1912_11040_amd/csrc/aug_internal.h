@@ -46,6 +46,12 @@ struct aug_ctx {
     aug::DeviceBuffer d_conv_items;      // int2 [n_conv_blocks]: (utterance, block)
     aug::DeviceBuffer d_frame_items;     // int2 [n_frame_groups]: (utterance, first frame)
 
+    // image-method work list
+    int n_cu = 0;                        // compute units of the device
+    aug::DeviceBuffer rir_items;         // Item [n_rir * items_per_response]
+    aug::DeviceBuffer rir_ctrl;          // int [2]: item count, next item
+    aug::DeviceBuffer rir_pow;           // float [n_rir][pow entries]: beta^k
+
     // intermediate results
     aug::DeviceBuffer rir;               // float [n_rir][rir_len]            (pipeline only)
     aug::DeviceBuffer rir_spec;          // float2 [n_rir][n_part][P+1]
@@ -66,10 +72,17 @@ namespace aug {
 
 // ---- kernels' host launchers (each checks nothing; arguments are validated by the API layer) ----
 
-// Image-method impulse responses into rir_out float [n_rir][rir_len] and/or tap counts into
-// cnt_out int32 [n_rir][rir_len] (either may be null); both must be zero on entry.
-hipError_t launch_rir(hipStream_t s, int n_rir, const float* geom, int rir_len, double fs_over_c,
-                      float* rir_out, int32_t* cnt_out);
+// Image-method impulse responses.  launch_rir_plan cuts every response into items (tap ranges of
+// about equal image count), fills the beta^k tables and resets ctrl = {item count, next item};
+// launch_rir then runs n_groups persistent work groups over the items, writing either
+// rir_out float [n_rir][rir_len] or, if rir_out is null, tap counts cnt_out int32 [n_rir][rir_len].
+int rir_items_per_response(int rir_len);
+size_t rir_item_bytes();
+int rir_pow_entries();
+hipError_t launch_rir_plan(hipStream_t s, int n_rir, const float* geom, int rir_len, double fs_over_c,
+                           void* items, int* ctrl, float* pow_table);
+hipError_t launch_rir(hipStream_t s, int n_groups, int n_rir, const float* geom, int rir_len, double fs_over_c,
+                      const void* items, int* ctrl, const float* pow_table, float* rir_out, int32_t* cnt_out);
 
 // Largest complex FFT size the convolution kernels are built for, and the size chosen for a response length.
 int conv_fft_size(int rir_len);

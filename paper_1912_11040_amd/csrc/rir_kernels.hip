@@ -6,46 +6,48 @@
 // Along one axis the images of a source at s between walls at 0 and L are
 // (1 - 2q) s + 2 n L, q in {0,1}, n integer, reflected |n - q| + |n| times.
 //
-// The tap index is integer work decided by floating point, so it is evaluated in
-// fp64 with a fixed operation order and no contraction:
+// The tap index is integer work decided by floating point, so it follows one fixed
+// fp64 recipe with no contraction:
 //     d2 = (dx*dx + dy*dy) + dz*dz;  idx = floor(sqrt(d2) * (fs/c) + 0.5)
-// Amplitudes are fp32 and accumulate through LDS float atomics (order free).
+// A cheap estimate of sqrt (fp32 rsq + one fp64 Newton step) decides the index
+// whenever the result is farther from a rounding boundary than the estimate's error
+// bound; the rare remaining images take the exact correctly-rounded sqrt.
 //
-// Work split: one response is cut over `n_split` work groups by striding the
-// (x image, y image) columns; each thread walks the z images of its columns that can
-// fall inside the sphere of radius rir_len * c / fs.  Every group keeps a private
-// tap histogram in LDS and adds it to the zero-initialised output at the end.
+// Layout of the work
+//   * plan kernel: one thread per response cuts its taps into shells [n0, n1) of about
+//     equal image count (equal volume of the spherical shell) and at most kMaxTaps taps,
+//     and appends them to an item table.
+//   * image kernel: persistent work groups fetch items from a counter.  An item owns its
+//     taps, so sums live in LDS and are stored once, without global atomics.
+//     A wave takes 64 (x image, y image) columns at a time; each column contributes up to
+//     four runs of consecutive z images inside the shell.  Runs are cut into pieces of at
+//     most kPiece images, the pieces are dealt to lanes, and each lane walks its piece.
+//   * amplitudes accumulate as 64-bit fixed point (2^-56) with integer LDS atomics:
+//     gfx950 executes float LDS atomics about thirty times slower than integer ones, and
+//     integer sums do not depend on the order of arrival.
 
 #include "aug_internal.h"
 
 namespace aug {
 namespace {
 
-constexpr int kRirThreads = 1024;
-constexpr int kPowTable = 4096;          // beta^k table entries held in LDS
-constexpr int kMaxSplit = 64;            // most work groups one response is cut into
-constexpr float kImagesPerGroup = 262144.0f;
+constexpr int kThreads = 512;
+constexpr int kWaves = kThreads / 64;
+constexpr int kMaxTaps = 6144;            // taps owned by one item (LDS: 8 bytes each)
+constexpr int kMinTaps = 64;
+constexpr int kPow = 2048;                // beta^k table entries held in LDS
+constexpr int kPiece = 16;                // images per piece
+constexpr float kTargetImages = 400000.f; // images per item aimed for
+constexpr int kMaxShells = 96;            // volume-balanced shells per response, at most
 
 #pragma clang fp contract(off)
 
-struct AxisGeom {
+struct Axis {
     double room, src, mic;
-    int n_max;       // images use n in [-n_max, n_max]
-    int n_img;       // 2 * (2 n_max + 1)
 };
 
-__device__ inline AxisGeom make_axis(float room, float src, float mic, double radius) {
-    AxisGeom a;
-    a.room = (double)room;
-    a.src = (double)src;
-    a.mic = (double)mic;
-    a.n_max = (int)ceil(radius / (2.0 * a.room)) + 1;
-    a.n_img = 2 * (2 * a.n_max + 1);
-    return a;
-}
-
-// image index i -> (q, n): q = i & 1, n = (i >> 1) - n_max
-__device__ inline double axis_delta(const AxisGeom& a, int q, int n) {
+// delta of image (q, n) to the microphone along one axis, in the reference operation order
+__device__ inline double axis_delta(const Axis& a, int q, int n) {
     const double sgn = q ? -1.0 : 1.0;
     const double coord = __dadd_rn(__dmul_rn(sgn, a.src), __dmul_rn(__dmul_rn(2.0, (double)n), a.room));
     return __dsub_rn(coord, a.mic);
@@ -53,100 +55,251 @@ __device__ inline double axis_delta(const AxisGeom& a, int q, int n) {
 
 __device__ inline int iabs(int v) { return v < 0 ? -v : v; }
 
-template <bool COUNT>
-__global__ __launch_bounds__(kRirThreads) void rir_image_kernel(
-    const float* __restrict__ geom, int rir_len, double k_fs_c, float* __restrict__ rir_out,
-    int32_t* __restrict__ cnt_out) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    float* hist_f = reinterpret_cast<float*>(smem);
-    int* hist_i = reinterpret_cast<int*>(smem);
-    float* bpow = reinterpret_cast<float*>(smem + sizeof(float) * (size_t)rir_len);
+__device__ inline bool room_ok(const float* g) {
+    return (g[0] >= 0.1f) && (g[1] >= 0.1f) && (g[2] >= 0.1f) && (g[0] * g[1] * g[2] < 1e30f);
+}
 
-    const int r = blockIdx.x / kMaxSplit;
-    const int part = blockIdx.x % kMaxSplit;
+struct Item { int rir, n0, n1; };
+
+// ctrl[0] = number of items, ctrl[1] = next item to hand out
+__global__ void rir_plan_kernel(int n_rir, const float* __restrict__ geom, int rir_len, double k_fs_c,
+                                Item* __restrict__ items, int items_per_rir, int* __restrict__ ctrl) {
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= n_rir) return;
     const float* g = geom + (size_t)r * 10;
-
-    // Images beyond this distance cannot round to a tap below rir_len.
     const double radius = (double)rir_len / k_fs_c;
-    // a degenerate room (a side under 10 cm, or not a number) has no images: the output stays zero
-    if (!(g[0] >= 0.1f) || !(g[1] >= 0.1f) || !(g[2] >= 0.1f) || !(g[0] * g[1] * g[2] < 1e30f)) return;
-    const float volume = g[0] * g[1] * g[2];
-    const float est_images = 4.18879f * (float)(radius * radius * radius) / volume;
-    int n_split = (int)ceilf(est_images / kImagesPerGroup);
-    n_split = n_split < 1 ? 1 : (n_split > kMaxSplit ? kMaxSplit : n_split);
-    if (part >= n_split) return;
-
-    const AxisGeom ax = make_axis(g[0], g[3], g[6], radius);
-    const AxisGeom ay = make_axis(g[1], g[4], g[7], radius);
-    const AxisGeom az = make_axis(g[2], g[5], g[8], radius);
-    const double beta = (double)g[9];
-
-    for (int i = threadIdx.x; i < rir_len; i += kRirThreads) {
-        if (COUNT) hist_i[i] = 0; else hist_f[i] = 0.0f;
+    float shells = 1.f;
+    if (room_ok(g)) {
+        const float est = 4.18879f * (float)(radius * radius * radius) / (g[0] * g[1] * g[2]);
+        shells = fminf(fmaxf(ceilf(est / kTargetImages), 1.f), (float)kMaxShells);
     }
-    if (!COUNT) {
-        for (int i = threadIdx.x; i < kPowTable; i += kRirThreads)
-            bpow[i] = (float)pow(beta, (double)i);
+    const double L3 = (double)rir_len * rir_len * rir_len;
+    const double step = L3 / (double)shells;
+    int bounds[kMaxShells + AUG_MAX_RIR_LEN / kMaxTaps + 4];
+    int count = 0, b = 0;
+    while (b < rir_len && count < items_per_rir - 1) {
+        int nb = (int)cbrt((double)b * b * b + step);
+        nb = max(nb, b + kMinTaps);
+        nb = min(min(nb, b + kMaxTaps), rir_len);
+        bounds[count++] = nb;
+        b = nb;
     }
-    __syncthreads();
+    if (b < rir_len) {          // out of table space: cannot happen with the sizes chosen by the host
+        while (b < rir_len && count < items_per_rir) {
+            const int nb = min(b + kMaxTaps, rir_len);
+            bounds[count++] = nb;
+            b = nb;
+        }
+    }
+    const int base = atomicAdd(&ctrl[0], count);
+    int lo = 0;
+    for (int i = 0; i < count; ++i) {
+        items[base + i] = Item{r, lo, bounds[i]};
+        lo = bounds[i];
+    }
+}
 
-    const double r2_cut = radius * radius * (1.0 + 1e-9) + 1e-9;
-    const double two_lz = 2.0 * az.room;
-    const double inv_two_lz = 1.0 / two_lz;
-    const float inv_4pi = 0.07957747154594767f;
+__global__ void rir_pow_kernel(int n_rir, const float* __restrict__ geom, float* __restrict__ table) {
+    const int r = blockIdx.y;
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= kPow) return;
+    table[(size_t)r * kPow + k] = (float)pow((double)geom[(size_t)r * 10 + 9], (double)k);
+}
 
-    const int64_t n_col = (int64_t)ax.n_img * ay.n_img;
-    for (int64_t col = (int64_t)part * kRirThreads + threadIdx.x; col < n_col;
-         col += (int64_t)n_split * kRirThreads) {
-        const int ix = (int)(col / ay.n_img), iy = (int)(col % ay.n_img);
-        const int qx = ix & 1, nx = (ix >> 1) - ax.n_max;
-        const int qy = iy & 1, ny = (iy >> 1) - ay.n_max;
-        const double dx = axis_delta(ax, qx, nx);
-        const double dy = axis_delta(ay, qy, ny);
-        const double a = __dadd_rn(__dmul_rn(dx, dx), __dmul_rn(dy, dy));
-        if (a >= r2_cut) continue;
-        const int kxy = iabs(nx - qx) + iabs(nx) + iabs(ny - qy) + iabs(ny);
-        const double z_reach = sqrt(r2_cut - a);
+// per-column record shared through LDS between the lane that built it and the lanes that walk its pieces
+struct __align__(16) Column {
+    double a;            // dx*dx + dy*dy
+    int kxy;             // reflections along x and y
+    int pfx;             // inclusive prefix of piece counts within the wave's batch
+    short start[4];      // first n of runs (q=0: runs 0,1; q=1: runs 2,3)
+    short len[4];
+};
+
+__device__ inline int wave_inclusive_scan(int v, int lane) {
 #pragma unroll
-        for (int qz = 0; qz < 2; ++qz) {
-            // images with |dz| <= z_reach, padded by one on either side; the exact
-            // idx < rir_len test below decides.
-            const double z0 = __dsub_rn(__dmul_rn(qz ? -1.0 : 1.0, az.src), az.mic);
-            int n_lo = (int)floor((-z_reach - z0) * inv_two_lz) - 1;
-            int n_hi = (int)ceil((z_reach - z0) * inv_two_lz) + 1;
-            n_lo = n_lo < -az.n_max ? -az.n_max : n_lo;
-            n_hi = n_hi > az.n_max ? az.n_max : n_hi;
-            for (int n = n_lo; n <= n_hi; ++n) {
-                const double dz = axis_delta(az, qz, n);
-                const double d2 = __dadd_rn(a, __dmul_rn(dz, dz));
-                const double d = __dsqrt_rn(d2);
-                const double t = __dadd_rn(__dmul_rn(d, k_fs_c), 0.5);
-                if (!(t < (double)rir_len)) continue;
-                const int idx = (int)t;            // t >= 0.5 > 0: truncation is floor
-                if (COUNT) {
-                    atomicAdd(&hist_i[idx], 1);
-                } else {
-                    const int k = kxy + iabs(n - qz) + iabs(n);
-                    const float b = k < kPowTable ? bpow[k] : (float)pow(beta, (double)k);
-                    atomicAdd(&hist_f[idx], b * inv_4pi / (float)d);
+    for (int off = 1; off < 64; off <<= 1) {
+        const int t = __shfl_up(v, off, 64);
+        if (lane >= off) v += t;
+    }
+    return v;
+}
+
+template <bool COUNT>
+__global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
+    const float* __restrict__ geom, int rir_len, double k_fs_c, const Item* __restrict__ items,
+    int* __restrict__ ctrl, const float* __restrict__ pow_table, float* __restrict__ rir_out,
+    int32_t* __restrict__ cnt_out) {
+    __shared__ unsigned long long hist[COUNT ? kMaxTaps / 2 : kMaxTaps];
+    __shared__ float bpow[COUNT ? 1 : kPow];
+    __shared__ Column cols[kWaves][64];
+    __shared__ int s_item;
+    unsigned int* hist32 = reinterpret_cast<unsigned int*>(hist);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n_items = ctrl[0];
+
+    for (;;) {
+        if (tid == 0) s_item = atomicAdd(&ctrl[1], 1);
+        __syncthreads();
+        const int it = s_item;
+        if (it >= n_items) break;
+        const Item item = items[it];
+        const int n0 = item.n0, n1 = item.n1, n_taps = n1 - n0;
+        const float* g = geom + (size_t)item.rir * 10;
+
+        if (COUNT) {
+            for (int i = tid; i < n_taps; i += kThreads) hist32[i] = 0u;
+        } else {
+            for (int i = tid; i < n_taps; i += kThreads) hist[i] = 0ull;
+            for (int i = tid; i < kPow; i += kThreads) bpow[i] = pow_table[(size_t)item.rir * kPow + i];
+        }
+        __syncthreads();
+
+        if (room_ok(g)) {
+            const Axis ax{(double)g[0], (double)g[3], (double)g[6]};
+            const Axis ay{(double)g[1], (double)g[4], (double)g[7]};
+            const Axis az{(double)g[2], (double)g[5], (double)g[8]};
+            const double beta = (double)g[9];
+            // every image of this item lies in r_in <= d < r_out (half a tap of slack on either side)
+            const double r_out = (double)n1 / k_fs_c;
+            const double r_in = n0 > 0 ? (double)(n0 - 1) / k_fs_c : 0.0;
+            const double r_out2 = r_out * r_out, r_in2 = r_in * r_in;
+            const int nmx = (int)ceil(r_out / (2.0 * ax.room)) + 1;
+            const int nmy = (int)ceil(r_out / (2.0 * ay.room)) + 1;
+            const int nix = 2 * (2 * nmx + 1), niy = 2 * (2 * nmy + 1);
+            const int n_cand = nix * niy;
+            const double inv_two_lz = 1.0 / (2.0 * az.room);
+            const double z0q[2] = {__dsub_rn(az.src, az.mic), __dsub_rn(__dmul_rn(-1.0, az.src), az.mic)};
+            const int n_batch = (n_cand + 63) / 64;
+            Column* wc = cols[wave];
+
+            for (int batch = wave; batch < n_batch; batch += kWaves) {
+                // ---- each lane describes one candidate column ----
+                const int cand = batch * 64 + lane;
+                Column col;
+                col.a = 0.0; col.kxy = 0;
+                int pieces = 0;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) { col.start[i] = 0; col.len[i] = 0; }
+                if (cand < n_cand) {
+                    const int ix = cand / niy, iy = cand - ix * niy;
+                    const int qx = ix & 1, nx = (ix >> 1) - nmx;
+                    const int qy = iy & 1, ny = (iy >> 1) - nmy;
+                    const double dx = axis_delta(ax, qx, nx);
+                    const double dy = axis_delta(ay, qy, ny);
+                    col.a = __dadd_rn(__dmul_rn(dx, dx), __dmul_rn(dy, dy));
+                    col.kxy = iabs(nx - qx) + iabs(nx) + iabs(ny - qy) + iabs(ny);
+                    if (col.a < r_out2) {
+                        const double zout = sqrt(r_out2 - col.a);
+                        const double zin = col.a < r_in2 ? sqrt(r_in2 - col.a) : 0.0;
+#pragma unroll
+                        for (int q = 0; q < 2; ++q) {
+                            const double z0 = z0q[q];
+                            const int lo_n = (int)ceil((-zout - z0) * inv_two_lz - 1e-6);
+                            const int hi_n = (int)floor((-zin - z0) * inv_two_lz + 1e-6);
+                            const int lo_p = (int)ceil((zin - z0) * inv_two_lz - 1e-6);
+                            const int hi_p = (int)floor((zout - z0) * inv_two_lz + 1e-6);
+                            if (hi_n >= lo_p - 1) {            // the two sides touch: one run
+                                col.start[2 * q] = (short)lo_n;
+                                col.len[2 * q] = (short)max(hi_p - lo_n + 1, 0);
+                            } else {
+                                col.start[2 * q] = (short)lo_n;
+                                col.len[2 * q] = (short)max(hi_n - lo_n + 1, 0);
+                                col.start[2 * q + 1] = (short)lo_p;
+                                col.len[2 * q + 1] = (short)max(hi_p - lo_p + 1, 0);
+                            }
+                        }
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) pieces += (col.len[i] + kPiece - 1) / kPiece;
+                    }
                 }
+                col.pfx = wave_inclusive_scan(pieces, lane);
+                const int n_pieces = __shfl(col.pfx, 63, 64);
+                wc[lane] = col;
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+                // ---- pieces are dealt to lanes ----
+                for (int p = lane; p < n_pieces; p += 64) {
+                    int slot = 0;                               // smallest slot with pfx > p
+#pragma unroll
+                    for (int s = 32; s > 0; s >>= 1)
+                        if (wc[slot + s - 1].pfx <= p) slot += s;
+                    const Column c = wc[slot];
+                    int local = p - (slot ? wc[slot - 1].pfx : 0);
+                    // which of the four runs holds piece `local` (selects only: no register indexing)
+                    int run = 0, r_start = c.start[0], r_len = c.len[0];
+#pragma unroll
+                    for (int i = 0; i < 3; ++i) {
+                        const int np = ((int)c.len[i] + kPiece - 1) / kPiece;
+                        if (run == i && local >= np) {
+                            local -= np;
+                            run = i + 1;
+                            r_start = c.start[i + 1];
+                            r_len = c.len[i + 1];
+                        }
+                    }
+                    const int q = run >> 1;
+                    const int first = r_start + local * kPiece;
+                    const int len = min(kPiece, r_len - local * kPiece);
+
+                    for (int i = 0; i < len; ++i) {
+                        const int n = first + i;
+                        const double dz = axis_delta(az, q, n);
+                        const double d2 = __dadd_rn(c.a, __dmul_rn(dz, dz));
+                        // estimate: y ~ 1/sqrt(d2) in fp32, one Newton step in fp64
+                        const float d2f = (float)d2;
+                        const float y = __frsqrt_rn(d2f);
+                        const double s0 = (double)(d2f * y);
+                        const double res = fma(-s0, s0, d2);
+                        const double s1 = fma(res, (double)(0.5f * y), s0);
+                        double t = fma(s1, k_fs_c, 0.5);
+                        double fl = floor(t);
+                        const double frac = t - fl;
+                        // |t - exact| < 1e-12 t for any d2 > 0; closer than that to a boundary: redo exactly
+                        const double guard = 1e-12 * t + 1e-13;
+                        if (frac < guard || frac > 1.0 - guard) {
+                            const double d = __dsqrt_rn(d2);
+                            t = __dadd_rn(__dmul_rn(d, k_fs_c), 0.5);
+                            fl = floor(t);
+                        }
+                        if (!(fl >= (double)n0 && fl < (double)n1)) continue;
+                        const int idx = (int)fl - n0;
+                        if (COUNT) {
+                            atomicAdd(&hist32[idx], 1u);
+                        } else {
+                            const int k = c.kxy + iabs(n - q) + iabs(n);
+                            const float b = k < kPow ? bpow[k] : (float)pow(beta, (double)k);
+                            const float amp = b * (0.07957747154594767f * y);
+                            // amp * 2^56 as a 64-bit integer, from two exact fp32 scalings
+                            const float x = amp * 16777216.0f;
+                            const float xh = floorf(x);
+                            const unsigned int hi = (unsigned int)xh;
+                            const unsigned int lo = (unsigned int)((x - xh) * 4294967296.0f);
+                            atomicAdd(&hist[idx], ((unsigned long long)hi << 32) | lo);
+                        }
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             }
         }
-    }
-    __syncthreads();
+        __syncthreads();
 
-    if (COUNT) {
-        int32_t* out = cnt_out + (size_t)r * rir_len;
-        for (int i = threadIdx.x; i < rir_len; i += kRirThreads) {
-            const int v = hist_i[i];
-            if (n_split == 1) out[i] = v; else if (v) atomicAdd(&out[i], v);
+        if (COUNT) {
+            int32_t* out = cnt_out + (size_t)item.rir * rir_len + n0;
+            for (int i = tid; i < n_taps; i += kThreads) out[i] = (int32_t)hist32[i];
+        } else {
+            float* out = rir_out + (size_t)item.rir * rir_len + n0;
+            for (int i = tid; i < n_taps; i += kThreads) {
+                const unsigned long long v = hist[i];
+                const double d = (double)(unsigned int)(v >> 32) * 4294967296.0 + (double)(unsigned int)v;
+                out[i] = (float)(d * 1.3877787807814457e-17);       // 2^-56
+            }
         }
-    } else {
-        float* out = rir_out + (size_t)r * rir_len;
-        for (int i = threadIdx.x; i < rir_len; i += kRirThreads) {
-            const float v = hist_f[i];
-            if (n_split == 1) out[i] = v; else if (v != 0.0f) atomicAdd(&out[i], v);
-        }
+        __syncthreads();
     }
 }
 
@@ -165,34 +318,36 @@ hipError_t launch_fill_u32(hipStream_t s, void* p, uint32_t v, int64_t n) {
     return hipGetLastError();
 }
 
-hipError_t launch_rir(hipStream_t s, int n_rir, const float* geom, int rir_len, double fs_over_c,
-                      float* rir_out, int32_t* cnt_out) {
+int rir_items_per_response(int rir_len) { return kMaxShells + rir_len / kMaxTaps + 2; }
+size_t rir_item_bytes() { return sizeof(Item); }
+int rir_pow_entries() { return kPow; }
+
+hipError_t launch_rir_plan(hipStream_t s, int n_rir, const float* geom, int rir_len, double fs_over_c,
+                           void* items, int* ctrl, float* pow_table) {
     if (n_rir <= 0) return hipSuccess;
-    hipError_t e = hipSuccess;
-    const size_t lds_f = sizeof(float) * (size_t)rir_len + sizeof(float) * kPowTable;
-    const size_t lds_i = sizeof(int) * (size_t)rir_len;
-    static bool attr_set = false;
-    if (!attr_set) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&rir_image_kernel<false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&rir_image_kernel<true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    const dim3 grid((unsigned)n_rir * kMaxSplit), block(kRirThreads);
-    // Outputs must be zero on entry: a response cut over several groups is accumulated with atomics.
-    if (rir_out) {
-        rir_image_kernel<false><<<grid, block, lds_f, s>>>(geom, rir_len, fs_over_c, rir_out, nullptr);
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
-    if (cnt_out) {
-        rir_image_kernel<true><<<grid, block, lds_i, s>>>(geom, rir_len, fs_over_c, nullptr, cnt_out);
-        e = hipGetLastError();
-    }
-    return e;
+    hipError_t e = launch_fill_u32(s, ctrl, 0u, 2);
+    if (e != hipSuccess) return e;
+    rir_plan_kernel<<<dim3((n_rir + 127) / 128), dim3(128), 0, s>>>(
+        n_rir, geom, rir_len, fs_over_c, static_cast<Item*>(items), rir_items_per_response(rir_len), ctrl);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    rir_pow_kernel<<<dim3(kPow / 256, (unsigned)n_rir), dim3(256), 0, s>>>(n_rir, geom, pow_table);
+    return hipGetLastError();
+}
+
+hipError_t launch_rir(hipStream_t s, int n_groups, int n_rir, const float* geom, int rir_len, double fs_over_c,
+                      const void* items, int* ctrl, const float* pow_table, float* rir_out, int32_t* cnt_out) {
+    if (n_rir <= 0) return hipSuccess;
+    hipError_t e = launch_fill_u32(s, ctrl + 1, 0u, 1);      // restart the item counter
+    if (e != hipSuccess) return e;
+    const Item* it = static_cast<const Item*>(items);
+    if (rir_out)
+        rir_image_kernel<false><<<dim3((unsigned)n_groups), dim3(kThreads), 0, s>>>(
+            geom, rir_len, fs_over_c, it, ctrl, pow_table, rir_out, nullptr);
+    else
+        rir_image_kernel<true><<<dim3((unsigned)n_groups), dim3(kThreads), 0, s>>>(
+            geom, rir_len, fs_over_c, it, ctrl, pow_table, nullptr, cnt_out);
+    return hipGetLastError();
 }
 
 }  // namespace aug
