@@ -33,9 +33,10 @@ namespace {
 
 constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / 64;
-constexpr int kMaxTaps = 6144;            // taps owned by one item (LDS: 8 bytes each)
+constexpr int kMaxTaps = 6016;            // taps owned by one item (LDS: 8 bytes each)
 constexpr int kMinTaps = 64;
-constexpr int kPow = 2048;                // beta^k table entries held in LDS
+constexpr int kPow = 1024;                // beta^k table entries held in LDS
+constexpr int kZCap = 320;                // z images per q held in LDS; more than that: computed in the loop
 constexpr int kPiece = 16;                // images per piece
 constexpr float kTargetImages = 400000.f; // images per item aimed for
 constexpr int kMaxShells = 96;            // volume-balanced shells per response, at most
@@ -124,6 +125,81 @@ __device__ inline int wave_inclusive_scan(int v, int lane) {
     return v;
 }
 
+struct __align__(16) ZEntry {
+    double dz2;          // squared z distance of image (q, n), reference operation order
+    float bz;            // beta^(|n-q| + |n|)
+    float pad;
+};
+
+struct WalkCtx {
+    double k_fs_c;
+    double guard;        // estimates closer than this to a rounding boundary are redone exactly
+    double beta;
+    int n0, n_taps;
+};
+
+// the reference recipe, kept out of line so that the estimate's loop stays short
+__device__ __attribute__((noinline)) int exact_tap(double d2, double k_fs_c) {
+    const double d = __dsqrt_rn(d2);
+    return (int)__dadd_rn(__dmul_rn(d, k_fs_c), 0.5);     // positive: truncation is floor
+}
+
+// Tap index of an image at squared distance d2, and y ~ 1/sqrt(d2) for its amplitude.
+__device__ inline int tap_index(const WalkCtx& w, double d2, float& y) {
+    const float d2f = (float)d2;
+    y = __frsqrt_rn(d2f);
+    const double s0 = (double)(d2f * y);                   // sqrt(d2) to ~2e-7
+    const double res = fma(-s0, s0, d2);                   // exact residual
+    const double s1 = fma(res, (double)(0.5f * y), s0);    // one Newton step: ~1e-13 relative
+    const double t = fma(s1, w.k_fs_c, 0.5);
+    const double frac = __builtin_amdgcn_fract(t);
+    int idx = (int)t;
+    if (fabs(frac - 0.5) > 0.5 - w.guard) idx = exact_tap(d2, w.k_fs_c);
+    return idx;
+}
+
+template <bool COUNT>
+__device__ inline void deposit(const WalkCtx& w, int idx, float x, unsigned long long* hist, unsigned int* hist32) {
+    const unsigned int rel = (unsigned int)(idx - w.n0);
+    if (rel >= (unsigned int)w.n_taps) return;
+    if (COUNT) {
+        atomicAdd(&hist32[rel], 1u);
+    } else {
+        // x = amplitude * 2^24; amplitude * 2^56 as a 64-bit integer from two exact fp32 scalings
+        const float fr = __builtin_amdgcn_fractf(x);
+        const unsigned int hi = (unsigned int)x;
+        const unsigned int lo = (unsigned int)(fr * 4294967296.0f);
+        atomicAdd(&hist[rel], ((unsigned long long)hi << 32) | lo);
+    }
+}
+
+template <bool COUNT>
+__device__ inline void walk_piece_table(const WalkCtx& w, double a, float cxy, const ZEntry* z, int len,
+                                        unsigned long long* hist, unsigned int* hist32) {
+    for (int i = 0; i < len; ++i) {
+        const ZEntry e = z[i];
+        const double d2 = __dadd_rn(a, e.dz2);
+        float y;
+        const int idx = tap_index(w, d2, y);
+        deposit<COUNT>(w, idx, (e.bz * y) * cxy, hist, hist32);
+    }
+}
+
+template <bool COUNT>
+__device__ inline void walk_piece_direct(const WalkCtx& w, const Axis& az, double a, float cxy, int q, int first,
+                                         int len, unsigned long long* hist, unsigned int* hist32) {
+    for (int i = 0; i < len; ++i) {
+        const int n = first + i;
+        const double dz = axis_delta(az, q, n);
+        const double d2 = __dadd_rn(a, __dmul_rn(dz, dz));
+        float y;
+        const int idx = tap_index(w, d2, y);
+        float bz = 0.f;
+        if (!COUNT) bz = (float)pow(w.beta, (double)(iabs(n - q) + iabs(n)));
+        deposit<COUNT>(w, idx, (bz * y) * cxy, hist, hist32);
+    }
+}
+
 template <bool COUNT>
 __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
     const float* __restrict__ geom, int rir_len, double k_fs_c, const Item* __restrict__ items,
@@ -131,6 +207,7 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
     int32_t* __restrict__ cnt_out) {
     __shared__ unsigned long long hist[COUNT ? kMaxTaps / 2 : kMaxTaps];
     __shared__ float bpow[COUNT ? 1 : kPow];
+    __shared__ ZEntry ztab[2 * kZCap];
     __shared__ Column cols[kWaves][64];
     __shared__ int s_item;
     unsigned int* hist32 = reinterpret_cast<unsigned int*>(hist);
@@ -166,12 +243,39 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
             const double r_out2 = r_out * r_out, r_in2 = r_in * r_in;
             const int nmx = (int)ceil(r_out / (2.0 * ax.room)) + 1;
             const int nmy = (int)ceil(r_out / (2.0 * ay.room)) + 1;
+            const int nmz = (int)ceil(r_out / (2.0 * az.room)) + 1;
             const int nix = 2 * (2 * nmx + 1), niy = 2 * (2 * nmy + 1);
             const int n_cand = nix * niy;
             const double inv_two_lz = 1.0 / (2.0 * az.room);
             const double z0q[2] = {__dsub_rn(az.src, az.mic), __dsub_rn(__dmul_rn(-1.0, az.src), az.mic)};
             const int n_batch = (n_cand + 63) / 64;
             Column* wc = cols[wave];
+            WalkCtx wctx;
+            wctx.k_fs_c = k_fs_c;
+            wctx.guard = 1e-12 * (double)(n1 + 1) + 1e-13;
+            wctx.n0 = n0;
+            wctx.n_taps = n_taps;
+            wctx.beta = beta;
+
+            // z images of this response: (dz*dz, beta^reflections) per (q, n), shared by every column
+            const bool use_table = 2 * nmz + 1 <= kZCap;
+            if (use_table) {
+                const int per_q = 2 * nmz + 1;
+                for (int i = tid; i < 2 * per_q; i += kThreads) {
+                    const int q = i >= per_q, n = i - q * per_q - nmz;
+                    const double dz = axis_delta(az, q, n);
+                    ZEntry e;
+                    e.dz2 = __dmul_rn(dz, dz);
+                    e.bz = 0.f;
+                    if (!COUNT) {
+                        const int k = iabs(n - q) + iabs(n);
+                        e.bz = k < kPow ? bpow[k] : (float)pow(beta, (double)k);
+                    }
+                    e.pad = 0.f;
+                    ztab[q * kZCap + n + nmz] = e;
+                }
+            }
+            __syncthreads();
 
             for (int batch = wave; batch < n_batch; batch += kWaves) {
                 // ---- each lane describes one candidate column ----
@@ -243,43 +347,13 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
                     const int q = run >> 1;
                     const int first = r_start + local * kPiece;
                     const int len = min(kPiece, r_len - local * kPiece);
-
-                    for (int i = 0; i < len; ++i) {
-                        const int n = first + i;
-                        const double dz = axis_delta(az, q, n);
-                        const double d2 = __dadd_rn(c.a, __dmul_rn(dz, dz));
-                        // estimate: y ~ 1/sqrt(d2) in fp32, one Newton step in fp64
-                        const float d2f = (float)d2;
-                        const float y = __frsqrt_rn(d2f);
-                        const double s0 = (double)(d2f * y);
-                        const double res = fma(-s0, s0, d2);
-                        const double s1 = fma(res, (double)(0.5f * y), s0);
-                        double t = fma(s1, k_fs_c, 0.5);
-                        double fl = floor(t);
-                        const double frac = t - fl;
-                        // |t - exact| < 1e-12 t for any d2 > 0; closer than that to a boundary: redo exactly
-                        const double guard = 1e-12 * t + 1e-13;
-                        if (frac < guard || frac > 1.0 - guard) {
-                            const double d = __dsqrt_rn(d2);
-                            t = __dadd_rn(__dmul_rn(d, k_fs_c), 0.5);
-                            fl = floor(t);
-                        }
-                        if (!(fl >= (double)n0 && fl < (double)n1)) continue;
-                        const int idx = (int)fl - n0;
-                        if (COUNT) {
-                            atomicAdd(&hist32[idx], 1u);
-                        } else {
-                            const int k = c.kxy + iabs(n - q) + iabs(n);
-                            const float b = k < kPow ? bpow[k] : (float)pow(beta, (double)k);
-                            const float amp = b * (0.07957747154594767f * y);
-                            // amp * 2^56 as a 64-bit integer, from two exact fp32 scalings
-                            const float x = amp * 16777216.0f;
-                            const float xh = floorf(x);
-                            const unsigned int hi = (unsigned int)xh;
-                            const unsigned int lo = (unsigned int)((x - xh) * 4294967296.0f);
-                            atomicAdd(&hist[idx], ((unsigned long long)hi << 32) | lo);
-                        }
-                    }
+                    float cxy = 0.f;       // beta^kxy / (4 pi) * 2^24
+                    if (!COUNT)
+                        cxy = (c.kxy < kPow ? bpow[c.kxy] : (float)pow(beta, (double)c.kxy)) * (0.07957747154594767f * 16777216.0f);
+                    if (use_table)
+                        walk_piece_table<COUNT>(wctx, c.a, cxy, ztab + q * kZCap + first + nmz, len, hist, hist32);
+                    else
+                        walk_piece_direct<COUNT>(wctx, az, c.a, cxy, q, first, len, hist, hist32);
                 }
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
