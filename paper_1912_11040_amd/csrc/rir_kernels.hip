@@ -138,6 +138,16 @@ struct WalkCtx {
     int n0, n_taps;
 };
 
+// Largest reflection count k whose amplitude beta^k / (4 pi d) can still reach one unit of the
+// 2^-56 fixed point at distance d_min or beyond, with a factor-of-two margin and one count of slack;
+// "no limit" when beta is 0, >= 1 (log2_beta == 0 encodes both) or d_min is tiny.
+__device__ inline int reflection_cut(float log2_beta, float d_min) {
+    if (!(log2_beta < 0.f) || !(d_min > 1e-3f)) return 1 << 20;
+    // beta^k >= 4 pi d 2^-57  <=>  k <= (log2(4 pi d) - 57) / log2(beta)
+    const float k = (__log2f(12.566371f * d_min) - 57.f) / log2_beta;
+    return k > 1.0e6f ? (1 << 20) : (int)k + 2;
+}
+
 // the reference recipe, kept out of line so that the estimate's loop stays short
 __device__ __attribute__((noinline)) int exact_tap(double d2, double k_fs_c) {
     const double d = __dsqrt_rn(d2);
@@ -241,9 +251,16 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
             const double r_out = (double)n1 / k_fs_c;
             const double r_in = n0 > 0 ? (double)(n0 - 1) / k_fs_c : 0.0;
             const double r_out2 = r_out * r_out, r_in2 = r_in * r_in;
-            const int nmx = (int)ceil(r_out / (2.0 * ax.room)) + 1;
-            const int nmy = (int)ceil(r_out / (2.0 * ay.room)) + 1;
+            // An image reflected k times adds beta^k / (4 pi d) * 2^56, truncated to an integer, to its
+            // tap; once beta^k < 2 pi d 2^-56 that is exactly zero, so such images are never visited.
+            // log2_beta < 0 enables the cut (amplitude sums only; tap counts visit every image).
+            const float log2_beta = (!COUNT && g[9] > 0.f && g[9] < 1.f) ? __log2f(g[9]) : 0.f;
+            const int k_cut_item = reflection_cut(log2_beta, (float)r_in);
+            int nmx = (int)ceil(r_out / (2.0 * ax.room)) + 1;
+            int nmy = (int)ceil(r_out / (2.0 * ay.room)) + 1;
             const int nmz = (int)ceil(r_out / (2.0 * az.room)) + 1;
+            nmx = min(nmx, k_cut_item / 2 + 1);          // |n - q| + |n| >= 2 |n| - 1
+            nmy = min(nmy, k_cut_item / 2 + 1);
             const int nix = 2 * (2 * nmx + 1), niy = 2 * (2 * nmy + 1);
             const int n_cand = nix * niy;
             const double inv_two_lz = 1.0 / (2.0 * az.room);
@@ -293,16 +310,21 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
                     const double dy = axis_delta(ay, qy, ny);
                     col.a = __dadd_rn(__dmul_rn(dx, dx), __dmul_rn(dy, dy));
                     col.kxy = iabs(nx - qx) + iabs(nx) + iabs(ny - qy) + iabs(ny);
-                    if (col.a < r_out2) {
+                    // reflections left for the z axis before this column's images vanish
+                    const int kz_max = reflection_cut(log2_beta, fmaxf((float)r_in, sqrtf((float)col.a))) - col.kxy;
+                    if (col.a < r_out2 && kz_max >= 0) {
                         const double zout = sqrt(r_out2 - col.a);
                         const double zin = col.a < r_in2 ? sqrt(r_in2 - col.a) : 0.0;
 #pragma unroll
                         for (int q = 0; q < 2; ++q) {
                             const double z0 = z0q[q];
-                            const int lo_n = (int)ceil((-zout - z0) * inv_two_lz - 1e-6);
-                            const int hi_n = (int)floor((-zin - z0) * inv_two_lz + 1e-6);
-                            const int lo_p = (int)ceil((zin - z0) * inv_two_lz - 1e-6);
-                            const int hi_p = (int)floor((zout - z0) * inv_two_lz + 1e-6);
+                            // |n - q| + |n| <= kz_max  <=>  cut_lo <= n <= cut_hi
+                            const int cut_lo = q ? -((kz_max - 1) >> 1) : -(kz_max >> 1);
+                            const int cut_hi = q ? ((kz_max + 1) >> 1) : (kz_max >> 1);
+                            const int lo_n = max((int)ceil((-zout - z0) * inv_two_lz - 1e-6), cut_lo);
+                            const int hi_n = min((int)floor((-zin - z0) * inv_two_lz + 1e-6), cut_hi);
+                            const int lo_p = max((int)ceil((zin - z0) * inv_two_lz - 1e-6), cut_lo);
+                            const int hi_p = min((int)floor((zout - z0) * inv_two_lz + 1e-6), cut_hi);
                             if (hi_n >= lo_p - 1) {            // the two sides touch: one run
                                 col.start[2 * q] = (short)lo_n;
                                 col.len[2 * q] = (short)max(hi_p - lo_n + 1, 0);
