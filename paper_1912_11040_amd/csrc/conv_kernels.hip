@@ -5,7 +5,8 @@
 // (2P-point real FFT); an output block of P samples is the inverse transform of
 // sum_p X_{b-p} H_p, X_w the transform of input samples [(w-1)P, (w+1)P).
 // A 2P-point real transform is run as a P-point complex FFT of the even/odd packed
-// sequence, entirely in LDS; spectra stay in the FFT's digit-reversed order.
+// sequence, entirely in LDS; the first pass reads its inputs straight from HBM and the
+// last inverse pass writes the output block straight back.
 //
 // One work group produces one output block of one (utterance, source), adds the
 // block's energy to E[u][j] (fp64 atomics), and a second kernel forms the gains
@@ -17,7 +18,7 @@
 namespace aug {
 namespace {
 
-constexpr int conv_threads(int n) { return n / 16 > 1024 ? 1024 : (n / 16 < 64 ? 64 : n / 16); }
+constexpr int conv_threads(int n) { return n / 16; }
 
 __global__ void twiddle_kernel(int n, float2* tw) {
     // tw[t] = exp(-2 pi i t / n), t < n;  tw[n + k] = exp(-i pi k / n), k <= n/2
@@ -48,22 +49,26 @@ __global__ __launch_bounds__(T) void rir_spectrum_kernel(
     const int tid = threadIdx.x;
     const int r = blockIdx.x / n_part, p = blockIdx.x % n_part;
     const float* h = rir + (size_t)r * rir_len;
-    for (int n = tid; n < N; n += T) {
-        const int i = p * N + 2 * n;                 // taps of this partition: [pN, (p+1)N)
+    float2 v[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int n = fft_in_index<N, T>(tid, i);
+        const int t = p * N + 2 * n;                 // taps of this partition: [pN, (p+1)N), then N zeros
         float a = 0.f, b = 0.f;
         if (2 * n < N) {
-            if (i < rir_len) a = h[i];
-            if (i + 1 < rir_len) b = h[i + 1];
+            if (t < rir_len) a = h[t];
+            if (t + 1 < rir_len) b = h[t + 1];
         }
-        buf[lds_pad(n)] = make_float2(a, b);
+        v[i] = make_float2(a, b);
     }
+    fft_passes<N, T, false>(v, buf, tw, tid);
+    fft_store_natural<N, T>(v, buf, tid);
     __syncthreads();
-    fft_forward<N, T>(buf, tw, tid);
     float2* out = spec + ((size_t)r * n_part + p) * (N + 1);
     const float scale = 1.0f / (float)N;             // the inverse transform's normalisation
     for (int k = tid; k <= N / 2; k += T) {
-        const float2 A = buf[lds_pad(FftPlan<N>::position(k))];
-        const float2 B = cconj(buf[lds_pad(FftPlan<N>::position((N - k) & (N - 1)))]);
+        const float2 A = buf[lds_pad(k)];
+        const float2 B = cconj(buf[lds_pad((N - k) & (N - 1))]);
         float2 Hk, HNk_conj;
         unpack_pair(A, B, tw[N + k], Hk, HNk_conj);
         out[k] = make_float2(Hk.x * scale, Hk.y * scale);
@@ -71,12 +76,27 @@ __global__ __launch_bounds__(T) void rir_spectrum_kernel(
     }
 }
 
-template <int N, int T>
+// Z'[k] and Z'[N-k] of the packed output block from Z[k] = A, conj(Z[N-k]) = B and the response
+// spectrum: Y = W H on the 2N-point real transform, repacked for the N-point inverse.
+__device__ inline void multiply_pair(float2 A, float2 B, float2 w, float2 Hk, float2 HNk, float2& Zk, float2& ZNk) {
+    float2 Wk, WNk_conj;
+    unpack_pair(A, B, w, Wk, WNk_conj);
+    const float2 Yk = cmul(Hk, Wk);
+    const float2 YNk_conj = cmul_conj(WNk_conj, HNk);
+    const float2 Ye = make_float2(0.5f * (Yk.x + YNk_conj.x), 0.5f * (Yk.y + YNk_conj.y));
+    const float2 dY = make_float2(0.5f * (Yk.x - YNk_conj.x), 0.5f * (Yk.y - YNk_conj.y));
+    const float2 Yo = cmul_conj(dY, w);              // conj(w) (Y[k] - conj Y[N-k]) / 2
+    Zk = make_float2(Ye.x - Yo.y, Ye.y + Yo.x);      // Ye + i Yo
+    ZNk = make_float2(Ye.x + Yo.y, Yo.x - Ye.y);     // conj(Ye) + i conj(Yo)
+}
+
+// MULTI: the response has several partitions and the products are summed in registers.
+template <int N, int T, bool MULTI>
 __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* __restrict__ tw) {
     extern __shared__ float2 buf[];
     __shared__ double red[T / 64];
     constexpr int PAIRS = (N / 2) / T;               // bins k = tid + i T, k < N/2, each with N-k
-    static_assert(PAIRS >= 1 && PAIRS * T == N / 2, "thread count must divide N/2");
+    static_assert(PAIRS == 8, "sixteen values per thread");
     const int tid = threadIdx.x;
     const int64_t item = blockIdx.x / a.n_src;
     const int j = blockIdx.x % a.n_src;
@@ -86,67 +106,74 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
     const float* x = (j == 0 ? a.speech : a.noise + (size_t)(j - 1) * a.total) + start;
     const float2* H = a.spec + ((size_t)u * a.n_src + j) * a.n_part * (size_t)(N + 1);
 
-    float2 accK[PAIRS + 1], accN[PAIRS];             // Z'[k], Z'[N-k]; last accK is k = N/2
+    float2 accK[MULTI ? PAIRS + 1 : 1], accN[MULTI ? PAIRS : 1];   // Z'[k], Z'[N-k]; last accK is k = N/2
+    if (MULTI) {
 #pragma unroll
-    for (int i = 0; i < PAIRS; ++i) accK[i] = accN[i] = make_float2(0.f, 0.f);
-    accK[PAIRS] = make_float2(0.f, 0.f);
+        for (int i = 0; i < PAIRS; ++i) accK[i] = accN[i] = make_float2(0.f, 0.f);
+        accK[PAIRS] = make_float2(0.f, 0.f);
+    }
 
-    for (int p = 0; p < a.n_part; ++p) {
+    float2 v[16];
+    const int n_part = MULTI ? a.n_part : 1;
+    for (int p = 0; p < n_part; ++p) {
         const int wb = b - p;                        // input window [(wb-1)N, (wb+1)N)
         if (wb < 0) break;
         const int64_t w0 = ((int64_t)wb - 1) * N;
-        for (int n = tid; n < N; n += T) {
-            const int64_t g = w0 + 2 * n;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int64_t g = w0 + 2 * fft_in_index<N, T>(tid, i);
             const float x0 = (g >= 0 && g < len) ? x[g] : 0.f;
             const float x1 = (g + 1 >= 0 && g + 1 < len) ? x[g + 1] : 0.f;
-            buf[lds_pad(n)] = make_float2(x0, x1);
+            v[i] = make_float2(x0, x1);
         }
+        if (MULTI && p > 0) __syncthreads();         // the previous partition's pair reads are done
+        fft_passes<N, T, false>(v, buf, tw, tid);
+        fft_store_natural<N, T>(v, buf, tid);
         __syncthreads();
-        fft_forward<N, T>(buf, tw, tid);
         const float2* Hp = H + (size_t)p * (N + 1);
 #pragma unroll
         for (int i = 0; i <= PAIRS; ++i) {
             if (i == PAIRS && tid != 0) break;
             const int k = i == PAIRS ? N / 2 : tid + i * T;
-            const float2 A = buf[lds_pad(FftPlan<N>::position(k))];
-            const float2 B = cconj(buf[lds_pad(FftPlan<N>::position((N - k) & (N - 1)))]);
-            const float2 w = tw[N + k];
-            float2 Wk, WNk_conj;
-            unpack_pair(A, B, w, Wk, WNk_conj);
-            const float2 Yk = cmul(Hp[k], Wk);
-            const float2 YNk_conj = cmul_conj(WNk_conj, Hp[N - k]);
-            const float2 Ye = make_float2(0.5f * (Yk.x + YNk_conj.x), 0.5f * (Yk.y + YNk_conj.y));
-            const float2 dY = make_float2(0.5f * (Yk.x - YNk_conj.x), 0.5f * (Yk.y - YNk_conj.y));
-            const float2 Yo = cmul_conj(dY, w);      // conj(w) (Y[k] - conj Y[N-k]) / 2
-            accK[i].x += Ye.x - Yo.y;                // Ye + i Yo
-            accK[i].y += Ye.y + Yo.x;
-            if (i < PAIRS) {                         // conj(Ye) + i conj(Yo)
-                accN[i].x += Ye.x + Yo.y;
-                accN[i].y += Yo.x - Ye.y;
+            const int kn = (N - k) & (N - 1);
+            const float2 A = buf[lds_pad(k)];
+            const float2 B = cconj(buf[lds_pad(kn)]);
+            float2 Zk, ZNk;
+            multiply_pair(A, B, tw[N + k], Hp[k], Hp[N - k], Zk, ZNk);
+            if (MULTI) {
+                accK[i == PAIRS ? PAIRS : i] = cadd(accK[i == PAIRS ? PAIRS : i], Zk);
+                if (i < PAIRS) accN[i] = cadd(accN[i], ZNk);
+            } else {                                 // positions k and N-k belong to this thread alone
+                buf[lds_pad(k)] = Zk;
+                if (k != 0 && i < PAIRS) buf[lds_pad(kn)] = ZNk;
             }
         }
-        __syncthreads();
     }
-
+    if (MULTI) {
 #pragma unroll
-    for (int i = 0; i < PAIRS; ++i) {
-        const int k = tid + i * T;
-        buf[lds_pad(FftPlan<N>::position(k))] = accK[i];
-        if (k != 0) buf[lds_pad(FftPlan<N>::position(N - k))] = accN[i];
+        for (int i = 0; i < PAIRS; ++i) {
+            const int k = tid + i * T;
+            buf[lds_pad(k)] = accK[i];
+            if (k != 0) buf[lds_pad(N - k)] = accN[i];
+        }
+        if (tid == 0) buf[lds_pad(N / 2)] = accK[PAIRS];
     }
-    if (tid == 0) buf[lds_pad(FftPlan<N>::position(N / 2))] = accK[PAIRS];
     __syncthreads();
-    fft_inverse<N, T>(buf, tw, tid);
+    fft_load_natural<N, T>(v, buf, tid);
+    __syncthreads();
+    fft_passes<N, T, true>(v, buf, tw, tid);
 
     // the last N real samples of the 2N-sample window are this block's outputs
     float* y = a.reverb + (size_t)j * a.total + start;
     const int64_t out0 = (int64_t)b * N;
     float e = 0.f;
-    for (int n = tid; n < N / 2; n += T) {
-        const float2 v = buf[lds_pad(N / 2 + n)];
-        const int64_t g = out0 + 2 * n;
-        if (g < len) { y[g] = v.x; e += v.x * v.x; }
-        if (g + 1 < len) { y[g + 1] = v.y; e += v.y * v.y; }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int n = fft_out_index<N, T>(tid, i);
+        if (n < N / 2) continue;
+        const int64_t g = out0 + 2 * (n - N / 2);
+        if (g < len) { y[g] = v[i].x; e += v[i].x * v[i].x; }
+        if (g + 1 < len) { y[g + 1] = v[i].y; e += v[i].y * v[i].y; }
     }
     double es = (double)e;
     for (int off = 32; off > 0; off >>= 1) es += __shfl_down(es, off, 64);
@@ -210,7 +237,7 @@ template <int N>
 hipError_t convolve_n(hipStream_t s, const float2* tw, const ConvArgs& a) {
     constexpr int T = conv_threads(N);
     const size_t lds = sizeof(float2) * lds_padded_size(N);
-    auto k = &convolve_kernel<N, T>;
+    auto k = a.n_part > 1 ? &convolve_kernel<N, T, true> : &convolve_kernel<N, T, false>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
@@ -221,7 +248,7 @@ hipError_t convolve_n(hipStream_t s, const float2* tw, const ConvArgs& a) {
 }  // namespace
 
 int conv_fft_size(int rir_len) {
-    int n = 256;
+    int n = 1024;                       // at least one full wave of sixteen-point butterflies
     while (n < rir_len && n < 16384) n <<= 1;
     return n;
 }
@@ -234,8 +261,6 @@ hipError_t launch_twiddle(hipStream_t s, int n, float2* tw) {
 
 #define AUG_FFT_DISPATCH(n, CALL)                                  \
     switch (n) {                                                   \
-        case 256: return CALL(256);                                \
-        case 512: return CALL(512);                                \
         case 1024: return CALL(1024);                              \
         case 2048: return CALL(2048);                              \
         case 4096: return CALL(4096);                              \

@@ -1,17 +1,18 @@
-// In-place complex FFT of a power-of-two length held in LDS, shared by the
-// overlap-save convolution (lengths 256..16384) and the STFT (length nfft/2).
+// Complex FFT of a power-of-two length N held in LDS and worked on by T = N/16 threads,
+// shared by the overlap-save convolution (N = 256..16384) and the STFT (N = nfft/2).
 //
-// Forward: decimation in frequency, natural order in, digit-reversed order out.
-// Inverse: decimation in time, digit-reversed order in, natural order out, no 1/N.
-// A convolution multiplies spectra in the permuted order, so no reordering pass is
-// ever run; FftPlan<N>::position(k) says where frequency k sits.
+// Stockham autosort passes: a pass of radix R over sub-transforms of length NS reads, for
+// butterfly j < N/R, x[j + m N/R] (m < R), multiplies by exp(-+2 pi i (j mod NS) m / (NS R)),
+// takes an R-point DFT and writes y[(j div NS) NS R + (j mod NS) + r NS].  Input and output
+// are in natural order.  The transform runs in place: every thread keeps its 16 values of a
+// pass in registers, so all reads of a pass complete (barrier) before its writes begin.
+// Radix 16 while four or more bits remain, then radix 4 and/or 2.
 //
-// Passes use radix 16 (two radix-4 layers in registers) while four or more bits
-// remain, then one radix-4 and/or one radix-2 pass.  Twiddles come from a table
-// exp(-2 pi i t / N) rounded once from fp64.
+// Twiddles: one table value w = exp(-2 pi i t / N) per butterfly; its powers are formed by
+// at most four successive complex products.  The inverse uses conjugates and is unscaled.
 //
-// LDS addressing is padded by one complex per 16 so that the stride-16 accesses of
-// the late passes spread over banks: element i lives at lds_pad(i).
+// LDS addressing is padded by one complex per 16 (element i lives at lds_pad(i)) so that both
+// the unit-stride reads and the stride-NS writes of every pass spread over all banks.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -46,11 +47,11 @@ __device__ inline void dft4(float2& a0, float2& a1, float2& a2, float2& a3) {
     a3 = csub(d02, d13);
 }
 
-// R-point DFT of v[0..R) in registers, natural order in and out.
+// R-point DFT of v[0..R), natural order in and out.
 template <int R, bool INV> struct SmallDft;
 
 template <bool INV> struct SmallDft<2, INV> {
-    __device__ static inline void run(float2 (&v)[2]) {
+    __device__ static inline void run(float2* v) {
         const float2 a = v[0], b = v[1];
         v[0] = cadd(a, b);
         v[1] = csub(a, b);
@@ -58,13 +59,13 @@ template <bool INV> struct SmallDft<2, INV> {
 };
 
 template <bool INV> struct SmallDft<4, INV> {
-    __device__ static inline void run(float2 (&v)[4]) { dft4<INV>(v[0], v[1], v[2], v[3]); }
+    __device__ static inline void run(float2* v) { dft4<INV>(v[0], v[1], v[2], v[3]); }
 };
 
 template <bool INV> struct SmallDft<16, INV> {
     // m = m2 + 4 m1, r = r1 + 4 r2:
     // y[r1 + 4 r2] = sum_{m2} W4^{m2 r2} W16^{m2 r1} sum_{m1} x[m2 + 4 m1] W4^{m1 r1}
-    __device__ static inline void run(float2 (&v)[16]) {
+    __device__ static inline void run(float2* v) {
         constexpr float c1 = 0.92387953251128674f, s1 = 0.38268343236508977f;   // cos, sin(pi/8)
         constexpr float h = 0.70710678118654752f;
         // W16^e = exp(-2 pi i e / 16) for e = 0..9 (forward sign)
@@ -81,11 +82,8 @@ template <bool INV> struct SmallDft<16, INV> {
             }
         }
 #pragma unroll
-        for (int r1 = 0; r1 < 4; ++r1) {
-            // inputs t[m2][r1] sit at v[m2 + 4 r1]; outputs y[r1 + 4 r2] -> gather below
-            dft4<INV>(v[4 * r1 + 0], v[4 * r1 + 1], v[4 * r1 + 2], v[4 * r1 + 3]);  // v[4 r1 + r2]
-        }
-        // v[4 r1 + r2] holds y[r1 + 4 r2]: transpose the 4x4 index to natural order
+        for (int r1 = 0; r1 < 4; ++r1)
+            dft4<INV>(v[4 * r1 + 0], v[4 * r1 + 1], v[4 * r1 + 2], v[4 * r1 + 3]);  // v[4 r1 + r2] = y[r1 + 4 r2]
 #pragma unroll
         for (int r1 = 0; r1 < 4; ++r1)
 #pragma unroll
@@ -97,116 +95,127 @@ template <bool INV> struct SmallDft<16, INV> {
     }
 };
 
+// v[m] *= w^m for m = 1..R-1, powers by products of depth <= 4
+template <int R> __device__ inline void twiddle_inputs(float2* v, float2 w1) {
+    if constexpr (R == 2) {
+        v[1] = cmul(v[1], w1);
+    } else if constexpr (R == 4) {
+        const float2 w2 = cmul(w1, w1), w3 = cmul(w2, w1);
+        v[1] = cmul(v[1], w1);
+        v[2] = cmul(v[2], w2);
+        v[3] = cmul(v[3], w3);
+    } else {
+        static_assert(R == 16, "radix");
+        float2 w[16];
+        w[1] = w1;
+        w[2] = cmul(w1, w1);
+        w[3] = cmul(w[2], w1);
+        w[4] = cmul(w[2], w[2]);
+        w[5] = cmul(w[4], w1);
+        w[6] = cmul(w[4], w[2]);
+        w[7] = cmul(w[4], w[3]);
+        w[8] = cmul(w[4], w[4]);
+#pragma unroll
+        for (int m = 9; m < 16; ++m) w[m] = cmul(w[8], w[m - 8]);
+#pragma unroll
+        for (int m = 1; m < 16; ++m) v[m] = cmul(v[m], w[m]);
+    }
+}
+
 constexpr int ilog2(int n) { return n <= 1 ? 0 : 1 + ilog2(n >> 1); }
 
 template <int N>
 struct FftPlan {
     static constexpr int kLog = ilog2(N);
-    static constexpr int kN16 = kLog / 4;          // radix-16 passes
-    static constexpr int kRem = kLog % 4;          // remaining bits: 0..3
-    static constexpr bool kHas4 = kRem >= 2;
-    static constexpr bool kHas2 = (kRem & 1) != 0;
-
-    // Where frequency k sits after the forward transform: digits of k, least
-    // significant first in the order the passes ran, become the most significant
-    // digits of the position.
-    __device__ __host__ static inline int position(int k) {
-        int pos = 0, rest = N;
-        for (int p = 0; p < kN16; ++p) {
-            rest >>= 4;
-            pos += (k & 15) * rest;
-            k >>= 4;
-        }
-        if (kHas4) {
-            rest >>= 2;
-            pos += (k & 3) * rest;
-            k >>= 2;
-        }
-        if (kHas2) {
-            rest >>= 1;
-            pos += (k & 1) * rest;
-        }
-        return pos;
+    static constexpr int kN16 = kLog / 4;
+    static constexpr int kRem = kLog % 4;
+    static constexpr int kPasses = kN16 + (kRem >= 2 ? 1 : 0) + (kRem & 1);
+    static constexpr int radix(int p) { return p < kN16 ? 16 : ((p == kN16 && kRem >= 2) ? 4 : 2); }
+    static constexpr int ns(int p) {
+        int s = 1;
+        for (int i = 0; i < p; ++i) s *= radix(i);
+        return s;
     }
+    static constexpr int kLastRadix = radix(kPasses - 1);
 };
 
-// One pass over blocks of length S with radix R (sub-block length Q = S / R).
-// Forward (DIF):  y_r = W_S^{j r} sum_m x[j + m Q] W_R^{m r}       -> stored at j + r Q
-// Inverse (DIT):  x_m = sum_r (conj(W_S^{j r}) y[j + r Q]) W_R^{-m r} -> stored at j + m Q
-template <int N, int S, int R, bool INV, int T>
-__device__ inline void fft_pass(float2* buf, const float2* __restrict__ tw, int tid) {
-    constexpr int Q = S / R;
-    constexpr int kStep = N / S;        // W_S = W_N^kStep
-    for (int b = tid; b < N / R; b += T) {
-        const int blk = b / Q, j = b % Q;
-        const int base = blk * S + j;
-        float2 v[R];
+// Each thread owns 16 values per pass: 16 / R butterflies j = tid + bi T.
+template <int N, int T, int R>
+__device__ inline void fft_load(float2 (&v)[16], const float2* buf, int tid) {
+    static_assert(N == 16 * T, "sixteen values per thread");
 #pragma unroll
-        for (int m = 0; m < R; ++m) v[m] = buf[lds_pad(base + m * Q)];
-        if (INV && Q > 1) {
+    for (int bi = 0; bi < 16 / R; ++bi)
 #pragma unroll
-            for (int r = 1; r < R; ++r) v[r] = cmul_conj(v[r], tw[(j * r * kStep) & (N - 1)]);
-        }
-        SmallDft<R, INV>::run(v);
-        if (!INV && Q > 1) {
+        for (int m = 0; m < R; ++m) v[bi * R + m] = buf[lds_pad(tid + bi * T + m * (N / R))];
+}
+
+template <int N, int T, int R, int NS>
+__device__ inline void fft_store(const float2 (&v)[16], float2* buf, int tid) {
 #pragma unroll
-            for (int r = 1; r < R; ++r) v[r] = cmul(v[r], tw[(j * r * kStep) & (N - 1)]);
-        }
+    for (int bi = 0; bi < 16 / R; ++bi) {
+        const int j = tid + bi * T;
+        const int k = j % NS;
+        const int j0 = (j / NS) * NS * R + k;
 #pragma unroll
-        for (int m = 0; m < R; ++m) buf[lds_pad(base + m * Q)] = v[m];
+        for (int r = 0; r < R; ++r) buf[lds_pad(j0 + r * NS)] = v[bi * R + r];
     }
 }
 
-template <int N, int S, int P, bool INV, int T>
-struct Fft16Chain {     // P radix-16 passes left, current block length S
-    __device__ static inline void fwd(float2* buf, const float2* tw, int tid) {
-        if constexpr (P > 0) {
-            fft_pass<N, S, 16, false, T>(buf, tw, tid);
-            __syncthreads();
-            Fft16Chain<N, S / 16, P - 1, INV, T>::fwd(buf, tw, tid);
+template <int N, int T, int R, int NS, bool INV>
+__device__ inline void fft_compute(float2 (&v)[16], const float2* __restrict__ tw, int tid) {
+#pragma unroll
+    for (int bi = 0; bi < 16 / R; ++bi) {
+        if constexpr (NS > 1) {
+            const int k = (tid + bi * T) % NS;
+            float2 w1 = tw[k * (N / (NS * R))];
+            if (INV) w1.y = -w1.y;
+            twiddle_inputs<R>(&v[bi * R], w1);
         }
-    }
-    __device__ static inline void inv(float2* buf, const float2* tw, int tid) {
-        if constexpr (P > 0) {
-            Fft16Chain<N, S / 16, P - 1, INV, T>::inv(buf, tw, tid);
-            fft_pass<N, S, 16, true, T>(buf, tw, tid);
-            __syncthreads();
-        }
-    }
-};
-
-// Forward transform of buf[lds_pad(0..N)) by the T threads of the work group (all must call).
-// Data must be visible (barrier) before the call; results are visible after it.
-template <int N, int T>
-__device__ inline void fft_forward(float2* buf, const float2* __restrict__ tw, int tid) {
-    using Plan = FftPlan<N>;
-    Fft16Chain<N, N, Plan::kN16, false, T>::fwd(buf, tw, tid);
-    constexpr int S1 = N >> (4 * Plan::kN16);
-    if constexpr (Plan::kHas4) {
-        fft_pass<N, S1, 4, false, T>(buf, tw, tid);
-        __syncthreads();
-    }
-    if constexpr (Plan::kHas2) {
-        constexpr int S2 = Plan::kHas4 ? S1 / 4 : S1;
-        fft_pass<N, S2, 2, false, T>(buf, tw, tid);
-        __syncthreads();
+        SmallDft<R, INV>::run(&v[bi * R]);
     }
 }
 
+// Natural index of value v[bi R + r] after the last pass, and before the first pass of input v[bi R + m].
 template <int N, int T>
-__device__ inline void fft_inverse(float2* buf, const float2* __restrict__ tw, int tid) {
+__device__ inline int fft_out_index(int tid, int i) {
+    constexpr int R = FftPlan<N>::kLastRadix;
+    return tid + (i / R) * T + (i % R) * (N / R);
+}
+template <int N, int T>
+__device__ inline int fft_in_index(int tid, int i) {
+    constexpr int R = FftPlan<N>::radix(0);
+    return tid + (i / R) * T + (i % R) * (N / R);
+}
+
+// Run passes P.. of the transform.  On entry v holds the inputs of pass P (fft_in_index order for
+// P = 0); on return it holds the outputs of the last pass (fft_out_index order), not yet stored.
+// All T threads of the group must call; buf contents are overwritten.
+template <int N, int T, bool INV, int P = 0>
+__device__ inline void fft_passes(float2 (&v)[16], float2* buf, const float2* __restrict__ tw, int tid) {
     using Plan = FftPlan<N>;
-    constexpr int S1 = N >> (4 * Plan::kN16);
-    if constexpr (Plan::kHas2) {
-        constexpr int S2 = Plan::kHas4 ? S1 / 4 : S1;
-        fft_pass<N, S2, 2, true, T>(buf, tw, tid);
+    constexpr int R = Plan::radix(P), NS = Plan::ns(P);
+    fft_compute<N, T, R, NS, INV>(v, tw, tid);
+    if constexpr (P + 1 < Plan::kPasses) {
+        fft_store<N, T, R, NS>(v, buf, tid);
         __syncthreads();
-    }
-    if constexpr (Plan::kHas4) {
-        fft_pass<N, S1, 4, true, T>(buf, tw, tid);
+        fft_load<N, T, Plan::radix(P + 1)>(v, buf, tid);
         __syncthreads();
+        fft_passes<N, T, INV, P + 1>(v, buf, tw, tid);
     }
-    Fft16Chain<N, N, Plan::kN16, true, T>::inv(buf, tw, tid);
+}
+
+// Store the last pass's outputs in natural order.
+template <int N, int T>
+__device__ inline void fft_store_natural(const float2 (&v)[16], float2* buf, int tid) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) buf[lds_pad(fft_out_index<N, T>(tid, i))] = v[i];
+}
+
+// Load the first pass's inputs from a natural-order buffer.
+template <int N, int T>
+__device__ inline void fft_load_natural(float2 (&v)[16], const float2* buf, int tid) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v[i] = buf[lds_pad(fft_in_index<N, T>(tid, i))];
 }
 
 }  // namespace aug

@@ -80,30 +80,40 @@ __global__ __launch_bounds__(kMelThreads) void mel_kernel(MelArgs a, const float
     float2* buf = fft_buf[slot];
     float* acc = mel_acc[slot];
 
+    // this lane's window samples never change: z[n] = w[2n] x[2n] + i w[2n+1] x[2n+1], n = sub + 16 m
+    float2 wnd[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int i0 = 2 * fft_in_index<NC, kLanes>(sub, i);
+        wnd[i] = make_float2(i0 < win ? a.window[i0] : 0.f, i0 + 1 < win ? a.window[i0 + 1] : 0.f);
+    }
+
     for (int it = 0; it < a.frames_per_group / kSlots; ++it) {
         const int64_t t = (int64_t)first + it * kSlots + slot;
         const bool live = t < n_frames_u;
-        // z[n] = w[2n] x[2n] + i w[2n+1] x[2n+1]
-        for (int n = sub; n < NC; n += kLanes) {
+        float2 v[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int i0 = 2 * fft_in_index<NC, kLanes>(sub, i);
             float re = 0.f, im = 0.f;
             if (live) {
-                const int i0 = 2 * n;
-                if (i0 < win) re = x[t * hop + i0] * a.window[i0];
-                if (i0 + 1 < win) im = x[t * hop + i0 + 1] * a.window[i0 + 1];
+                if (i0 < win) re = x[t * hop + i0] * wnd[i].x;
+                if (i0 + 1 < win) im = x[t * hop + i0 + 1] * wnd[i].y;
             }
-            buf[lds_pad(n)] = make_float2(re, im);
+            v[i] = make_float2(re, im);
         }
         for (int m = sub; m < n_mel; m += kLanes) acc[m] = 0.f;
+        fft_passes<NC, kLanes, false>(v, buf, tw, sub);
+        fft_store_natural<NC, kLanes>(v, buf, sub);
         __syncthreads();
-        fft_forward<NC, kLanes>(buf, tw, sub);
 
         // bins sub*16 .. sub*16+15, and bin NC on the last lane
         for (int i = 0; i < kBinsPerLane + 1; ++i) {
             if (i == kBinsPerLane && sub != kLanes - 1) break;
             const int k = i == kBinsPerLane ? NC : sub * kBinsPerLane + i;
             const int kk = k & (NC - 1);
-            const float2 A = buf[lds_pad(FftPlan<NC>::position(kk))];
-            const float2 Bc = buf[lds_pad(FftPlan<NC>::position((NC - kk) & (NC - 1)))];
+            const float2 A = buf[lds_pad(kk)];
+            const float2 Bc = buf[lds_pad((NC - kk) & (NC - 1))];
             const float2 w = k <= NC / 2 ? tw[NC + k]
                                          : make_float2(-tw[NC + (NC - k)].x, tw[NC + (NC - k)].y);
             // X[k] = E + w O,  E = (A + conj B)/2,  O = -(i/2)(A - conj B)
