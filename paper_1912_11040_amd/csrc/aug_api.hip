@@ -281,7 +281,7 @@ int run_mel(aug_ctx* ctx, int n_utt, const float* wave, const float* alpha, cons
         AUG_HIP(aug::launch_window(ctx->stream, cfg->win, ctx->window.as<float>()), "window kernel");
         ctx->window_n = cfg->win;
     }
-    AUG_HIP(ctx->mel_tab.reserve(sizeof(float2) * (size_t)n_utt * (cfg->nfft / 2 + 1)), "mel table");
+    AUG_HIP(ctx->mel_tab.reserve(sizeof(float2) * (size_t)n_utt * aug::mel_table_stride(cfg->nfft)), "mel table");
     AUG_TRY(mark(ctx, -1));
     AUG_HIP(aug::launch_mel_table(ctx->stream, n_utt, alpha, *cfg, ctx->mel_tab.as<float2>()), "mel table kernel");
     aug::MelArgs ma;

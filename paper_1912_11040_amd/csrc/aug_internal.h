@@ -113,7 +113,9 @@ hipError_t launch_mix(hipStream_t s, int n_utt, const int64_t* d_offsets, int64_
                       const float* reverb, const double* energy, const float* snr_db,
                       float* mixed_out, float* gains_out, int64_t max_len);
 
-// Per-utterance (channel, weight) table of the warped mel bank: tab float2 [n_utt][nfft/2+1].
+// Per-utterance (band, weight) table of the warped mel bank followed by the lane partition of the
+// bins: tab float2 [n_utt][mel_table_stride(nfft)].
+int mel_table_stride(int nfft);
 hipError_t launch_mel_table(hipStream_t s, int n_utt, const float* alpha, const aug_frontend_cfg& cfg,
                             float2* tab);
 

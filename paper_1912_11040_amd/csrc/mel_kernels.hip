@@ -29,7 +29,7 @@ __global__ void window_kernel(int win, float* w) {
 }
 
 __global__ void mel_table_kernel(int n_utt, const float* __restrict__ alpha, aug_frontend_cfg cfg,
-                                 float2* __restrict__ tab) {
+                                 int stride, float2* __restrict__ tab) {
     const int bins = cfg.nfft / 2 + 1;
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n_utt * bins) return;
@@ -55,46 +55,89 @@ __global__ void mel_table_kernel(int n_utt, const float* __restrict__ alpha, aug
         ch = (float)c;
         wgt = (float)w;
     }
-    tab[i] = make_float2(ch, wgt);
+    tab[(size_t)u * stride + k] = make_float2(ch, wgt);
 }
+
+// Cut the bins of one utterance into 16 contiguous lane ranges that end on changes of the band
+// index c, so that every (c, utterance) sum is formed by one lane alone; ranges aim at equal sizes.
+__global__ void mel_partition_kernel(int n_utt, int bins, int stride, float2* __restrict__ tab) {
+    const int u = blockIdx.x * blockDim.x + threadIdx.x;
+    if (u >= n_utt) return;
+    const float2* t = tab + (size_t)u * stride;
+    int* kstart = reinterpret_cast<int*>(tab + (size_t)u * stride + bins);
+    int start = 0;
+    kstart[0] = 0;
+    for (int lane = 0; lane < 15; ++lane) {
+        const int ideal = ((lane + 1) * bins + 8) / 16;
+        int lo = -1, hi = bins;                       // nearest band changes at or below / above ideal
+        for (int k = start + 1; k < bins; ++k) {
+            if (t[k].x != t[k - 1].x) {
+                if (k <= ideal) lo = k;
+                else { hi = k; break; }
+            }
+        }
+        int end = (lo > start && (ideal - lo) <= (hi - ideal)) ? lo : hi;
+        if (end < start) end = start;
+        kstart[lane + 1] = end;
+        start = end;
+    }
+    kstart[16] = bins;
+}
+
+constexpr int kMelLanes = 16;                            // lanes per frame
+constexpr int kMelSlots = kMelThreads / kMelLanes;       // frames in flight per work group
 
 // K = 512: 256-point complex FFT per frame, 16 lanes per frame, 16 frames per pass of the group.
 template <int NC>
-__global__ __launch_bounds__(kMelThreads) void mel_kernel(MelArgs a, const float2* __restrict__ tw) {
-    constexpr int kLanes = NC / 16;                      // lanes per frame
-    constexpr int kSlots = kMelThreads / kLanes;         // frames in flight
-    constexpr int kBinsPerLane = NC / kLanes;            // contiguous bins per lane (16)
-    __shared__ float2 fft_buf[kSlots][lds_padded_size(NC)];
-    __shared__ float mel_acc[kSlots][AUG_MAX_MEL];
+__global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const float2* __restrict__ tw, int tab_stride) {
+    static_assert(NC / 16 == kMelLanes, "sixteen lanes per frame");
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int n_mel = a.cfg.n_mel;
+    const int n_seg = n_mel + 2;                         // band sums A[c], B[c] for c = 0..n_mel (+1 pad)
+    float2* fft_buf = reinterpret_cast<float2*>(smem);                       // [slots][padded NC]
+    float2* s_tab = fft_buf + kMelSlots * lds_padded_size(NC);               // [NC + 1]: (c, w) per bin
+    float2* s_tw = s_tab + (NC + 1);                                         // [NC + 1]: exp(-i pi k / NC)
+    float* s_ab = reinterpret_cast<float*>(s_tw + (NC + 1));                 // [slots][2][n_seg]
+    int* s_kstart = reinterpret_cast<int*>(s_ab + kMelSlots * 2 * n_seg);    // [17]
 
     const int tid = threadIdx.x;
-    const int slot = tid / kLanes, sub = tid % kLanes;
+    const int slot = tid / kMelLanes, sub = tid % kMelLanes;
     const int u = a.items[blockIdx.x].x;
     const int first = a.items[blockIdx.x].y;
     const int64_t start = a.offsets[u];
     const int64_t n_frames_u = a.frame_offsets[u + 1] - a.frame_offsets[u];
     const float* x = a.wave + start;
-    const float2* tab = a.mel_tab + (size_t)u * (NC + 1);
-    const int win = a.cfg.win, hop = a.cfg.hop, n_mel = a.cfg.n_mel;
+    const int win = a.cfg.win, hop = a.cfg.hop;
+    const float power = a.cfg.power;
     float* feats = a.feats + (size_t)a.frame_offsets[u] * n_mel;
-    float2* buf = fft_buf[slot];
-    float* acc = mel_acc[slot];
+    float2* buf = fft_buf + slot * lds_padded_size(NC);
+    float* A = s_ab + (slot * 2) * n_seg;
+    float* B = A + n_seg;
+
+    const float2* g_tab = a.mel_tab + (size_t)u * tab_stride;
+    for (int k = tid; k <= NC; k += kMelThreads) {
+        s_tab[k] = g_tab[k];
+        s_tw[k] = k <= NC / 2 ? tw[NC + k] : make_float2(-tw[NC + (NC - k)].x, tw[NC + (NC - k)].y);
+    }
+    if (tid < 17) s_kstart[tid] = reinterpret_cast<const int*>(g_tab + (NC + 1))[tid];
 
     // this lane's window samples never change: z[n] = w[2n] x[2n] + i w[2n+1] x[2n+1], n = sub + 16 m
     float2 wnd[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        const int i0 = 2 * fft_in_index<NC, kLanes>(sub, i);
+        const int i0 = 2 * fft_in_index<NC, kMelLanes>(sub, i);
         wnd[i] = make_float2(i0 < win ? a.window[i0] : 0.f, i0 + 1 < win ? a.window[i0 + 1] : 0.f);
     }
+    __syncthreads();
+    const int k_lo = s_kstart[sub], k_hi = s_kstart[sub + 1];
 
-    for (int it = 0; it < a.frames_per_group / kSlots; ++it) {
-        const int64_t t = (int64_t)first + it * kSlots + slot;
+    for (int it = 0; it < a.frames_per_group / kMelSlots; ++it) {
+        const int64_t t = (int64_t)first + it * kMelSlots + slot;
         const bool live = t < n_frames_u;
         float2 v[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const int i0 = 2 * fft_in_index<NC, kLanes>(sub, i);
+            const int i0 = 2 * fft_in_index<NC, kMelLanes>(sub, i);
             float re = 0.f, im = 0.f;
             if (live) {
                 if (i0 < win) re = x[t * hop + i0] * wnd[i].x;
@@ -102,39 +145,46 @@ __global__ __launch_bounds__(kMelThreads) void mel_kernel(MelArgs a, const float
             }
             v[i] = make_float2(re, im);
         }
-        for (int m = sub; m < n_mel; m += kLanes) acc[m] = 0.f;
-        fft_passes<NC, kLanes, false>(v, buf, tw, sub);
-        fft_store_natural<NC, kLanes>(v, buf, sub);
+        fft_passes<NC, kMelLanes, false>(v, buf, tw, sub);      // two barriers inside: the last frame's sums were read
+        fft_store_natural<NC, kMelLanes>(v, buf, sub);
+        for (int m = sub; m < 2 * n_seg; m += kMelLanes) A[m] = 0.f;
         __syncthreads();
 
-        // bins sub*16 .. sub*16+15, and bin NC on the last lane
-        for (int i = 0; i < kBinsPerLane + 1; ++i) {
-            if (i == kBinsPerLane && sub != kLanes - 1) break;
-            const int k = i == kBinsPerLane ? NC : sub * kBinsPerLane + i;
+        // power of bins [k_lo, k_hi) -> per-band sums; this lane owns every band it meets
+        float run_a = 0.f, run_b = 0.f;
+        int cur = -100;
+        for (int k = k_lo; k < k_hi; ++k) {
             const int kk = k & (NC - 1);
-            const float2 A = buf[lds_pad(kk)];
-            const float2 Bc = buf[lds_pad((NC - kk) & (NC - 1))];
-            const float2 w = k <= NC / 2 ? tw[NC + k]
-                                         : make_float2(-tw[NC + (NC - k)].x, tw[NC + (NC - k)].y);
-            // X[k] = E + w O,  E = (A + conj B)/2,  O = -(i/2)(A - conj B)
-            const float2 E = make_float2(0.5f * (A.x + Bc.x), 0.5f * (A.y - Bc.y));
-            const float2 d = make_float2(A.x - Bc.x, A.y + Bc.y);
+            const float2 Zk = buf[lds_pad(kk)];
+            const float2 Zn = buf[lds_pad((NC - kk) & (NC - 1))];
+            const float2 w = s_tw[k];
+            // X[k] = E + w O,  E = (Z[k] + conj Z[N-k])/2,  O = -(i/2)(Z[k] - conj Z[N-k])
+            const float2 E = make_float2(0.5f * (Zk.x + Zn.x), 0.5f * (Zk.y - Zn.y));
+            const float2 d = make_float2(Zk.x - Zn.x, Zk.y + Zn.y);
             const float2 O = make_float2(0.5f * d.y, -0.5f * d.x);
             const float2 X = cadd(E, cmul(w, O));
             const float p = X.x * X.x + X.y * X.y;
-            const float2 cw = tab[k];
+            const float2 cw = s_tab[k];
             const int c = (int)cw.x;
-            if (c >= 0 && c < n_mel) atomicAdd(&acc[c], cw.y * p);
-            if (c >= 1 && c <= n_mel) atomicAdd(&acc[c - 1], (1.f - cw.y) * p);
+            if (c != cur) {
+                if (cur >= 0) { A[cur] = run_a; B[cur] = run_b; }
+                cur = c;
+                run_a = 0.f;
+                run_b = 0.f;
+            }
+            run_a += cw.y * p;
+            run_b += (1.f - cw.y) * p;
         }
+        if (cur >= 0) { A[cur] = run_a; B[cur] = run_b; }
         __syncthreads();
+
+        // channel m collects the rising side of band m and the falling side of band m + 1
         if (live) {
-            for (int m = sub; m < n_mel; m += kLanes) {
-                const float e = acc[m];
-                feats[t * n_mel + m] = e > 0.f ? powf(e, a.cfg.power) : 0.f;
+            for (int m = sub; m < n_mel; m += kMelLanes) {
+                const float e = A[m] + B[m + 1];
+                feats[t * n_mel + m] = e > 0.f ? __powf(e, power) : 0.f;
             }
         }
-        __syncthreads();
     }
 }
 
@@ -147,18 +197,28 @@ hipError_t launch_window(hipStream_t s, int win, float* w) {
     return hipGetLastError();
 }
 
+int mel_table_stride(int nfft) { return nfft / 2 + 1 + 9; }   // (c, w) per bin, then 17 lane starts (+ pad)
+
 hipError_t launch_mel_table(hipStream_t s, int n_utt, const float* alpha, const aug_frontend_cfg& cfg,
                             float2* tab) {
-    const int64_t n = (int64_t)n_utt * (cfg.nfft / 2 + 1);
+    const int bins = cfg.nfft / 2 + 1;
+    const int64_t n = (int64_t)n_utt * bins;
     if (n <= 0) return hipSuccess;
-    mel_table_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(n_utt, alpha, cfg, tab);
+    mel_table_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(n_utt, alpha, cfg,
+                                                                             mel_table_stride(cfg.nfft), tab);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    mel_partition_kernel<<<dim3((n_utt + 63) / 64), dim3(64), 0, s>>>(n_utt, bins, mel_table_stride(cfg.nfft), tab);
     return hipGetLastError();
 }
 
 hipError_t launch_mel(hipStream_t s, const MelArgs& a) {
     if (a.n_items <= 0) return hipSuccess;
     if (a.cfg.nfft != 512) return hipErrorInvalidValue;
-    mel_kernel<256><<<dim3((unsigned)a.n_items), dim3(kMelThreads), 0, s>>>(a, a.twiddle);
+    constexpr int NC = 256;
+    const size_t lds = sizeof(float2) * (kMelSlots * lds_padded_size(NC) + 2 * (NC + 1)) +
+                       sizeof(float) * kMelSlots * 2 * (a.cfg.n_mel + 2) + sizeof(int) * 20;
+    mel_kernel<NC><<<dim3((unsigned)a.n_items), dim3(kMelThreads), lds, s>>>(a, a.twiddle, mel_table_stride(a.cfg.nfft));
     return hipGetLastError();
 }
 
