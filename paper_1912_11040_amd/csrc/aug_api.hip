@@ -179,7 +179,7 @@ int ensure_twiddle(aug_ctx* ctx, int n, const float2** out) {
     while ((1 << lg) < n) ++lg;
     DeviceBuffer& b = ctx->twiddle[lg];
     if (!b.ptr) {
-        AUG_HIP(b.reserve(sizeof(float2) * (size_t)(n + n / 2 + 1)), "twiddle table");
+        AUG_HIP(b.reserve(sizeof(float2) * (size_t)aug::twiddle_entries(n)), "twiddle table");
         AUG_HIP(aug::launch_twiddle(ctx->stream, n, b.as<float2>()), "twiddle kernel");
     }
     *out = b.as<float2>();

@@ -122,7 +122,9 @@ hipError_t launch_mel_table(hipStream_t s, int n_utt, const float* alpha, const 
 // Hamming window, float [win].
 hipError_t launch_window(hipStream_t s, int win, float* w);
 
-// tw[t] = exp(-2 pi i t / n), t < n, then tw[n + k] = exp(-i pi k / n), k <= n/2; fp64 rounded once.
+// tw[t] = exp(-2 pi i t / n), t < n, then tw[n + k] = exp(-i pi k / n), k <= n/2, then
+// exp(-i pi 16 j / n), j < n/32; each computed in fp64 and rounded once.
+int twiddle_entries(int n);
 hipError_t launch_twiddle(hipStream_t s, int n, float2* tw);
 
 // STFT power -> warped mel -> power law.

@@ -5,8 +5,9 @@
 // (2P-point real FFT); an output block of P samples is the inverse transform of
 // sum_p X_{b-p} H_p, X_w the transform of input samples [(w-1)P, (w+1)P).
 // A 2P-point real transform is run as a P-point complex FFT of the even/odd packed
-// sequence, entirely in LDS; the first pass reads its inputs straight from HBM and the
-// last inverse pass writes the output block straight back.
+// sequence, entirely in LDS, split as 16 x P/16: the radix-16 column step reads its inputs
+// straight from HBM (and, inverse, writes the block straight back); the 16 row transforms
+// run one per wavefront without work-group barriers.
 //
 // One work group produces one output block of one (utterance, source), adds the
 // block's energy to E[u][j] (fp64 atomics), and a second kernel forms the gains
@@ -20,13 +21,17 @@ namespace {
 
 constexpr int conv_threads(int n) { return n / 16; }
 
+__host__ __device__ constexpr int twiddle_count(int n) { return n + n / 2 + 1 + n / 32; }
+
 __global__ void twiddle_kernel(int n, float2* tw) {
-    // tw[t] = exp(-2 pi i t / n), t < n;  tw[n + k] = exp(-i pi k / n), k <= n/2
+    // tw[t] = exp(-2 pi i t / n), t < n;  tw[n + k] = exp(-i pi k / n), k <= n/2;
+    // tw[n + n/2 + 1 + j] = exp(-i pi 16 j / n), j < n/32
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n + n / 2 + 1) return;
+    if (i >= twiddle_count(n)) return;
     double s, c;
     if (i < n) sincospi(-2.0 * (double)i / (double)n, &s, &c);
-    else sincospi(-(double)(i - n) / (double)n, &s, &c);
+    else if (i < n + n / 2 + 1) sincospi(-(double)(i - n) / (double)n, &s, &c);
+    else sincospi(-16.0 * (double)(i - n - n / 2 - 1) / (double)n, &s, &c);
     tw[i] = make_float2((float)c, (float)s);
 }
 
@@ -41,38 +46,66 @@ __device__ inline void unpack_pair(float2 A, float2 B, float2 w, float2& Wk, flo
     WNk_conj = csub(E, wO);
 }
 
+// Bins are visited as k = k1 + 16 k2 (row k1, column k2 of the split transform), k < N/2, each with
+// its partner N - k.  Thread tid owns column k2 = tid mod M/2 of rows k1 = 8 (tid div M/2) + i.
+template <int N>
+struct PairIndex {
+    static constexpr int M = N / 16;
+    int k, pos, pos_partner, h_partner;     // LDS/spectrum position of k and of N-k (spectrum: H[N] sits at N)
+    __device__ inline PairIndex(int k1, int k2) {
+        k = k1 + 16 * k2;
+        pos = k1 * M + k2;
+        pos_partner = k1 ? (16 - k1) * M + (M - 1 - k2) : ((M - k2) & (M - 1));
+        h_partner = k ? pos_partner : N;
+    }
+};
+
+template <int N> __device__ inline float2 pair_twiddle(const float2* __restrict__ tw, int k1, int k2) {
+    return cmul(tw[N + k1], tw[N + N / 2 + 1 + k2]);           // exp(-i pi (k1 + 16 k2) / N)
+}
+
+// Spectrum of one response partition, stored in the split order (k at fft_split_pos(k), k = N last)
+// and scaled by 1/N for the unnormalised inverse.
 template <int N, int T>
 __global__ __launch_bounds__(T) void rir_spectrum_kernel(
     const float* __restrict__ rir, int rir_len, int n_part, const float2* __restrict__ tw,
     float2* __restrict__ spec) {
     extern __shared__ float2 buf[];
+    constexpr int M = N / 16;
     const int tid = threadIdx.x;
     const int r = blockIdx.x / n_part, p = blockIdx.x % n_part;
     const float* h = rir + (size_t)r * rir_len;
     float2 v[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int n = fft_in_index<N, T>(tid, i);
+    for (int n1 = 0; n1 < 16; ++n1) {
+        const int n = tid + M * n1;
         const int t = p * N + 2 * n;                 // taps of this partition: [pN, (p+1)N), then N zeros
         float a = 0.f, b = 0.f;
         if (2 * n < N) {
             if (t < rir_len) a = h[t];
             if (t + 1 < rir_len) b = h[t + 1];
         }
-        v[i] = make_float2(a, b);
+        v[n1] = make_float2(a, b);
     }
-    fft_passes<N, T, false>(v, buf, tw, tid);
-    fft_store_natural<N, T>(v, buf, tid);
+    fft_columns_forward<N>(v, tw, tid);
+    fft_columns_store<N, T>(v, buf, tid);
+    __syncthreads();
+    fft_rows<N, false>(buf, tw, tid);
     __syncthreads();
     float2* out = spec + ((size_t)r * n_part + p) * (N + 1);
     const float scale = 1.0f / (float)N;             // the inverse transform's normalisation
-    for (int k = tid; k <= N / 2; k += T) {
-        const float2 A = buf[lds_pad(k)];
-        const float2 B = cconj(buf[lds_pad((N - k) & (N - 1))]);
+    const int k2 = tid % (M / 2), half = tid / (M / 2);
+#pragma unroll
+    for (int i = 0; i <= 8; ++i) {
+        if (i == 8 && tid != 0) break;
+        const PairIndex<N> ix(i == 8 ? 0 : half * 8 + i, i == 8 ? M / 2 : k2);
+        const float2 A = buf[lds_pad(ix.pos)];
+        const float2 B = cconj(buf[lds_pad(ix.pos_partner)]);
+        const float2 w = i == 8 ? tw[N + N / 2] : pair_twiddle<N>(tw, half * 8 + i, k2);
         float2 Hk, HNk_conj;
-        unpack_pair(A, B, tw[N + k], Hk, HNk_conj);
-        out[k] = make_float2(Hk.x * scale, Hk.y * scale);
-        out[N - k] = make_float2(HNk_conj.x * scale, -HNk_conj.y * scale);
+        unpack_pair(A, B, w, Hk, HNk_conj);
+        out[ix.pos] = make_float2(Hk.x * scale, Hk.y * scale);
+        if (i < 8) out[ix.h_partner] = make_float2(HNk_conj.x * scale, -HNk_conj.y * scale);
     }
 }
 
@@ -95,8 +128,8 @@ template <int N, int T, bool MULTI>
 __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* __restrict__ tw) {
     extern __shared__ float2 buf[];
     __shared__ double red[T / 64];
-    constexpr int PAIRS = (N / 2) / T;               // bins k = tid + i T, k < N/2, each with N-k
-    static_assert(PAIRS == 8, "sixteen values per thread");
+    constexpr int M = N / 16;
+    static_assert(T == M, "one thread per column of the split transform");
     const int tid = threadIdx.x;
     const int64_t item = blockIdx.x / a.n_src;
     const int j = blockIdx.x % a.n_src;
@@ -105,12 +138,13 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
     const int64_t len = a.offsets[u + 1] - start;
     const float* x = (j == 0 ? a.speech : a.noise + (size_t)(j - 1) * a.total) + start;
     const float2* H = a.spec + ((size_t)u * a.n_src + j) * a.n_part * (size_t)(N + 1);
+    const int k2 = tid % (M / 2), half = tid / (M / 2);
 
-    float2 accK[MULTI ? PAIRS + 1 : 1], accN[MULTI ? PAIRS : 1];   // Z'[k], Z'[N-k]; last accK is k = N/2
+    float2 accK[MULTI ? 9 : 1], accN[MULTI ? 8 : 1];   // Z'[k], Z'[N-k]; accK[8] is k = N/2
     if (MULTI) {
 #pragma unroll
-        for (int i = 0; i < PAIRS; ++i) accK[i] = accN[i] = make_float2(0.f, 0.f);
-        accK[PAIRS] = make_float2(0.f, 0.f);
+        for (int i = 0; i < 8; ++i) accK[i] = accN[i] = make_float2(0.f, 0.f);
+        accK[8] = make_float2(0.f, 0.f);
     }
 
     float2 v[16];
@@ -120,60 +154,61 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
         if (wb < 0) break;
         const int64_t w0 = ((int64_t)wb - 1) * N;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int64_t g = w0 + 2 * fft_in_index<N, T>(tid, i);
+        for (int n1 = 0; n1 < 16; ++n1) {
+            const int64_t g = w0 + 2 * (tid + M * n1);
             const float x0 = (g >= 0 && g < len) ? x[g] : 0.f;
             const float x1 = (g + 1 >= 0 && g + 1 < len) ? x[g + 1] : 0.f;
-            v[i] = make_float2(x0, x1);
+            v[n1] = make_float2(x0, x1);
         }
+        fft_columns_forward<N>(v, tw, tid);
         if (MULTI && p > 0) __syncthreads();         // the previous partition's pair reads are done
-        fft_passes<N, T, false>(v, buf, tw, tid);
-        fft_store_natural<N, T>(v, buf, tid);
+        fft_columns_store<N, T>(v, buf, tid);
+        __syncthreads();
+        fft_rows<N, false>(buf, tw, tid);
         __syncthreads();
         const float2* Hp = H + (size_t)p * (N + 1);
 #pragma unroll
-        for (int i = 0; i <= PAIRS; ++i) {
-            if (i == PAIRS && tid != 0) break;
-            const int k = i == PAIRS ? N / 2 : tid + i * T;
-            const int kn = (N - k) & (N - 1);
-            const float2 A = buf[lds_pad(k)];
-            const float2 B = cconj(buf[lds_pad(kn)]);
+        for (int i = 0; i <= 8; ++i) {
+            if (i == 8 && tid != 0) break;
+            const PairIndex<N> ix(i == 8 ? 0 : half * 8 + i, i == 8 ? M / 2 : k2);
+            const float2 A = buf[lds_pad(ix.pos)];
+            const float2 B = cconj(buf[lds_pad(ix.pos_partner)]);
+            const float2 w = i == 8 ? tw[N + N / 2] : pair_twiddle<N>(tw, half * 8 + i, k2);
             float2 Zk, ZNk;
-            multiply_pair(A, B, tw[N + k], Hp[k], Hp[N - k], Zk, ZNk);
+            multiply_pair(A, B, w, Hp[ix.pos], Hp[ix.h_partner], Zk, ZNk);
             if (MULTI) {
-                accK[i == PAIRS ? PAIRS : i] = cadd(accK[i == PAIRS ? PAIRS : i], Zk);
-                if (i < PAIRS) accN[i] = cadd(accN[i], ZNk);
-            } else {                                 // positions k and N-k belong to this thread alone
-                buf[lds_pad(k)] = Zk;
-                if (k != 0 && i < PAIRS) buf[lds_pad(kn)] = ZNk;
+                accK[i] = cadd(accK[i], Zk);
+                if (i < 8) accN[i] = cadd(accN[i], ZNk);
+            } else {                                 // both positions belong to this thread alone
+                buf[lds_pad(ix.pos)] = Zk;
+                if (ix.k != 0 && i < 8) buf[lds_pad(ix.pos_partner)] = ZNk;
             }
         }
     }
     if (MULTI) {
 #pragma unroll
-        for (int i = 0; i < PAIRS; ++i) {
-            const int k = tid + i * T;
-            buf[lds_pad(k)] = accK[i];
-            if (k != 0) buf[lds_pad(N - k)] = accN[i];
+        for (int i = 0; i < 8; ++i) {
+            const PairIndex<N> ix(half * 8 + i, k2);
+            buf[lds_pad(ix.pos)] = accK[i];
+            if (ix.k != 0) buf[lds_pad(ix.pos_partner)] = accN[i];
         }
-        if (tid == 0) buf[lds_pad(N / 2)] = accK[PAIRS];
+        if (tid == 0) buf[lds_pad(M / 2)] = accK[8];
     }
     __syncthreads();
-    fft_load_natural<N, T>(v, buf, tid);
+    fft_rows<N, true>(buf, tw, tid);
     __syncthreads();
-    fft_passes<N, T, true>(v, buf, tw, tid);
+    fft_columns_load<N, T>(v, buf, tid);
+    fft_columns_inverse<N>(v, tw, tid);
 
-    // the last N real samples of the 2N-sample window are this block's outputs
+    // the last N real samples of the 2N-sample window are this block's outputs: n = tid + M n1 >= N/2
     float* y = a.reverb + (size_t)j * a.total + start;
     const int64_t out0 = (int64_t)b * N;
     float e = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int n = fft_out_index<N, T>(tid, i);
-        if (n < N / 2) continue;
-        const int64_t g = out0 + 2 * (n - N / 2);
-        if (g < len) { y[g] = v[i].x; e += v[i].x * v[i].x; }
-        if (g + 1 < len) { y[g + 1] = v[i].y; e += v[i].y * v[i].y; }
+    for (int n1 = 8; n1 < 16; ++n1) {
+        const int64_t g = out0 + 2 * (tid + M * (n1 - 8));
+        if (g < len) { y[g] = v[n1].x; e += v[n1].x * v[n1].x; }
+        if (g + 1 < len) { y[g + 1] = v[n1].y; e += v[n1].y * v[n1].y; }
     }
     double es = (double)e;
     for (int off = 32; off > 0; off >>= 1) es += __shfl_down(es, off, 64);
@@ -253,8 +288,10 @@ int conv_fft_size(int rir_len) {
     return n;
 }
 
+int twiddle_entries(int n) { return twiddle_count(n); }
+
 hipError_t launch_twiddle(hipStream_t s, int n, float2* tw) {
-    const int count = n + n / 2 + 1;
+    const int count = twiddle_count(n);
     twiddle_kernel<<<dim3((count + 255) / 256), dim3(256), 0, s>>>(n, tw);
     return hipGetLastError();
 }

@@ -11,6 +11,12 @@
 // Twiddles: one table value w = exp(-2 pi i t / N) per butterfly; its powers are formed by
 // at most four successive complex products.  The inverse uses conjugates and is unscaled.
 //
+// Synchronisation between the reads and writes of a pass is a work-group barrier, or, when all
+// threads of one transform sit in one wavefront, only a wave-level fence (LDS operations of a wave
+// complete in order).  Large transforms are split as N = 16 x M: one radix-16 step across the
+// group, then 16 independent M-point row transforms of at most 64 lanes each, which need no
+// barriers and so overlap each other's LDS and ALU phases (see fft_columns_*).
+//
 // LDS addressing is padded by one complex per 16 (element i lives at lds_pad(i)) so that both
 // the unit-stride reads and the stride-NS writes of every pass spread over all banks.
 #pragma once
@@ -161,13 +167,26 @@ __device__ inline void fft_store(const float2 (&v)[16], float2* buf, int tid) {
     }
 }
 
-template <int N, int T, int R, int NS, bool INV>
+enum class FftSync { Group, Wave };
+
+template <FftSync S> __device__ inline void fft_sync() {
+    if constexpr (S == FftSync::Group) {
+        __syncthreads();
+    } else {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+}
+
+// TWS: the table holds exp(-2 pi i t / (N TWS)), i.e. it was built for a TWS times longer transform.
+template <int N, int T, int R, int NS, bool INV, int TWS>
 __device__ inline void fft_compute(float2 (&v)[16], const float2* __restrict__ tw, int tid) {
 #pragma unroll
     for (int bi = 0; bi < 16 / R; ++bi) {
         if constexpr (NS > 1) {
             const int k = (tid + bi * T) % NS;
-            float2 w1 = tw[k * (N / (NS * R))];
+            float2 w1 = tw[k * (N / (NS * R)) * TWS];
             if (INV) w1.y = -w1.y;
             twiddle_inputs<R>(&v[bi * R], w1);
         }
@@ -190,17 +209,17 @@ __device__ inline int fft_in_index(int tid, int i) {
 // Run passes P.. of the transform.  On entry v holds the inputs of pass P (fft_in_index order for
 // P = 0); on return it holds the outputs of the last pass (fft_out_index order), not yet stored.
 // All T threads of the group must call; buf contents are overwritten.
-template <int N, int T, bool INV, int P = 0>
+template <int N, int T, bool INV, FftSync S = FftSync::Group, int TWS = 1, int P = 0>
 __device__ inline void fft_passes(float2 (&v)[16], float2* buf, const float2* __restrict__ tw, int tid) {
     using Plan = FftPlan<N>;
     constexpr int R = Plan::radix(P), NS = Plan::ns(P);
-    fft_compute<N, T, R, NS, INV>(v, tw, tid);
+    fft_compute<N, T, R, NS, INV, TWS>(v, tw, tid);
     if constexpr (P + 1 < Plan::kPasses) {
         fft_store<N, T, R, NS>(v, buf, tid);
-        __syncthreads();
+        fft_sync<S>();
         fft_load<N, T, Plan::radix(P + 1)>(v, buf, tid);
-        __syncthreads();
-        fft_passes<N, T, INV, P + 1>(v, buf, tw, tid);
+        fft_sync<S>();
+        fft_passes<N, T, INV, S, TWS, P + 1>(v, buf, tw, tid);
     }
 }
 
@@ -216,6 +235,56 @@ template <int N, int T>
 __device__ inline void fft_load_natural(float2 (&v)[16], const float2* buf, int tid) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) v[i] = buf[lds_pad(fft_in_index<N, T>(tid, i))];
+}
+
+// ---- N = 16 x M split -------------------------------------------------------------------
+// X[k1 + 16 k2] = sum_{n2 < M} W_M^{n2 k2} W_N^{n2 k1} sum_{n1 < 16} x[n2 + M n1] W_16^{n1 k1}.
+// Thread n2 of the M = N/16 threads holds x[n2 + M n1] in v[n1]; after the column step v[k1] belongs
+// to row k1, column n2.  Row k1 lives at buf[lds_pad(k1 M + .)] and is transformed by M/16 lanes of
+// one wavefront.  After the forward transform frequency k = k1 + 16 k2 sits at row k1, column k2.
+
+template <int N> __device__ __host__ constexpr int fft_split_pos(int k) { return (k & 15) * (N / 16) + (k >> 4); }
+
+// forward column step on registers: v[n1] -> v[k1] (twiddled), to be stored at row k1, column n2
+template <int N>
+__device__ inline void fft_columns_forward(float2 (&v)[16], const float2* __restrict__ tw, int n2) {
+    SmallDft<16, false>::run(v);
+    twiddle_inputs<16>(v, tw[n2]);
+}
+
+// inverse column step: v[k1] (row k1, column n2) -> v[n1] = N x[n2 + M n1]
+template <int N>
+__device__ inline void fft_columns_inverse(float2 (&v)[16], const float2* __restrict__ tw, int n2) {
+    float2 w1 = tw[n2];
+    w1.y = -w1.y;
+    twiddle_inputs<16>(v, w1);
+    SmallDft<16, true>::run(v);
+}
+
+template <int N, int T>
+__device__ inline void fft_columns_store(const float2 (&v)[16], float2* buf, int n2) {
+#pragma unroll
+    for (int k1 = 0; k1 < 16; ++k1) buf[lds_pad(k1 * (N / 16) + n2)] = v[k1];
+}
+template <int N, int T>
+__device__ inline void fft_columns_load(float2 (&v)[16], const float2* buf, int n2) {
+#pragma unroll
+    for (int k1 = 0; k1 < 16; ++k1) v[k1] = buf[lds_pad(k1 * (N / 16) + n2)];
+}
+
+// The 16 row transforms, in place in natural order within each row; wave-level synchronisation only.
+// Thread tid works on row tid / (M/16) as lane tid % (M/16).  Rows must be complete (barrier) before.
+template <int N, bool INV>
+__device__ inline void fft_rows(float2* buf, const float2* __restrict__ tw, int tid) {
+    constexpr int M = N / 16, LANES = M / 16;
+    static_assert(LANES >= 1 && LANES <= 64, "a row is transformed inside one wavefront");
+    float2* row = buf + lds_pad((tid / LANES) * M);
+    const int lane = tid % LANES;
+    float2 v[16];
+    fft_load_natural<M, LANES>(v, row, lane);
+    fft_sync<FftSync::Wave>();
+    fft_passes<M, LANES, INV, FftSync::Wave, 16>(v, row, tw, lane);
+    fft_store_natural<M, LANES>(v, row, lane);
 }
 
 }  // namespace aug

@@ -59,29 +59,28 @@ __global__ void mel_table_kernel(int n_utt, const float* __restrict__ alpha, aug
 }
 
 // Cut the bins of one utterance into 16 contiguous lane ranges that end on changes of the band
-// index c, so that every (c, utterance) sum is formed by one lane alone; ranges aim at equal sizes.
-__global__ void mel_partition_kernel(int n_utt, int bins, int stride, float2* __restrict__ tab) {
-    const int u = blockIdx.x * blockDim.x + threadIdx.x;
-    if (u >= n_utt) return;
+// index c, so that every (c, utterance) sum is formed by one lane alone.  Range i ends at the band
+// change nearest to (i + 1) bins / 16; the ends are non-decreasing because the targets are.
+// One work group of 64 threads per utterance; threads 0..14 each place one boundary.
+__global__ __launch_bounds__(64) void mel_partition_kernel(int n_utt, int bins, int stride, float2* __restrict__ tab) {
+    __shared__ float band[2050];
+    const int u = blockIdx.x;
     const float2* t = tab + (size_t)u * stride;
     int* kstart = reinterpret_cast<int*>(tab + (size_t)u * stride + bins);
-    int start = 0;
-    kstart[0] = 0;
-    for (int lane = 0; lane < 15; ++lane) {
+    for (int k = threadIdx.x; k < bins; k += 64) band[k] = t[k].x;
+    __syncthreads();
+    const int lane = threadIdx.x;
+    if (lane == 0) { kstart[0] = 0; kstart[16] = bins; }
+    if (lane < 15) {
         const int ideal = ((lane + 1) * bins + 8) / 16;
-        int lo = -1, hi = bins;                       // nearest band changes at or below / above ideal
-        for (int k = start + 1; k < bins; ++k) {
-            if (t[k].x != t[k - 1].x) {
-                if (k <= ideal) lo = k;
-                else { hi = k; break; }
-            }
+        int end = bins;                               // no change found: everything up to the end
+        for (int d = 0; d < bins; ++d) {
+            const int lo = ideal - d, hi = ideal + d;
+            if (lo >= 1 && lo < bins && band[lo] != band[lo - 1]) { end = lo; break; }
+            if (hi >= 1 && hi < bins && band[hi] != band[hi - 1]) { end = hi; break; }
         }
-        int end = (lo > start && (ideal - lo) <= (hi - ideal)) ? lo : hi;
-        if (end < start) end = start;
         kstart[lane + 1] = end;
-        start = end;
     }
-    kstart[16] = bins;
 }
 
 constexpr int kMelLanes = 16;                            // lanes per frame
@@ -145,10 +144,10 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
             }
             v[i] = make_float2(re, im);
         }
-        fft_passes<NC, kMelLanes, false>(v, buf, tw, sub);      // two barriers inside: the last frame's sums were read
+        fft_passes<NC, kMelLanes, false, FftSync::Wave>(v, buf, tw, sub);
         fft_store_natural<NC, kMelLanes>(v, buf, sub);
         for (int m = sub; m < 2 * n_seg; m += kMelLanes) A[m] = 0.f;
-        __syncthreads();
+        fft_sync<FftSync::Wave>();                       // a frame's 16 lanes share a wavefront
 
         // power of bins [k_lo, k_hi) -> per-band sums; this lane owns every band it meets
         float run_a = 0.f, run_b = 0.f;
@@ -176,7 +175,7 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
             run_b += (1.f - cw.y) * p;
         }
         if (cur >= 0) { A[cur] = run_a; B[cur] = run_b; }
-        __syncthreads();
+        fft_sync<FftSync::Wave>();
 
         // channel m collects the rising side of band m and the falling side of band m + 1
         if (live) {
@@ -185,6 +184,7 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
                 feats[t * n_mel + m] = e > 0.f ? __powf(e, power) : 0.f;
             }
         }
+        fft_sync<FftSync::Wave>();                       // sums are read before the next frame clears them
     }
 }
 
@@ -208,7 +208,7 @@ hipError_t launch_mel_table(hipStream_t s, int n_utt, const float* alpha, const 
                                                                              mel_table_stride(cfg.nfft), tab);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    mel_partition_kernel<<<dim3((n_utt + 63) / 64), dim3(64), 0, s>>>(n_utt, bins, mel_table_stride(cfg.nfft), tab);
+    mel_partition_kernel<<<dim3((unsigned)n_utt), dim3(64), 0, s>>>(n_utt, bins, mel_table_stride(cfg.nfft), tab);
     return hipGetLastError();
 }
 

@@ -68,6 +68,7 @@ def test_pure_tone_and_alpha_extremes(aug, alpha):
     f = _run(aug, offsets, x, a)
     ref = O.vtlp_mel_batch(offsets, x, a, FE)
     assert feat_err(f, ref) <= FEAT_TOL
+    print(f"feature error = {feat_err(f, ref):.2e}", flush=True)
     assert (np.argmax(f, axis=1) == np.argmax(ref, axis=1)).all()
 
 

@@ -40,6 +40,8 @@ def _oracle(w, conv="direct"):
 
 
 def _compare(got, ref, w):
+    print(f"  rir err {rir_err(got['rir'], ref['rir']):.2e}  wave err {wave_err(got['mixed'], ref['mixed'], w.offsets):.2e}"
+          f"  feat err {feat_err(got['feats'], ref['feats']):.2e}", flush=True)
     assert rir_err(got["rir"], ref["rir"]) <= RIR_TOL
     assert wave_err(got["mixed"], ref["mixed"], w.offsets) <= WAVE_TOL
     np.testing.assert_allclose(got["gains"], ref["gains"], rtol=GAIN_TOL)
