@@ -38,7 +38,7 @@ constexpr int kMinTaps = 64;
 constexpr int kPow = 1024;                // beta^k table entries held in LDS
 constexpr int kZCap = 320;                // z images per q held in LDS; more than that: computed in the loop
 constexpr int kPiece = 16;                // images per piece
-constexpr float kTargetImages = 400000.f; // images per item aimed for
+constexpr float kTargetImages = 800000.f; // images per item aimed for (before reflection cuts)
 constexpr int kMaxShells = 96;            // volume-balanced shells per response, at most
 
 #pragma clang fp contract(off)
@@ -263,8 +263,8 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
             nmy = min(nmy, k_cut_item / 2 + 1);
             const int nix = 2 * (2 * nmx + 1), niy = 2 * (2 * nmy + 1);
             const int n_cand = nix * niy;
-            const double inv_two_lz = 1.0 / (2.0 * az.room);
-            const double z0q[2] = {__dsub_rn(az.src, az.mic), __dsub_rn(__dmul_rn(-1.0, az.src), az.mic)};
+            const float inv_two_lzf = (float)(1.0 / (2.0 * az.room));
+            const float z0qf[2] = {(float)(az.src - az.mic), (float)(-az.src - az.mic)};
             const int n_batch = (n_cand + 63) / 64;
             Column* wc = cols[wave];
             WalkCtx wctx;
@@ -313,18 +313,20 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
                     // reflections left for the z axis before this column's images vanish
                     const int kz_max = reflection_cut(log2_beta, fmaxf((float)r_in, sqrtf((float)col.a))) - col.kxy;
                     if (col.a < r_out2 && kz_max >= 0) {
-                        const double zout = sqrt(r_out2 - col.a);
-                        const double zin = col.a < r_in2 ? sqrt(r_in2 - col.a) : 0.0;
+                        // z reach of the shell in this column; fp32 is enough because the shell radii carry
+                        // half a tap (about a centimetre) of slack and the exact tap test decides anyway
+                        const float zout = sqrtf((float)(r_out2 - col.a));
+                        const float zin = col.a < r_in2 ? sqrtf((float)(r_in2 - col.a)) : 0.f;
 #pragma unroll
                         for (int q = 0; q < 2; ++q) {
-                            const double z0 = z0q[q];
+                            const float z0 = z0qf[q];
                             // |n - q| + |n| <= kz_max  <=>  cut_lo <= n <= cut_hi
                             const int cut_lo = q ? -((kz_max - 1) >> 1) : -(kz_max >> 1);
                             const int cut_hi = q ? ((kz_max + 1) >> 1) : (kz_max >> 1);
-                            const int lo_n = max((int)ceil((-zout - z0) * inv_two_lz - 1e-6), cut_lo);
-                            const int hi_n = min((int)floor((-zin - z0) * inv_two_lz + 1e-6), cut_hi);
-                            const int lo_p = max((int)ceil((zin - z0) * inv_two_lz - 1e-6), cut_lo);
-                            const int hi_p = min((int)floor((zout - z0) * inv_two_lz + 1e-6), cut_hi);
+                            const int lo_n = max((int)ceilf((-zout - z0) * inv_two_lzf - 1e-4f), cut_lo);
+                            const int hi_n = min((int)floorf((-zin - z0) * inv_two_lzf + 1e-4f), cut_hi);
+                            const int lo_p = max((int)ceilf((zin - z0) * inv_two_lzf - 1e-4f), cut_lo);
+                            const int hi_p = min((int)floorf((zout - z0) * inv_two_lzf + 1e-4f), cut_hi);
                             if (hi_n >= lo_p - 1) {            // the two sides touch: one run
                                 col.start[2 * q] = (short)lo_n;
                                 col.len[2 * q] = (short)max(hi_p - lo_n + 1, 0);
