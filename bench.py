@@ -121,6 +121,9 @@ def main() -> int:
     ap.add_argument("--workload", default="varlen",
                     choices=["tiny", "features", "batch", "varlen", "throughput"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one untimed 1 GiB device-to-device copy, the known-size kernel that "
+                         "FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path runs on one GPU (utterances are independent; there is nothing to "
@@ -165,6 +168,13 @@ def main() -> int:
             aug.aug_rir_batch(g2[a:b].contiguous(), w.rir_len, w.fs, w.c, h, cnt)
             n_images += float(cnt.sum(dtype=torch.int64).item())
             del h, cnt
+
+    if args.copy_probe:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

@@ -83,9 +83,12 @@ int check_offsets(aug_ctx* ctx, int n_utt, const int64_t* offsets) {
     if (n_utt < 0) return fail(ctx, AUG_ERR_INVALID_ARG, "n_utt is negative");
     if (!offsets) return fail(ctx, AUG_ERR_INVALID_ARG, "offsets is null");
     if (offsets[0] != 0) return fail(ctx, AUG_ERR_INVALID_ARG, "offsets[0] must be 0");
-    for (int u = 0; u < n_utt; ++u)
+    for (int u = 0; u < n_utt; ++u) {
         if (offsets[u + 1] < offsets[u])
             return fail(ctx, AUG_ERR_INVALID_ARG, "offsets not ascending at utterance %d", u);
+        if (offsets[u + 1] - offsets[u] >= ((int64_t)1 << 30))
+            return fail(ctx, AUG_ERR_UNSUPPORTED, "utterance %d is 2^30 samples or longer", u);
+    }
     if (offsets[n_utt] > ((int64_t)1 << 40)) return fail(ctx, AUG_ERR_UNSUPPORTED, "packed signal too long");
     return AUG_OK;
 }

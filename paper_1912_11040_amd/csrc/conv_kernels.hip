@@ -135,7 +135,7 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
     const int j = blockIdx.x % a.n_src;
     const int u = a.items[item].x, b = a.items[item].y;
     const int64_t start = a.offsets[u];
-    const int64_t len = a.offsets[u + 1] - start;
+    const int len = (int)(a.offsets[u + 1] - start);      // utterances are shorter than 2^30 samples (checked on the host)
     const float* x = (j == 0 ? a.speech : a.noise + (size_t)(j - 1) * a.total) + start;
     const float2* H = a.spec + ((size_t)u * a.n_src + j) * a.n_part * (size_t)(N + 1);
     const int k2 = tid % (M / 2), half = tid / (M / 2);
@@ -152,12 +152,13 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
     for (int p = 0; p < n_part; ++p) {
         const int wb = b - p;                        // input window [(wb-1)N, (wb+1)N)
         if (wb < 0) break;
-        const int64_t w0 = ((int64_t)wb - 1) * N;
+        const int w0 = (wb - 1) * N + 2 * tid;           // first sample of this thread in the window (may be < 0)
 #pragma unroll
         for (int n1 = 0; n1 < 16; ++n1) {
-            const int64_t g = w0 + 2 * (tid + M * n1);
-            const float x0 = (g >= 0 && g < len) ? x[g] : 0.f;
-            const float x1 = (g + 1 >= 0 && g + 1 < len) ? x[g + 1] : 0.f;
+            const int g = w0 + 2 * M * n1;
+            // unsigned compares fold the g >= 0 test in
+            const float x0 = (unsigned)g < (unsigned)len ? x[g] : 0.f;
+            const float x1 = (unsigned)(g + 1) < (unsigned)len ? x[g + 1] : 0.f;
             v[n1] = make_float2(x0, x1);
         }
         fft_columns_forward<N>(v, tw, tid);
@@ -167,9 +168,7 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
         fft_rows<N, false>(buf, tw, tid);
         __syncthreads();
         const float2* Hp = H + (size_t)p * (N + 1);
-#pragma unroll
-        for (int i = 0; i <= 8; ++i) {
-            if (i == 8 && tid != 0) break;
+        auto pair = [&](int i) {
             const PairIndex<N> ix(i == 8 ? 0 : half * 8 + i, i == 8 ? M / 2 : k2);
             const float2 A = buf[lds_pad(ix.pos)];
             const float2 B = cconj(buf[lds_pad(ix.pos_partner)]);
@@ -183,7 +182,17 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
                 buf[lds_pad(ix.pos)] = Zk;
                 if (ix.k != 0 && i < 8) buf[lds_pad(ix.pos_partner)] = ZNk;
             }
+        };
+        if constexpr (MULTI) {
+            // the running sums are indexed by the loop counter: kept rolled they stay out of the
+            // register budget of the transforms
+#pragma unroll 1
+            for (int i = 0; i < 8; ++i) pair(i);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) pair(i);
         }
+        if (tid == 0) pair(8);
     }
     if (MULTI) {
 #pragma unroll
@@ -202,11 +211,11 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
 
     // the last N real samples of the 2N-sample window are this block's outputs: n = tid + M n1 >= N/2
     float* y = a.reverb + (size_t)j * a.total + start;
-    const int64_t out0 = (int64_t)b * N;
+    const int out0 = b * N + 2 * tid;
     float e = 0.f;
 #pragma unroll
     for (int n1 = 8; n1 < 16; ++n1) {
-        const int64_t g = out0 + 2 * (tid + M * (n1 - 8));
+        const int g = out0 + 2 * M * (n1 - 8);
         if (g < len) { y[g] = v[n1].x; e += v[n1].x * v[n1].x; }
         if (g + 1 < len) { y[g + 1] = v[n1].y; e += v[n1].y * v[n1].y; }
     }

@@ -112,19 +112,29 @@ template <int R> __device__ inline void twiddle_inputs(float2* v, float2 w1) {
         v[3] = cmul(v[3], w3);
     } else {
         static_assert(R == 16, "radix");
-        float2 w[16];
-        w[1] = w1;
-        w[2] = cmul(w1, w1);
-        w[3] = cmul(w[2], w1);
-        w[4] = cmul(w[2], w[2]);
-        w[5] = cmul(w[4], w1);
-        w[6] = cmul(w[4], w[2]);
-        w[7] = cmul(w[4], w[3]);
-        w[8] = cmul(w[4], w[4]);
-#pragma unroll
-        for (int m = 9; m < 16; ++m) w[m] = cmul(w[8], w[m - 8]);
-#pragma unroll
-        for (int m = 1; m < 16; ++m) v[m] = cmul(v[m], w[m]);
+        // powers are formed and used in an order that keeps few of them alive: w1..w8, then w8 w_m
+        const float2 w2 = cmul(w1, w1);
+        const float2 w3 = cmul(w2, w1);
+        const float2 w4 = cmul(w2, w2);
+        v[1] = cmul(v[1], w1);
+        v[2] = cmul(v[2], w2);
+        v[3] = cmul(v[3], w3);
+        v[4] = cmul(v[4], w4);
+        const float2 w5 = cmul(w4, w1);
+        const float2 w6 = cmul(w4, w2);
+        const float2 w7 = cmul(w4, w3);
+        const float2 w8 = cmul(w4, w4);
+        v[5] = cmul(v[5], w5);
+        v[6] = cmul(v[6], w6);
+        v[7] = cmul(v[7], w7);
+        v[8] = cmul(v[8], w8);
+        v[9] = cmul(v[9], cmul(w8, w1));
+        v[10] = cmul(v[10], cmul(w8, w2));
+        v[11] = cmul(v[11], cmul(w8, w3));
+        v[12] = cmul(v[12], cmul(w8, w4));
+        v[13] = cmul(v[13], cmul(w8, w5));
+        v[14] = cmul(v[14], cmul(w8, w6));
+        v[15] = cmul(v[15], cmul(w8, w7));
     }
 }
 
@@ -145,14 +155,25 @@ struct FftPlan {
     static constexpr int kLastRadix = radix(kPasses - 1);
 };
 
+// lds_pad(a + b) = lds_pad(a) + lds_pad(b) whenever b is a multiple of 16; the address code below
+// uses this to keep one padded base per thread plus compile-time offsets.
+
 // Each thread owns 16 values per pass: 16 / R butterflies j = tid + bi T.
 template <int N, int T, int R>
 __device__ inline void fft_load(float2 (&v)[16], const float2* buf, int tid) {
     static_assert(N == 16 * T, "sixteen values per thread");
+    if constexpr (T % 16 == 0 && (N / R) % 16 == 0) {
+        const float2* base = buf + lds_pad(tid);
 #pragma unroll
-    for (int bi = 0; bi < 16 / R; ++bi)
+        for (int bi = 0; bi < 16 / R; ++bi)
 #pragma unroll
-        for (int m = 0; m < R; ++m) v[bi * R + m] = buf[lds_pad(tid + bi * T + m * (N / R))];
+            for (int m = 0; m < R; ++m) v[bi * R + m] = base[lds_pad(bi * T + m * (N / R))];
+    } else {
+#pragma unroll
+        for (int bi = 0; bi < 16 / R; ++bi)
+#pragma unroll
+            for (int m = 0; m < R; ++m) v[bi * R + m] = buf[lds_pad(tid + bi * T + m * (N / R))];
+    }
 }
 
 template <int N, int T, int R, int NS>
@@ -162,8 +183,18 @@ __device__ inline void fft_store(const float2 (&v)[16], float2* buf, int tid) {
         const int j = tid + bi * T;
         const int k = j % NS;
         const int j0 = (j / NS) * NS * R + k;
+        if constexpr (NS % 16 == 0) {
+            float2* base = buf + lds_pad(j0);
 #pragma unroll
-        for (int r = 0; r < R; ++r) buf[lds_pad(j0 + r * NS)] = v[bi * R + r];
+            for (int r = 0; r < R; ++r) base[lds_pad(r * NS)] = v[bi * R + r];
+        } else if constexpr (NS == 1 && R == 16) {
+            float2* base = buf + 17 * j;                 // lds_pad(16 j + r) = 17 j + r
+#pragma unroll
+            for (int r = 0; r < R; ++r) base[r] = v[bi * R + r];
+        } else {
+#pragma unroll
+            for (int r = 0; r < R; ++r) buf[lds_pad(j0 + r * NS)] = v[bi * R + r];
+        }
     }
 }
 
@@ -226,15 +257,29 @@ __device__ inline void fft_passes(float2 (&v)[16], float2* buf, const float2* __
 // Store the last pass's outputs in natural order.
 template <int N, int T>
 __device__ inline void fft_store_natural(const float2 (&v)[16], float2* buf, int tid) {
+    constexpr int R = FftPlan<N>::kLastRadix;
+    if constexpr (T % 16 == 0 && (N / R) % 16 == 0) {
+        float2* base = buf + lds_pad(tid);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) buf[lds_pad(fft_out_index<N, T>(tid, i))] = v[i];
+        for (int i = 0; i < 16; ++i) base[lds_pad((i / R) * T + (i % R) * (N / R))] = v[i];
+    } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) buf[lds_pad(fft_out_index<N, T>(tid, i))] = v[i];
+    }
 }
 
 // Load the first pass's inputs from a natural-order buffer.
 template <int N, int T>
 __device__ inline void fft_load_natural(float2 (&v)[16], const float2* buf, int tid) {
+    constexpr int R = FftPlan<N>::radix(0);
+    if constexpr (T % 16 == 0 && (N / R) % 16 == 0) {
+        const float2* base = buf + lds_pad(tid);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) v[i] = buf[lds_pad(fft_in_index<N, T>(tid, i))];
+        for (int i = 0; i < 16; ++i) v[i] = base[lds_pad((i / R) * T + (i % R) * (N / R))];
+    } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = buf[lds_pad(fft_in_index<N, T>(tid, i))];
+    }
 }
 
 // ---- N = 16 x M split -------------------------------------------------------------------
@@ -263,13 +308,16 @@ __device__ inline void fft_columns_inverse(float2 (&v)[16], const float2* __rest
 
 template <int N, int T>
 __device__ inline void fft_columns_store(const float2 (&v)[16], float2* buf, int n2) {
+    static_assert((N / 16) % 16 == 0, "rows are whole padding groups");
+    float2* base = buf + lds_pad(n2);
 #pragma unroll
-    for (int k1 = 0; k1 < 16; ++k1) buf[lds_pad(k1 * (N / 16) + n2)] = v[k1];
+    for (int k1 = 0; k1 < 16; ++k1) base[lds_pad(k1 * (N / 16))] = v[k1];
 }
 template <int N, int T>
 __device__ inline void fft_columns_load(float2 (&v)[16], const float2* buf, int n2) {
+    const float2* base = buf + lds_pad(n2);
 #pragma unroll
-    for (int k1 = 0; k1 < 16; ++k1) v[k1] = buf[lds_pad(k1 * (N / 16) + n2)];
+    for (int k1 = 0; k1 < 16; ++k1) v[k1] = base[lds_pad(k1 * (N / 16))];
 }
 
 // The 16 row transforms, in place in natural order within each row; wave-level synchronisation only.
