@@ -129,40 +129,72 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
     }
     __syncthreads();
     const int k_lo = s_kstart[sub], k_hi = s_kstart[sub + 1];
+    const bool pairs_aligned = ((start & 1) == 0) && ((hop & 1) == 0) &&
+                               ((reinterpret_cast<uintptr_t>(a.wave) & 7) == 0);
 
     for (int it = 0; it < a.frames_per_group / kMelSlots; ++it) {
         const int64_t t = (int64_t)first + it * kMelSlots + slot;
         const bool live = t < n_frames_u;
         float2 v[16];
+        const float* xf = x + t * hop;
+        if (pairs_aligned) {                              // even sample offset: one 8-byte load per complex input
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int i0 = 2 * fft_in_index<NC, kMelLanes>(sub, i);
-            float re = 0.f, im = 0.f;
-            if (live) {
-                if (i0 < win) re = x[t * hop + i0] * wnd[i].x;
-                if (i0 + 1 < win) im = x[t * hop + i0 + 1] * wnd[i].y;
+            for (int i = 0; i < 16; ++i) {
+                const int i0 = 2 * fft_in_index<NC, kMelLanes>(sub, i);
+                float2 s2 = make_float2(0.f, 0.f);
+                if (live && i0 + 1 < win) s2 = *reinterpret_cast<const float2*>(xf + i0);
+                else if (live && i0 < win) s2.x = xf[i0];
+                v[i] = make_float2(s2.x * wnd[i].x, s2.y * wnd[i].y);
             }
-            v[i] = make_float2(re, im);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int i0 = 2 * fft_in_index<NC, kMelLanes>(sub, i);
+                float re = 0.f, im = 0.f;
+                if (live) {
+                    if (i0 < win) re = xf[i0] * wnd[i].x;
+                    if (i0 + 1 < win) im = xf[i0 + 1] * wnd[i].y;
+                }
+                v[i] = make_float2(re, im);
+            }
         }
         fft_passes<NC, kMelLanes, false, FftSync::Wave>(v, buf, tw, sub);
         fft_store_natural<NC, kMelLanes>(v, buf, sub);
         for (int m = sub; m < 2 * n_seg; m += kMelLanes) A[m] = 0.f;
         fft_sync<FftSync::Wave>();                       // a frame's 16 lanes share a wavefront
 
-        // power of bins [k_lo, k_hi) -> per-band sums; this lane owns every band it meets
+        // Bin powers, two at a time: with E = (Z[k] + conj Z[N-k])/2, O = -(i/2)(Z[k] - conj Z[N-k]) and
+        // w = exp(-i pi k / N):  X[k] = E + w O and conj(X[N-k]) = E - w O.
+        // P[k] replaces the real part of slot k (k < N); P[N] goes to the imaginary part of slot 0.
+        // Pair (k, N-k) is read and overwritten by one lane only.
+#pragma unroll
+        for (int i = 0; i <= NC / 2 / kMelLanes; ++i) {
+            if (i == NC / 2 / kMelLanes && sub != 0) break;
+            const int k = sub + kMelLanes * i;            // 0..N/2
+            const int kn = (NC - k) & (NC - 1);
+            const float2 Zk = buf[lds_pad(k)];
+            const float2 Zn = buf[lds_pad(kn)];
+            const float2 w = s_tw[k];
+            const float2 E = make_float2(0.5f * (Zk.x + Zn.x), 0.5f * (Zk.y - Zn.y));
+            const float2 O = make_float2(0.5f * (Zk.y + Zn.y), -0.5f * (Zk.x - Zn.x));
+            const float2 wO = cmul(w, O);
+            // sums first, then squares: a weak bin next to a strong mirror bin keeps its relative accuracy
+            const float2 Xk = cadd(E, wO), Xn = csub(E, wO);
+            const float p_lo = Xk.x * Xk.x + Xk.y * Xk.y, p_hi = Xn.x * Xn.x + Xn.y * Xn.y;
+            if (k == 0) {
+                buf[lds_pad(0)] = make_float2(p_lo, p_hi);
+            } else {
+                buf[lds_pad(k)].x = p_lo;
+                buf[lds_pad(kn)].x = p_hi;
+            }
+        }
+        fft_sync<FftSync::Wave>();
+
+        // bins [k_lo, k_hi) -> per-band sums; this lane owns every band it meets
         float run_a = 0.f, run_b = 0.f;
         int cur = -100;
         for (int k = k_lo; k < k_hi; ++k) {
-            const int kk = k & (NC - 1);
-            const float2 Zk = buf[lds_pad(kk)];
-            const float2 Zn = buf[lds_pad((NC - kk) & (NC - 1))];
-            const float2 w = s_tw[k];
-            // X[k] = E + w O,  E = (Z[k] + conj Z[N-k])/2,  O = -(i/2)(Z[k] - conj Z[N-k])
-            const float2 E = make_float2(0.5f * (Zk.x + Zn.x), 0.5f * (Zk.y - Zn.y));
-            const float2 d = make_float2(Zk.x - Zn.x, Zk.y + Zn.y);
-            const float2 O = make_float2(0.5f * d.y, -0.5f * d.x);
-            const float2 X = cadd(E, cmul(w, O));
-            const float p = X.x * X.x + X.y * X.y;
+            const float p = k < NC ? buf[lds_pad(k)].x : buf[lds_pad(0)].y;
             const float2 cw = s_tab[k];
             const int c = (int)cw.x;
             if (c != cur) {
