@@ -87,9 +87,10 @@ constexpr int kMelLanes = 16;                            // lanes per frame
 constexpr int kMelSlots = kMelThreads / kMelLanes;       // frames in flight per work group
 
 // K = 512: 256-point complex FFT per frame, 16 lanes per frame, 16 frames per pass of the group.
-template <int NC>
+// WIN: the window length when it is known at compile time (the paper's front end uses 400), else 0.
+template <int NC, int WIN>
 __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const float2* __restrict__ tw, int tab_stride) {
-    static_assert(NC / 16 == kMelLanes, "sixteen lanes per frame");
+    static_assert(NC == 256 && NC / 16 == kMelLanes, "two radix-16 passes, sixteen lanes per frame");
     extern __shared__ __align__(16) unsigned char smem[];
     const int n_mel = a.cfg.n_mel;
     const int n_seg = n_mel + 2;                         // band sums A[c], B[c] for c = 0..n_mel (+1 pad)
@@ -106,7 +107,7 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
     const int64_t start = a.offsets[u];
     const int64_t n_frames_u = a.frame_offsets[u + 1] - a.frame_offsets[u];
     const float* x = a.wave + start;
-    const int win = a.cfg.win, hop = a.cfg.hop;
+    const int win = WIN ? WIN : a.cfg.win, hop = a.cfg.hop;
     const float power = a.cfg.power;
     float* feats = a.feats + (size_t)a.frame_offsets[u] * n_mel;
     float2* buf = fft_buf + slot * lds_padded_size(NC);
@@ -124,9 +125,13 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
     float2 wnd[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        const int i0 = 2 * fft_in_index<NC, kMelLanes>(sub, i);
+        const int i0 = 2 * (sub + kMelLanes * i);
         wnd[i] = make_float2(i0 < win ? a.window[i0] : 0.f, i0 + 1 < win ? a.window[i0 + 1] : 0.f);
     }
+    // twiddles of the second pass, exp(-2 pi i sub m / NC), are the same for every frame of this lane
+    float2 twp[16];
+#pragma unroll
+    for (int m = 1; m < 16; ++m) twp[m] = tw[(sub * m) & (NC - 1)];
     __syncthreads();
     const int k_lo = s_kstart[sub], k_hi = s_kstart[sub + 1];
     const bool pairs_aligned = ((start & 1) == 0) && ((hop & 1) == 0) &&
@@ -136,29 +141,38 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
         const int64_t t = (int64_t)first + it * kMelSlots + slot;
         const bool live = t < n_frames_u;
         float2 v[16];
-        const float* xf = x + t * hop;
+        const int x0 = (int)t * hop;                      // first sample of the frame (utterances are < 2^30 samples)
         if (pairs_aligned) {                              // even sample offset: one 8-byte load per complex input
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int i0 = 2 * fft_in_index<NC, kMelLanes>(sub, i);
+                const int i0 = 2 * (sub + kMelLanes * i);
                 float2 s2 = make_float2(0.f, 0.f);
-                if (live && i0 + 1 < win) s2 = *reinterpret_cast<const float2*>(xf + i0);
-                else if (live && i0 < win) s2.x = xf[i0];
+                if (live && i0 + 1 < win) s2 = *reinterpret_cast<const float2*>(x + (x0 + i0));
+                else if (live && i0 < win) s2.x = x[x0 + i0];
                 v[i] = make_float2(s2.x * wnd[i].x, s2.y * wnd[i].y);
             }
         } else {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int i0 = 2 * fft_in_index<NC, kMelLanes>(sub, i);
+                const int i0 = 2 * (sub + kMelLanes * i);
                 float re = 0.f, im = 0.f;
                 if (live) {
-                    if (i0 < win) re = xf[i0] * wnd[i].x;
-                    if (i0 + 1 < win) im = xf[i0 + 1] * wnd[i].y;
+                    if (i0 < win) re = x[x0 + i0] * wnd[i].x;
+                    if (i0 + 1 < win) im = x[x0 + i0 + 1] * wnd[i].y;
                 }
                 v[i] = make_float2(re, im);
             }
         }
-        fft_passes<NC, kMelLanes, false, FftSync::Wave>(v, buf, tw, sub);
+        // 256 = 16 x 16: first pass without twiddles (inputs past the window are zero and fold away when
+        // WIN is known), exchange through LDS, second pass with this lane's fixed twiddles
+        SmallDft<16, false>::run(v);
+        fft_store<NC, kMelLanes, 16, 1>(v, buf, sub);
+        fft_sync<FftSync::Wave>();
+        fft_load<NC, kMelLanes, 16>(v, buf, sub);
+        fft_sync<FftSync::Wave>();
+#pragma unroll
+        for (int m = 1; m < 16; ++m) v[m] = cmul(v[m], twp[m]);
+        SmallDft<16, false>::run(v);
         fft_store_natural<NC, kMelLanes>(v, buf, sub);
         for (int m = sub; m < 2 * n_seg; m += kMelLanes) A[m] = 0.f;
         fft_sync<FftSync::Wave>();                       // a frame's 16 lanes share a wavefront
@@ -250,7 +264,10 @@ hipError_t launch_mel(hipStream_t s, const MelArgs& a) {
     constexpr int NC = 256;
     const size_t lds = sizeof(float2) * (kMelSlots * lds_padded_size(NC) + 2 * (NC + 1)) +
                        sizeof(float) * kMelSlots * 2 * (a.cfg.n_mel + 2) + sizeof(int) * 20;
-    mel_kernel<NC><<<dim3((unsigned)a.n_items), dim3(kMelThreads), lds, s>>>(a, a.twiddle, mel_table_stride(a.cfg.nfft));
+    if (a.cfg.win == 400)
+        mel_kernel<NC, 400><<<dim3((unsigned)a.n_items), dim3(kMelThreads), lds, s>>>(a, a.twiddle, mel_table_stride(a.cfg.nfft));
+    else
+        mel_kernel<NC, 0><<<dim3((unsigned)a.n_items), dim3(kMelThreads), lds, s>>>(a, a.twiddle, mel_table_stride(a.cfg.nfft));
     return hipGetLastError();
 }
 

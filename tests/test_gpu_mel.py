@@ -92,3 +92,19 @@ def test_other_mel_counts_and_band(aug):
     ref = O.vtlp_mel_batch(w.offsets, w.speech, w.alpha, fe)
     assert f.shape == ref.shape == (196, 23)
     assert feat_err(f, ref) <= FEAT_TOL
+
+
+@pytest.mark.parametrize("win,hop", [(320, 128), (400, 161), (512, 256), (33, 7)])
+def test_other_window_and_hop(aug, win, hop):
+    import dataclasses
+    fe = dataclasses.replace(FE, win=win, hop=hop)
+    rng = np.random.default_rng(win + hop)
+    lens = [3001, 0, 2000, win, win - 1, 4097]
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    x = rng.standard_normal(int(offsets[-1])).astype(np.float32)
+    alpha = rng.uniform(0.8, 1.2, len(lens)).astype(np.float32)
+    print(f"case: win={win} hop={hop}", flush=True)
+    f = _run(aug, offsets, x, alpha, fe)
+    ref = O.vtlp_mel_batch(offsets, x, alpha, fe)
+    assert f.shape == ref.shape and f.shape[0] > 0
+    assert feat_err(f, ref) <= FEAT_TOL
