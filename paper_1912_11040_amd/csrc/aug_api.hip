@@ -208,9 +208,9 @@ int mark(aug_ctx* ctx, int stage) {
 int run_rir(aug_ctx* ctx, int n_rir, const float* geom, int rir_len, float fs, float c, float* rir_out,
             int32_t* tap_count_out) {
     const double k = (double)fs / (double)c;
-    AUG_HIP(ctx->rir_items.reserve(aug::rir_item_bytes() * (size_t)n_rir * aug::rir_items_per_response(rir_len)),
+    AUG_HIP(ctx->rir_items.reserve(2 * aug::rir_item_bytes() * (size_t)n_rir * aug::rir_items_per_response(rir_len)),
             "response item table");
-    AUG_HIP(ctx->rir_ctrl.reserve(2 * sizeof(int)), "response item counter");
+    AUG_HIP(ctx->rir_ctrl.reserve(aug::rir_ctrl_ints() * sizeof(int)), "response item counter");
     AUG_HIP(ctx->rir_pow.reserve(sizeof(float) * (size_t)n_rir * aug::rir_pow_entries()), "reflection table");
     const int n_groups = 2 * ctx->n_cu;
     AUG_TRY(mark(ctx, -1));

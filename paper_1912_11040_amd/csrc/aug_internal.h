@@ -49,7 +49,7 @@ struct aug_ctx {
     // image-method work list
     int n_cu = 0;                        // compute units of the device
     aug::DeviceBuffer rir_items;         // Item [n_rir * items_per_response]
-    aug::DeviceBuffer rir_ctrl;          // int [2]: item count, next item
+    aug::DeviceBuffer rir_ctrl;          // int [rir_ctrl_ints()]: item count, next item, class counters
     aug::DeviceBuffer rir_pow;           // float [n_rir][pow entries]: beta^k
 
     // intermediate results
@@ -73,11 +73,13 @@ namespace aug {
 // ---- kernels' host launchers (each checks nothing; arguments are validated by the API layer) ----
 
 // Image-method impulse responses.  launch_rir_plan cuts every response into items (tap ranges of
-// about equal image count), fills the beta^k tables and resets ctrl = {item count, next item};
+// about equal image count) ordered heaviest first, fills the beta^k tables and resets ctrl (item count,
+// next item, class counters: rir_ctrl_ints() ints); `items` needs room for 2 n_rir rir_items_per_response items;
 // launch_rir then runs n_groups persistent work groups over the items, writing either
 // rir_out float [n_rir][rir_len] or, if rir_out is null, tap counts cnt_out int32 [n_rir][rir_len].
 int rir_items_per_response(int rir_len);
 size_t rir_item_bytes();
+int rir_ctrl_ints();
 int rir_pow_entries();
 hipError_t launch_rir_plan(hipStream_t s, int n_rir, const float* geom, int rir_len, double fs_over_c,
                            void* items, int* ctrl, float* pow_table);

@@ -14,14 +14,20 @@
 // bound; the rare remaining images take the exact correctly-rounded sqrt.
 //
 // Layout of the work
-//   * plan kernel: one thread per response cuts its taps into shells [n0, n1) of about
-//     equal image count (equal volume of the spherical shell) and at most kMaxTaps taps,
-//     and appends them to an item table.
+//   * plan kernels: one thread per response cuts its taps into shells [n0, n1) of about
+//     equal image count (equal volume of the spherical shell) and at most kMaxTaps taps, with an
+//     estimate of each shell's work; a counting sort orders the items heaviest first.
 //   * image kernel: persistent work groups fetch items from a counter.  An item owns its
 //     taps, so sums live in LDS and are stored once, without global atomics.
-//     A wave takes 64 (x image, y image) columns at a time; each column contributes up to
-//     four runs of consecutive z images inside the shell.  Runs are cut into pieces of at
-//     most kPiece images, the pieces are dealt to lanes, and each lane walks its piece.
+//     The z images of the response (both q, both signs) are merged into one LDS table sorted by
+//     dz*dz, so the images of an (x image, y image) column that can fall inside the shell are one
+//     contiguous range of that table, found by two binary searches on r_in^2 - a and r_out^2 - a.
+//     The y images are sorted the same way, so the live columns of an x image are a prefix of the
+//     y table; a prefix sum over the x images numbers the live columns and dead ones are never seen.
+//     A wave takes 64 live columns at a time; their z ranges are cut into pieces of at most kPiece
+//     images, a wave scan numbers the pieces, lanes take pieces by binary search and walk them.
+//     Rooms so flat or narrow that an axis has more images than the tables hold take a plain path
+//     (all columns of the bounding box, every z image of a live column).
 //   * amplitudes accumulate as 64-bit fixed point (2^-56) with integer LDS atomics:
 //     gfx950 executes float LDS atomics about thirty times slower than integer ones, and
 //     integer sums do not depend on the order of arrival.
@@ -33,12 +39,12 @@ namespace {
 
 constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / 64;
-constexpr int kMaxTaps = 6016;            // taps owned by one item (LDS: 8 bytes each)
+constexpr int kMaxTaps = 5120;            // taps owned by one item (LDS: 8 bytes each)
 constexpr int kMinTaps = 64;
 constexpr int kPow = 1024;                // beta^k table entries held in LDS
-constexpr int kZCap = 320;                // z images per q held in LDS; more than that: computed in the loop
+constexpr int kAxisCap = 320;             // y or z images per q held in the sorted LDS tables 
 constexpr int kPiece = 16;                // images per piece
-constexpr float kTargetImages = 800000.f; // images per item aimed for (before reflection cuts)
+constexpr float kTargetWork = 600000.f;   // work per item aimed for, in image visits (see item_cost)
 constexpr int kMaxShells = 96;            // volume-balanced shells per response, at most
 
 #pragma clang fp contract(off)
@@ -60,19 +66,59 @@ __device__ inline bool room_ok(const float* g) {
     return (g[0] >= 0.1f) && (g[1] >= 0.1f) && (g[2] >= 0.1f) && (g[0] * g[1] * g[2] < 1e30f);
 }
 
-struct Item { int rir, n0, n1; };
+struct Item { int rir, n0, n1, cls; };
 
-// ctrl[0] = number of items, ctrl[1] = next item to hand out
+constexpr int kClasses = 32;            // cost classes for the order in which items are handed out
+// ctrl: [0] number of items, [1] next item to hand out, [2 .. 2+kClasses) items per class,
+// [2+kClasses .. 2+2 kClasses) next free slot of each class in the sorted table
+constexpr int kCtrlInts = 2 + 2 * kClasses;
+
+// Fraction of the images at distance d that the reflection cut keeps: an image in direction u has
+// about d (|ux|/Lx + |uy|/Ly + |uz|/Lz) reflections, so this is the share of directions whose
+// reflections per metre stay under cut / d, counted on a fixed 8 x 8 equal-area lattice of an octant.
+__device__ inline float kept_fraction(const float* g, float log2_beta, float d) {
+    if (!(log2_beta < 0.f) || !(d > 1e-3f)) return 1.f;
+    const float per_metre = (__log2f(12.566371f * d) - 57.f) / (log2_beta * d);
+    const float ix = 1.f / g[0], iy = 1.f / g[1], iz = 1.f / g[2];
+    int kept = 0;
+    for (int i = 0; i < 8; ++i) {
+        const float uz = (i + 0.5f) * 0.125f, rho = sqrtf(1.f - uz * uz);
+        for (int j = 0; j < 8; ++j) {
+            float sn, cs;
+            __sincosf((j + 0.5f) * 0.19634954f, &sn, &cs);
+            kept += (rho * cs * ix + rho * sn * iy + uz * iz) <= per_metre;
+        }
+    }
+    return fmaxf((float)kept * (1.f / 64.f), 1.f / 128.f);
+}
+
+// Work of one item in units of one image visit: the images it keeps plus about twelve visits' worth
+// of set-up for every live (x image, y image) column inside its outer radius.
+__device__ inline float item_cost(const float* g, float log2_beta, float est_images, float rir_len, float n0, float n1,
+                                  float metres_per_tap) {
+    const float share = (n1 * n1 * n1 - n0 * n0 * n0) / (rir_len * rir_len * rir_len);
+    const float f = kept_fraction(g, log2_beta, 0.5f * (n0 + n1) * metres_per_tap);
+    const float r_out = n1 * metres_per_tap;
+    const float columns = 3.14159265f * r_out * r_out / (g[0] * g[1]);
+    return est_images * share * f + 12.f * columns * __powf(f, 0.6667f);
+}
+
+// One thread per response: cut its taps into shells of about equal image count (equal volume), at most
+// kMaxTaps wide, and append them with a cost class to the unsorted item table.
 __global__ void rir_plan_kernel(int n_rir, const float* __restrict__ geom, int rir_len, double k_fs_c,
-                                Item* __restrict__ items, int items_per_rir, int* __restrict__ ctrl) {
+                                Item* __restrict__ unsorted, int items_per_rir, int* __restrict__ ctrl) {
     const int r = blockIdx.x * blockDim.x + threadIdx.x;
     if (r >= n_rir) return;
     const float* g = geom + (size_t)r * 10;
     const double radius = (double)rir_len / k_fs_c;
-    float shells = 1.f;
-    if (room_ok(g)) {
-        const float est = 4.18879f * (float)(radius * radius * radius) / (g[0] * g[1] * g[2]);
-        shells = fminf(fmaxf(ceilf(est / kTargetImages), 1.f), (float)kMaxShells);
+    const float metres_per_tap = (float)(1.0 / k_fs_c);
+    const bool ok = room_ok(g);
+    const float log2_beta = (ok && g[9] > 0.f && g[9] < 1.f) ? __log2f(g[9]) : 0.f;
+    float shells = 1.f, est = 0.f;
+    if (ok) {
+        est = 4.18879f * (float)(radius * radius * radius) / (g[0] * g[1] * g[2]);
+        const float work = item_cost(g, log2_beta, est, (float)rir_len, 0.f, (float)rir_len, metres_per_tap);
+        shells = fminf(fmaxf(ceilf(work / kTargetWork), 1.f), (float)kMaxShells);
     }
     const double L3 = (double)rir_len * rir_len * rir_len;
     const double step = L3 / (double)shells;
@@ -95,9 +141,48 @@ __global__ void rir_plan_kernel(int n_rir, const float* __restrict__ geom, int r
     const int base = atomicAdd(&ctrl[0], count);
     int lo = 0;
     for (int i = 0; i < count; ++i) {
-        items[base + i] = Item{r, lo, bounds[i]};
+        unsorted[base + i] = Item{r, lo, bounds[i], kClasses - 1};
         lo = bounds[i];
     }
+}
+
+// one thread per item: its cost class (0 = heaviest), and the class census
+__global__ void rir_classify_kernel(const float* __restrict__ geom, int rir_len, double k_fs_c,
+                                    Item* __restrict__ unsorted, int* __restrict__ ctrl) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= ctrl[0]) return;
+    Item it = unsorted[i];
+    const float* g = geom + (size_t)it.rir * 10;
+    int cls = kClasses - 1;
+    if (room_ok(g)) {
+        const double radius = (double)rir_len / k_fs_c;
+        const float est = 4.18879f * (float)(radius * radius * radius) / (g[0] * g[1] * g[2]);
+        const float log2_beta = (g[9] > 0.f && g[9] < 1.f) ? __log2f(g[9]) : 0.f;
+        const float cost = item_cost(g, log2_beta, est, (float)rir_len, (float)it.n0, (float)it.n1, (float)(1.0 / k_fs_c));
+        cls = min(max((int)(2.5f * __log2f(4.0e6f / fmaxf(cost, 1.f))), 0), kClasses - 1);
+    }
+    unsorted[i].cls = cls;
+    atomicAdd(&ctrl[2 + cls], 1);
+}
+
+// first slot of each class in the sorted table, heaviest class first
+__global__ void rir_class_offsets_kernel(int* __restrict__ ctrl) {
+    if (threadIdx.x == 0) {
+        int at = 0;
+        for (int c = 0; c < kClasses; ++c) {
+            ctrl[2 + kClasses + c] = at;
+            at += ctrl[2 + c];
+        }
+    }
+}
+
+// Items move to their class's stretch of the sorted table: persistent groups then take the heaviest
+// items first and finish on the light ones, which evens out their finishing times.
+__global__ void rir_sort_items_kernel(const Item* __restrict__ unsorted, Item* __restrict__ sorted, int* __restrict__ ctrl) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= ctrl[0]) return;
+    const Item it = unsorted[i];
+    sorted[atomicAdd(&ctrl[2 + kClasses + it.cls], 1)] = it;
 }
 
 __global__ void rir_pow_kernel(int n_rir, const float* __restrict__ geom, float* __restrict__ table) {
@@ -108,12 +193,11 @@ __global__ void rir_pow_kernel(int n_rir, const float* __restrict__ geom, float*
 }
 
 // per-column record shared through LDS between the lane that built it and the lanes that walk its pieces
-struct __align__(16) Column {
+struct __align__(8) Column {
     double a;            // dx*dx + dy*dy
     int kxy;             // reflections along x and y
     int pfx;             // inclusive prefix of piece counts within the wave's batch
-    short start[4];      // first n of runs (q=0: runs 0,1; q=1: runs 2,3)
-    short len[4];
+    unsigned short start, len;   // range of the sorted z table that can fall inside the shell
 };
 
 __device__ inline int wave_inclusive_scan(int v, int lane) {
@@ -125,10 +209,13 @@ __device__ inline int wave_inclusive_scan(int v, int lane) {
     return v;
 }
 
-struct __align__(16) ZEntry {
-    double dz2;          // squared z distance of image (q, n), reference operation order
-    float bz;            // beta^(|n-q| + |n|)
-    float pad;
+// One image along an axis, as stored in the sorted tables: key = squared distance to the microphone
+// along that axis (reference operation order); aux = beta^reflections as float bits (z axis) or the
+// reflection count (y axis).
+struct __align__(16) AxisImage {
+    double key;
+    int aux;
+    int pad;
 };
 
 struct WalkCtx {
@@ -138,6 +225,12 @@ struct WalkCtx {
     int n0, n_taps;
 };
 
+// the reference recipe, kept out of line so that the estimate's loop stays short
+__device__ __attribute__((noinline)) int exact_tap(double d2, double k_fs_c) {
+    const double d = __dsqrt_rn(d2);
+    return (int)__dadd_rn(__dmul_rn(d, k_fs_c), 0.5);     // positive: truncation is floor
+}
+
 // Largest reflection count k whose amplitude beta^k / (4 pi d) can still reach one unit of the
 // 2^-56 fixed point at distance d_min or beyond, with a factor-of-two margin and one count of slack;
 // "no limit" when beta is 0, >= 1 (log2_beta == 0 encodes both) or d_min is tiny.
@@ -146,12 +239,6 @@ __device__ inline int reflection_cut(float log2_beta, float d_min) {
     // beta^k >= 4 pi d 2^-57  <=>  k <= (log2(4 pi d) - 57) / log2(beta)
     const float k = (__log2f(12.566371f * d_min) - 57.f) / log2_beta;
     return k > 1.0e6f ? (1 << 20) : (int)k + 2;
-}
-
-// the reference recipe, kept out of line so that the estimate's loop stays short
-__device__ __attribute__((noinline)) int exact_tap(double d2, double k_fs_c) {
-    const double d = __dsqrt_rn(d2);
-    return (int)__dadd_rn(__dmul_rn(d, k_fs_c), 0.5);     // positive: truncation is floor
 }
 
 // Tap index of an image at squared distance d2, and y ~ 1/sqrt(d2) for its amplitude.
@@ -184,30 +271,87 @@ __device__ inline void deposit(const WalkCtx& w, int idx, float x, unsigned long
 }
 
 template <bool COUNT>
-__device__ inline void walk_piece_table(const WalkCtx& w, double a, float cxy, const ZEntry* z, int len,
+__device__ inline void walk_piece_table(const WalkCtx& w, double a, float cxy, const AxisImage* z, int len,
                                         unsigned long long* hist, unsigned int* hist32) {
     for (int i = 0; i < len; ++i) {
-        const ZEntry e = z[i];
-        const double d2 = __dadd_rn(a, e.dz2);
+        const AxisImage e = z[i];
+        const double d2 = __dadd_rn(a, e.key);
         float y;
         const int idx = tap_index(w, d2, y);
-        deposit<COUNT>(w, idx, (e.bz * y) * cxy, hist, hist32);
+        deposit<COUNT>(w, idx, (__int_as_float(e.aux) * y) * cxy, hist, hist32);
     }
 }
 
 template <bool COUNT>
-__device__ inline void walk_piece_direct(const WalkCtx& w, const Axis& az, double a, float cxy, int q, int first,
-                                         int len, unsigned long long* hist, unsigned int* hist32) {
-    for (int i = 0; i < len; ++i) {
-        const int n = first + i;
-        const double dz = axis_delta(az, q, n);
-        const double d2 = __dadd_rn(a, __dmul_rn(dz, dz));
-        float y;
-        const int idx = tap_index(w, d2, y);
-        float bz = 0.f;
-        if (!COUNT) bz = (float)pow(w.beta, (double)(iabs(n - q) + iabs(n)));
-        deposit<COUNT>(w, idx, (bz * y) * cxy, hist, hist32);
+__device__ inline void walk_column_direct(const WalkCtx& w, const Axis& az, double a, float cxy, int nmz,
+                                          unsigned long long* hist, unsigned int* hist32) {
+    for (int q = 0; q < 2; ++q)
+        for (int n = -nmz; n <= nmz; ++n) {
+            const double dz = axis_delta(az, q, n);
+            const double d2 = __dadd_rn(a, __dmul_rn(dz, dz));
+            float y;
+            const int idx = tap_index(w, d2, y);
+            float bz = 0.f;
+            if (!COUNT) bz = (float)pow(w.beta, (double)(iabs(n - q) + iabs(n)));
+            deposit<COUNT>(w, idx, (bz * y) * cxy, hist, hist32);
+        }
+}
+
+// All images (1 - 2q) s + 2 n L - m, q in {0,1}, |n| <= nm, of one axis, written to `out` in order of
+// squared distance.  For each q the signed distance grows with n, so the images with negative
+// distance (walked towards smaller n) and those with non-negative distance are two sorted lists;
+// an image's place in the merged order is its place in its own list plus, by binary search, the
+// number of images of the other three lists that sort before it (ties go to the lower list).
+// All threads of the group must call; aux(q, n) supplies the entry's second field.
+template <class Aux>
+__device__ inline void build_sorted_images(const Axis& ax, int nm, int* s_split, AxisImage* out, int tid, Aux aux) {
+    const int per_q = 2 * nm + 1, n_all = 2 * per_q;
+    if (tid < 2) s_split[tid] = per_q;
+    __syncthreads();
+    for (int i = tid; i < n_all; i += kThreads) {
+        const int q = i >= per_q, n = i - q * per_q - nm;
+        if (axis_delta(ax, q, n) >= 0.0 && (n == -nm || axis_delta(ax, q, n - 1) < 0.0)) s_split[q] = n + nm;
     }
+    __syncthreads();
+    auto key_at = [&](int l, int pos) {           // list l = 2 q + side, position pos in walking order
+        const int sp = s_split[l >> 1];
+        const double d = axis_delta(ax, l >> 1, ((l & 1) ? sp + pos : sp - 1 - pos) - nm);
+        return __dmul_rn(d, d);
+    };
+    for (int i = tid; i < n_all; i += kThreads) {
+        const int q = i >= per_q, t = i - q * per_q, sp = s_split[q];
+        const int side = t >= sp, own = 2 * q + side;
+        const double d = axis_delta(ax, q, t - nm);
+        const double key = __dmul_rn(d, d);
+        int rank = side ? t - sp : sp - 1 - t;
+#pragma unroll
+        for (int l = 0; l < 4; ++l) {
+            if (l == own) continue;
+            int lo = 0, hi = (l & 1) ? per_q - s_split[l >> 1] : s_split[l >> 1];
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                const double km = key_at(l, mid);
+                if (km < key || (km == key && l < own)) lo = mid + 1; else hi = mid;
+            }
+            rank += lo;
+        }
+        AxisImage e;
+        e.key = key;
+        e.aux = aux(q, t - nm);
+        e.pad = 0;
+        out[rank] = e;
+    }
+    __syncthreads();
+}
+
+// number of entries of a sorted table with key <= bound
+__device__ inline int count_not_above(const AxisImage* tab, int n, double bound) {
+    int lo = 0, hi = n;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (tab[mid].key <= bound) lo = mid + 1; else hi = mid;
+    }
+    return lo;
 }
 
 template <bool COUNT>
@@ -217,7 +361,10 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
     int32_t* __restrict__ cnt_out) {
     __shared__ unsigned long long hist[COUNT ? kMaxTaps / 2 : kMaxTaps];
     __shared__ float bpow[COUNT ? 1 : kPow];
-    __shared__ ZEntry ztab[2 * kZCap];
+    __shared__ AxisImage ztab[2 * kAxisCap];       // z images sorted by dz*dz
+    __shared__ AxisImage ytab[2 * kAxisCap];       // y images sorted by dy*dy
+    __shared__ int row_pfx[2 * kAxisCap];          // per x image: inclusive prefix of live column counts
+    __shared__ int s_split[2];
     __shared__ Column cols[kWaves][64];
     __shared__ int s_item;
     unsigned int* hist32 = reinterpret_cast<unsigned int*>(hist);
@@ -261,11 +408,7 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
             const int nmz = (int)ceil(r_out / (2.0 * az.room)) + 1;
             nmx = min(nmx, k_cut_item / 2 + 1);          // |n - q| + |n| >= 2 |n| - 1
             nmy = min(nmy, k_cut_item / 2 + 1);
-            const int nix = 2 * (2 * nmx + 1), niy = 2 * (2 * nmy + 1);
-            const int n_cand = nix * niy;
-            const float inv_two_lzf = (float)(1.0 / (2.0 * az.room));
-            const float z0qf[2] = {(float)(az.src - az.mic), (float)(-az.src - az.mic)};
-            const int n_batch = (n_cand + 63) / 64;
+            const int nix = 2 * (2 * nmx + 1), niy = 2 * (2 * nmy + 1), niz = 2 * (2 * nmz + 1);
             Column* wc = cols[wave];
             WalkCtx wctx;
             wctx.k_fs_c = k_fs_c;
@@ -273,72 +416,107 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
             wctx.n0 = n0;
             wctx.n_taps = n_taps;
             wctx.beta = beta;
+            const float y0_max = fmaxf(fabsf((float)(ay.src - ay.mic)), fabsf((float)(ay.src + ay.mic)));
+            const float z0_max = fmaxf(fabsf((float)(az.src - az.mic)), fabsf((float)(az.src + az.mic)));
+            const float lyf = (float)ay.room, lzf = (float)az.room;
+            // every image with at most k reflections along an axis lies within max|c_q| + (k + 1) L of the
+            // microphone on that axis; squared, with a little slack, this bounds the table range to visit
+            auto reach2 = [](float c_max, float room, int k) {
+                const float r = c_max + (float)(k + 1) * room;
+                return (double)(r * r * 1.0001f + 1e-3f);
+            };
 
-            // z images of this response: (dz*dz, beta^reflections) per (q, n), shared by every column
-            const bool use_table = 2 * nmz + 1 <= kZCap;
-            if (use_table) {
-                const int per_q = 2 * nmz + 1;
-                for (int i = tid; i < 2 * per_q; i += kThreads) {
-                    const int q = i >= per_q, n = i - q * per_q - nmz;
-                    const double dz = axis_delta(az, q, n);
-                    ZEntry e;
-                    e.dz2 = __dmul_rn(dz, dz);
-                    e.bz = 0.f;
-                    if (!COUNT) {
-                        const int k = iabs(n - q) + iabs(n);
-                        e.bz = k < kPow ? bpow[k] : (float)pow(beta, (double)k);
-                    }
-                    e.pad = 0.f;
-                    ztab[q * kZCap + n + nmz] = e;
+            // fast path: the y and z images fit the LDS tables and so do the x rows
+            const bool fast = nix <= 2 * kAxisCap && niy <= 2 * kAxisCap && niz <= 2 * kAxisCap;
+            int n_cand;
+            if (fast) {
+                build_sorted_images(az, nmz, s_split, ztab, tid, [&](int q, int n) {
+                    if (COUNT) return 0;
+                    const int k = iabs(n - q) + iabs(n);
+                    return __float_as_int(k < kPow ? bpow[k] : (float)pow(beta, (double)k));
+                });
+                build_sorted_images(ay, nmy, s_split, ytab, tid, [&](int q, int n) { return iabs(n - q) + iabs(n); });
+                // live columns of x image ix: the y images with dy^2 <= r_out^2 - dx^2 that the reflection
+                // cut can still reach -- a prefix of the sorted y table
+                for (int ix = tid; ix < nix; ix += kThreads) {
+                    const int qx = ix & 1, nx = (ix >> 1) - nmx;
+                    const double dx = axis_delta(ax, qx, nx);
+                    double bound = r_out2 - __dmul_rn(dx, dx);
+                    const int ky_max = k_cut_item - (iabs(nx - qx) + iabs(nx));
+                    if (ky_max < (1 << 18)) bound = fmin(bound, reach2(y0_max, lyf, ky_max));
+                    row_pfx[ix] = (bound >= 0.0 && ky_max >= 0) ? count_not_above(ytab, niy, bound) : 0;
                 }
+                __syncthreads();
+                if (wave == 0) {                              // inclusive scan over the rows, 64 at a time
+                    int carry = 0;
+                    for (int base = 0; base < nix; base += 64) {
+                        const int i = base + lane;
+                        const int v = wave_inclusive_scan(i < nix ? row_pfx[i] : 0, lane) + carry;
+                        if (i < nix) row_pfx[i] = v;
+                        carry = __shfl(v, 63, 64);
+                    }
+                }
+                __syncthreads();
+                n_cand = row_pfx[nix - 1];
+            } else {
+                n_cand = nix * niy;
             }
-            __syncthreads();
+            const int n_batch = (n_cand + 63) / 64;
 
             for (int batch = wave; batch < n_batch; batch += kWaves) {
                 // ---- each lane describes one candidate column ----
                 const int cand = batch * 64 + lane;
                 Column col;
-                col.a = 0.0; col.kxy = 0;
+                col.a = 0.0; col.kxy = 0; col.start = 0; col.len = 0;
                 int pieces = 0;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) { col.start[i] = 0; col.len[i] = 0; }
                 if (cand < n_cand) {
-                    const int ix = cand / niy, iy = cand - ix * niy;
-                    const int qx = ix & 1, nx = (ix >> 1) - nmx;
-                    const int qy = iy & 1, ny = (iy >> 1) - nmy;
-                    const double dx = axis_delta(ax, qx, nx);
-                    const double dy = axis_delta(ay, qy, ny);
-                    col.a = __dadd_rn(__dmul_rn(dx, dx), __dmul_rn(dy, dy));
-                    col.kxy = iabs(nx - qx) + iabs(nx) + iabs(ny - qy) + iabs(ny);
+                    if (fast) {
+                        int lo = 0, hi = nix - 1;              // smallest row with row_pfx > cand
+                        while (lo < hi) {
+                            const int mid = (lo + hi) >> 1;
+                            if (row_pfx[mid] <= cand) lo = mid + 1; else hi = mid;
+                        }
+                        const int ix = lo, qx = ix & 1, nx = (ix >> 1) - nmx;
+                        const AxisImage ye = ytab[cand - (ix ? row_pfx[ix - 1] : 0)];
+                        const double dx = axis_delta(ax, qx, nx);
+                        col.a = __dadd_rn(__dmul_rn(dx, dx), ye.key);
+                        col.kxy = iabs(nx - qx) + iabs(nx) + ye.aux;
+                    } else {
+                        const int ix = cand / niy, iy = cand - ix * niy;
+                        const int qx = ix & 1, nx = (ix >> 1) - nmx;
+                        const int qy = iy & 1, ny = (iy >> 1) - nmy;
+                        const double dx = axis_delta(ax, qx, nx);
+                        const double dy = axis_delta(ay, qy, ny);
+                        col.a = __dadd_rn(__dmul_rn(dx, dx), __dmul_rn(dy, dy));
+                        col.kxy = iabs(nx - qx) + iabs(nx) + iabs(ny - qy) + iabs(ny);
+                    }
                     // reflections left for the z axis before this column's images vanish
                     const int kz_max = reflection_cut(log2_beta, fmaxf((float)r_in, sqrtf((float)col.a))) - col.kxy;
                     if (col.a < r_out2 && kz_max >= 0) {
-                        // z reach of the shell in this column; fp32 is enough because the shell radii carry
-                        // half a tap (about a centimetre) of slack and the exact tap test decides anyway
-                        const float zout = sqrtf((float)(r_out2 - col.a));
-                        const float zin = col.a < r_in2 ? sqrtf((float)(r_in2 - col.a)) : 0.f;
-#pragma unroll
-                        for (int q = 0; q < 2; ++q) {
-                            const float z0 = z0qf[q];
-                            // |n - q| + |n| <= kz_max  <=>  cut_lo <= n <= cut_hi
-                            const int cut_lo = q ? -((kz_max - 1) >> 1) : -(kz_max >> 1);
-                            const int cut_hi = q ? ((kz_max + 1) >> 1) : (kz_max >> 1);
-                            const int lo_n = max((int)ceilf((-zout - z0) * inv_two_lzf - 1e-4f), cut_lo);
-                            const int hi_n = min((int)floorf((-zin - z0) * inv_two_lzf + 1e-4f), cut_hi);
-                            const int lo_p = max((int)ceilf((zin - z0) * inv_two_lzf - 1e-4f), cut_lo);
-                            const int hi_p = min((int)floorf((zout - z0) * inv_two_lzf + 1e-4f), cut_hi);
-                            if (hi_n >= lo_p - 1) {            // the two sides touch: one run
-                                col.start[2 * q] = (short)lo_n;
-                                col.len[2 * q] = (short)max(hi_p - lo_n + 1, 0);
-                            } else {
-                                col.start[2 * q] = (short)lo_n;
-                                col.len[2 * q] = (short)max(hi_n - lo_n + 1, 0);
-                                col.start[2 * q + 1] = (short)lo_p;
-                                col.len[2 * q + 1] = (short)max(hi_p - lo_p + 1, 0);
+                        if (fast) {
+                            // images with r_in^2 - a <= dz^2 <= r_out^2 - a within reach of the reflection cut:
+                            // one contiguous range of the sorted z table (the few images past the cut that it
+                            // keeps add exactly zero)
+                            double hi2 = r_out2 - col.a;
+                            if (kz_max < (1 << 18)) hi2 = fmin(hi2, reach2(z0_max, lzf, kz_max));
+                            const double lo2 = r_in2 - col.a;
+                            int first = 0;
+                            if (lo2 > 0.0) {                   // first entry with dz2 >= lo2
+                                int hi = niz;
+                                while (first < hi) {
+                                    const int mid = (first + hi) >> 1;
+                                    if (ztab[mid].key < lo2) first = mid + 1; else hi = mid;
+                                }
                             }
+                            const int last = count_not_above(ztab, niz, hi2);
+                            if (last > first) {
+                                col.start = (unsigned short)first;
+                                col.len = (unsigned short)(last - first);
+                                pieces = (last - first + kPiece - 1) / kPiece;
+                            }
+                        } else {
+                            pieces = 1;                        // one lane walks every z image of the column
                         }
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) pieces += (col.len[i] + kPiece - 1) / kPiece;
                     }
                 }
                 col.pfx = wave_inclusive_scan(pieces, lane);
@@ -355,29 +533,17 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
                     for (int s = 32; s > 0; s >>= 1)
                         if (wc[slot + s - 1].pfx <= p) slot += s;
                     const Column c = wc[slot];
-                    int local = p - (slot ? wc[slot - 1].pfx : 0);
-                    // which of the four runs holds piece `local` (selects only: no register indexing)
-                    int run = 0, r_start = c.start[0], r_len = c.len[0];
-#pragma unroll
-                    for (int i = 0; i < 3; ++i) {
-                        const int np = ((int)c.len[i] + kPiece - 1) / kPiece;
-                        if (run == i && local >= np) {
-                            local -= np;
-                            run = i + 1;
-                            r_start = c.start[i + 1];
-                            r_len = c.len[i + 1];
-                        }
-                    }
-                    const int q = run >> 1;
-                    const int first = r_start + local * kPiece;
-                    const int len = min(kPiece, r_len - local * kPiece);
+                    const int local = p - (slot ? wc[slot - 1].pfx : 0);
                     float cxy = 0.f;       // beta^kxy / (4 pi) * 2^24
                     if (!COUNT)
                         cxy = (c.kxy < kPow ? bpow[c.kxy] : (float)pow(beta, (double)c.kxy)) * (0.07957747154594767f * 16777216.0f);
-                    if (use_table)
-                        walk_piece_table<COUNT>(wctx, c.a, cxy, ztab + q * kZCap + first + nmz, len, hist, hist32);
-                    else
-                        walk_piece_direct<COUNT>(wctx, az, c.a, cxy, q, first, len, hist, hist32);
+                    if (fast) {
+                        const int first = (int)c.start + local * kPiece;
+                        const int len = min(kPiece, (int)c.len - local * kPiece);
+                        walk_piece_table<COUNT>(wctx, c.a, cxy, ztab + first, len, hist, hist32);
+                    } else {
+                        walk_column_direct<COUNT>(wctx, az, c.a, cxy, nmz, hist, hist32);
+                    }
                 }
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
@@ -420,13 +586,28 @@ int rir_items_per_response(int rir_len) { return kMaxShells + rir_len / kMaxTaps
 size_t rir_item_bytes() { return sizeof(Item); }
 int rir_pow_entries() { return kPow; }
 
+int rir_ctrl_ints() { return kCtrlInts; }
+
 hipError_t launch_rir_plan(hipStream_t s, int n_rir, const float* geom, int rir_len, double fs_over_c,
                            void* items, int* ctrl, float* pow_table) {
     if (n_rir <= 0) return hipSuccess;
-    hipError_t e = launch_fill_u32(s, ctrl, 0u, 2);
+    hipError_t e = launch_fill_u32(s, ctrl, 0u, kCtrlInts);
     if (e != hipSuccess) return e;
-    rir_plan_kernel<<<dim3((n_rir + 127) / 128), dim3(128), 0, s>>>(
-        n_rir, geom, rir_len, fs_over_c, static_cast<Item*>(items), rir_items_per_response(rir_len), ctrl);
+    // `items` holds the sorted table followed by the unsorted one
+    const int per_rir = rir_items_per_response(rir_len);
+    Item* sorted = static_cast<Item*>(items);
+    Item* unsorted = sorted + (size_t)n_rir * per_rir;
+    rir_plan_kernel<<<dim3((n_rir + 127) / 128), dim3(128), 0, s>>>(n_rir, geom, rir_len, fs_over_c, unsorted, per_rir, ctrl);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const size_t max_items = (size_t)n_rir * per_rir;
+    rir_classify_kernel<<<dim3((unsigned)((max_items + 255) / 256)), dim3(256), 0, s>>>(geom, rir_len, fs_over_c, unsorted, ctrl);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    rir_class_offsets_kernel<<<dim3(1), dim3(64), 0, s>>>(ctrl);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    rir_sort_items_kernel<<<dim3((unsigned)((max_items + 255) / 256)), dim3(256), 0, s>>>(unsorted, sorted, ctrl);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     rir_pow_kernel<<<dim3(kPow / 256, (unsigned)n_rir), dim3(256), 0, s>>>(n_rir, geom, pow_table);

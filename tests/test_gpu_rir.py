@@ -94,3 +94,19 @@ def test_beta_one_and_repeatable_counts(aug):
     h2, cnt2 = _run(aug, g, 3000)
     np.testing.assert_array_equal(cnt, cnt2)
     assert rir_err(h2, h.astype(np.float64)) <= RIR_TOL
+
+
+def test_very_flat_room_walks_images_directly(aug):
+    # a 12 cm high room has more z images than the kernel's LDS table holds; it then walks them directly
+    g = np.array([[3.0, 3.2, 0.12, 1.0, 1.1, 0.04, 2.1, 2.0, 0.08, 0.5],
+                  [4.0, 3.0, 2.7, 1.0, 1.1, 1.0, 2.1, 2.0, 1.5, 0.6]], np.float32)
+    print("case: flat room, L=2000", flush=True)
+    _check(aug, g, 2000)
+
+
+def test_symmetric_geometry_with_tied_distances(aug):
+    # source and microphone at mid height: images above and below tie exactly in distance
+    g = np.array([[4.0, 4.0, 3.0, 1.0, 2.0, 1.5, 3.0, 2.0, 1.5, 0.8],
+                  [4.0, 4.0, 3.0, 2.0, 2.0, 1.5, 2.0, 2.0, 1.0, 0.5]], np.float32)
+    print("case: symmetric rooms, L=3000", flush=True)
+    _check(aug, g, 3000)
