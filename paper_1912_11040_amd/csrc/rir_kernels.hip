@@ -471,11 +471,15 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
                 int pieces = 0;
                 if (cand < n_cand) {
                     if (fast) {
-                        int lo = 0, hi = nix - 1;              // smallest row with row_pfx > cand
+                        // smallest row with row_pfx > cand: found once for the batch's first column (the same
+                        // in every lane), then a short walk, since 64 consecutive columns span few rows
+                        int lo = 0, hi = nix - 1;
+                        const int cand0 = batch * 64;
                         while (lo < hi) {
                             const int mid = (lo + hi) >> 1;
-                            if (row_pfx[mid] <= cand) lo = mid + 1; else hi = mid;
+                            if (row_pfx[mid] <= cand0) lo = mid + 1; else hi = mid;
                         }
+                        while (row_pfx[lo] <= cand) ++lo;
                         const int ix = lo, qx = ix & 1, nx = (ix >> 1) - nmx;
                         const AxisImage ye = ytab[cand - (ix ? row_pfx[ix - 1] : 0)];
                         const double dx = axis_delta(ax, qx, nx);
@@ -491,7 +495,8 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
                         col.kxy = iabs(nx - qx) + iabs(nx) + iabs(ny - qy) + iabs(ny);
                     }
                     // reflections left for the z axis before this column's images vanish
-                    const int kz_max = reflection_cut(log2_beta, fmaxf((float)r_in, sqrtf((float)col.a))) - col.kxy;
+                    // (beyond the first shell the shell's own inner radius bounds the distance well enough)
+                    const int kz_max = (n0 > 0 ? k_cut_item : reflection_cut(log2_beta, sqrtf((float)col.a))) - col.kxy;
                     if (col.a < r_out2 && kz_max >= 0) {
                         if (fast) {
                             // images with r_in^2 - a <= dz^2 <= r_out^2 - a within reach of the reflection cut:
