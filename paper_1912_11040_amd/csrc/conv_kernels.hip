@@ -123,7 +123,7 @@ __device__ inline void multiply_pair(float2 A, float2 B, float2 w, float2 Hk, fl
     ZNk = make_float2(Ye.x + Yo.y, Yo.x - Ye.y);     // conj(Ye) + i conj(Yo)
 }
 
-// MULTI: the response has several partitions and the products are summed in registers.
+// MULTI: the response has several partitions.
 template <int N, int T, bool MULTI>
 __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* __restrict__ tw) {
     extern __shared__ float2 buf[];
@@ -138,21 +138,25 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
     const int len = (int)(a.offsets[u + 1] - start);      // utterances are shorter than 2^30 samples (checked on the host)
     const float* x = (j == 0 ? a.speech : a.noise + (size_t)(j - 1) * a.total) + start;
     const float2* H = a.spec + ((size_t)u * a.n_src + j) * a.n_part * (size_t)(N + 1);
-    const int k2 = tid % (M / 2), half = tid / (M / 2);
 
-    float2 accK[MULTI ? 9 : 1], accN[MULTI ? 8 : 1];   // Z'[k], Z'[N-k]; accK[8] is k = N/2
-    if (MULTI) {
+    // Responses longer than N taps: every partition p convolves the window p blocks back with its own
+    // spectrum and the N output samples are summed in registers (eight complex values per thread), which
+    // keeps each pass on the register budget of the single-partition path.
+    float2 out[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) accK[i] = accN[i] = make_float2(0.f, 0.f);
-        accK[8] = make_float2(0.f, 0.f);
-    }
+    for (int i = 0; i < 8; ++i) out[i] = make_float2(0.f, 0.f);
 
     float2 v[16];
     const int n_part = MULTI ? a.n_part : 1;
     for (int p = 0; p < n_part; ++p) {
         const int wb = b - p;                        // input window [(wb-1)N, (wb+1)N)
         if (wb < 0) break;
-        const int w0 = (wb - 1) * N + 2 * tid;           // first sample of this thread in the window (may be < 0)
+        // The thread index is made opaque in every round so that twiddle powers and addresses are not
+        // hoisted out of the partition loop, where they would sit on top of the transforms' registers.
+        int tid_p = tid;
+        if (MULTI) asm volatile("" : "+v"(tid_p));
+        const int k2 = tid_p % (M / 2), half = tid_p / (M / 2);
+        const int w0 = (wb - 1) * N + 2 * tid_p;           // first sample of this thread in the window (may be < 0)
 #pragma unroll
         for (int n1 = 0; n1 < 16; ++n1) {
             const int g = w0 + 2 * M * n1;
@@ -161,11 +165,11 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
             const float x1 = (unsigned)(g + 1) < (unsigned)len ? x[g + 1] : 0.f;
             v[n1] = make_float2(x0, x1);
         }
-        fft_columns_forward<N>(v, tw, tid);
-        if (MULTI && p > 0) __syncthreads();         // the previous partition's pair reads are done
-        fft_columns_store<N, T>(v, buf, tid);
+        fft_columns_forward<N>(v, tw, tid_p);
+        if (MULTI && p > 0) __syncthreads();         // the previous partition's column loads are done
+        fft_columns_store<N, T>(v, buf, tid_p);
         __syncthreads();
-        fft_rows<N, false>(buf, tw, tid);
+        fft_rows<N, false>(buf, tw, tid_p);
         __syncthreads();
         const float2* Hp = H + (size_t)p * (N + 1);
         auto pair = [&](int i) {
@@ -175,49 +179,30 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
             const float2 w = i == 8 ? tw[N + N / 2] : pair_twiddle<N>(tw, half * 8 + i, k2);
             float2 Zk, ZNk;
             multiply_pair(A, B, w, Hp[ix.pos], Hp[ix.h_partner], Zk, ZNk);
-            if (MULTI) {
-                accK[i] = cadd(accK[i], Zk);
-                if (i < 8) accN[i] = cadd(accN[i], ZNk);
-            } else {                                 // both positions belong to this thread alone
-                buf[lds_pad(ix.pos)] = Zk;
-                if (ix.k != 0 && i < 8) buf[lds_pad(ix.pos_partner)] = ZNk;
-            }
+            buf[lds_pad(ix.pos)] = Zk;               // both positions belong to this thread alone
+            if (ix.k != 0 && i < 8) buf[lds_pad(ix.pos_partner)] = ZNk;
         };
-        if constexpr (MULTI) {
-            // the running sums are indexed by the loop counter: kept rolled they stay out of the
-            // register budget of the transforms
-#pragma unroll 1
-            for (int i = 0; i < 8; ++i) pair(i);
-        } else {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) pair(i);
-        }
-        if (tid == 0) pair(8);
-    }
-    if (MULTI) {
+        for (int i = 0; i < 8; ++i) pair(i);
+        if (tid_p == 0) pair(8);
+        __syncthreads();
+        fft_rows<N, true>(buf, tw, tid_p);
+        __syncthreads();
+        fft_columns_load<N, T>(v, buf, tid_p);
+        fft_columns_inverse<N>(v, tw, tid_p);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const PairIndex<N> ix(half * 8 + i, k2);
-            buf[lds_pad(ix.pos)] = accK[i];
-            if (ix.k != 0) buf[lds_pad(ix.pos_partner)] = accN[i];
-        }
-        if (tid == 0) buf[lds_pad(M / 2)] = accK[8];
+        for (int i = 0; i < 8; ++i) out[i] = cadd(out[i], v[8 + i]);
     }
-    __syncthreads();
-    fft_rows<N, true>(buf, tw, tid);
-    __syncthreads();
-    fft_columns_load<N, T>(v, buf, tid);
-    fft_columns_inverse<N>(v, tw, tid);
 
     // the last N real samples of the 2N-sample window are this block's outputs: n = tid + M n1 >= N/2
     float* y = a.reverb + (size_t)j * a.total + start;
     const int out0 = b * N + 2 * tid;
     float e = 0.f;
 #pragma unroll
-    for (int n1 = 8; n1 < 16; ++n1) {
-        const int g = out0 + 2 * M * (n1 - 8);
-        if (g < len) { y[g] = v[n1].x; e += v[n1].x * v[n1].x; }
-        if (g + 1 < len) { y[g + 1] = v[n1].y; e += v[n1].y * v[n1].y; }
+    for (int i = 0; i < 8; ++i) {
+        const int g = out0 + 2 * M * i;
+        if (g < len) { y[g] = out[i].x; e += out[i].x * out[i].x; }
+        if (g + 1 < len) { y[g + 1] = out[i].y; e += out[i].y * out[i].y; }
     }
     double es = (double)e;
     for (int off = 32; off > 0; off >>= 1) es += __shfl_down(es, off, 64);
