@@ -134,33 +134,29 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
     for (int m = 1; m < 16; ++m) twp[m] = tw[(sub * m) & (NC - 1)];
     __syncthreads();
     const int k_lo = s_kstart[sub], k_hi = s_kstart[sub + 1];
-    const bool pairs_aligned = ((start & 1) == 0) && ((hop & 1) == 0) &&
+    const bool pairs_aligned = ((start & 1) == 0) && ((hop & 1) == 0) && ((win & 1) == 0) &&
                                ((reinterpret_cast<uintptr_t>(a.wave) & 7) == 0);
 
     for (int it = 0; it < a.frames_per_group / kMelSlots; ++it) {
         const int64_t t = (int64_t)first + it * kMelSlots + slot;
         const bool live = t < n_frames_u;
         float2 v[16];
-        const int x0 = (int)t * hop;                      // first sample of the frame (utterances are < 2^30 samples)
+        // Loads are unconditional: a slot past the utterance's last frame recomputes that last frame (its
+        // result is dropped) and inputs past the window are read from the frame's last samples and meet a
+        // zero window weight.
+        const int x0 = (int)(live ? t : n_frames_u - 1) * hop;
         if (pairs_aligned) {                              // even sample offset: one 8-byte load per complex input
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int i0 = 2 * (sub + kMelLanes * i);
-                float2 s2 = make_float2(0.f, 0.f);
-                if (live && i0 + 1 < win) s2 = *reinterpret_cast<const float2*>(x + (x0 + i0));
-                else if (live && i0 < win) s2.x = x[x0 + i0];
+                const int i0 = min(2 * (sub + kMelLanes * i), win - 2);
+                const float2 s2 = *reinterpret_cast<const float2*>(x + (x0 + i0));
                 v[i] = make_float2(s2.x * wnd[i].x, s2.y * wnd[i].y);
             }
         } else {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int i0 = 2 * (sub + kMelLanes * i);
-                float re = 0.f, im = 0.f;
-                if (live) {
-                    if (i0 < win) re = x[x0 + i0] * wnd[i].x;
-                    if (i0 + 1 < win) im = x[x0 + i0 + 1] * wnd[i].y;
-                }
-                v[i] = make_float2(re, im);
+                v[i] = make_float2(x[x0 + min(i0, win - 1)] * wnd[i].x, x[x0 + min(i0 + 1, win - 1)] * wnd[i].y);
             }
         }
         // 256 = 16 x 16: first pass without twiddles (inputs past the window are zero and fold away when

@@ -76,13 +76,19 @@ def test_warp_identity_endpoints_and_closed_form():
     assert O.bilinear_warp(1.0, 0.8) > 1.0 > O.bilinear_warp(1.0, 1.2)
 
 
-def test_mel_edges():
+def test_mel_scale_anchors_and_edges():
+    # the scale is anchored so that 1000 Hz is about 1000 mel; 1 + f/700 = 10 gives exactly 2595 mel
+    assert O._hz_to_mel(1000.0) == pytest.approx(1000.0, abs=0.1)
+    assert O._hz_to_mel(6300.0) == pytest.approx(2595.0, rel=1e-12)
+    assert O._hz_to_mel(0.0) == 0.0
+    f = np.array([10.0, 250.0, 1000.0, 4000.0, 7999.0])
+    np.testing.assert_allclose(O._mel_to_hz(O._hz_to_mel(f)), f, rtol=1e-12)
     e = O.mel_edges_hz(40, 0.0, 8000.0)
     assert len(e) == 42 and e[0] == pytest.approx(0.0, abs=1e-9) and e[-1] == pytest.approx(8000.0)
-    mel = 2595 * np.log10(1 + e / 700)
-    np.testing.assert_allclose(np.diff(mel), mel[-1] / 41, rtol=1e-9)
-    # the scale is defined so that 1000 Hz is about 1000 mel
-    assert 2595 * math.log10(1 + 1000 / 700) == pytest.approx(1000, abs=0.1)
+    np.testing.assert_allclose(np.diff(O._hz_to_mel(e)), O._hz_to_mel(8000.0) / 41, rtol=1e-9)
+    # bands widen with frequency: nearly linear at the bottom, nearly logarithmic at the top
+    w = np.diff(e)
+    assert np.all(np.diff(w) > 0) and w[0] == pytest.approx(45.0, abs=3.0) and w[-1] / w[0] > 8
 
 
 def _plain_mel(n_mel, nfft, fs, f_lo, f_hi):
