@@ -123,6 +123,8 @@ __device__ inline void multiply_pair(float2 A, float2 B, float2 w, float2 Hk, fl
     ZNk = make_float2(Ye.x + Yo.y, Yo.x - Ye.y);     // conj(Ye) + i conj(Yo)
 }
 
+constexpr int kXcds = 8;
+
 // MULTI: the response has several partitions.
 template <int N, int T, bool MULTI>
 __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* __restrict__ tw) {
@@ -131,8 +133,14 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
     constexpr int M = N / 16;
     static_assert(T == M, "one thread per column of the split transform");
     const int tid = threadIdx.x;
-    const int64_t item = blockIdx.x / a.n_src;
-    const int j = blockIdx.x % a.n_src;
+    // Groups are dealt to the eight XCDs in turn, each with an L2 of its own.  Group ids that share an XCD
+    // take one contiguous eighth of the work, so that the blocks of an utterance, which read the same response
+    // spectrum and overlapping input windows, meet in one L2.
+    const unsigned per_xcd = gridDim.x / kXcds;
+    const int64_t work = (int64_t)(blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+    if (work >= a.n_items * a.n_src) return;
+    const int64_t item = work / a.n_src;
+    const int j = (int)(work % a.n_src);
     const int u = a.items[item].x, b = a.items[item].y;
     const int64_t start = a.offsets[u];
     const int len = (int)(a.offsets[u + 1] - start);      // utterances are shorter than 2^30 samples (checked on the host)
@@ -270,7 +278,8 @@ hipError_t convolve_n(hipStream_t s, const float2* tw, const ConvArgs& a) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    k<<<dim3((unsigned)(a.n_items * a.n_src)), dim3(T), lds, s>>>(a, tw);
+    const int64_t per_xcd = (a.n_items * a.n_src + kXcds - 1) / kXcds;
+    k<<<dim3((unsigned)(per_xcd * kXcds)), dim3(T), lds, s>>>(a, tw);
     return hipGetLastError();
 }
 
