@@ -229,6 +229,12 @@ int run_rir(aug_ctx* ctx, int n_rir, const float* geom, int rir_len, float fs, f
     return AUG_OK;
 }
 
+// Source j of the reverberated signals starts at j * reverb_stride(total): an even stride keeps the
+// 8-byte loads of the front end aligned for every source.
+int64_t reverb_stride(int64_t total) { return (total + 1) & ~(int64_t)1; }
+
+// Reverberates every source, measures the energies and derives the gains.  With mixed_out the mixture
+// is written there; without it the caller mixes on the fly from the context's reverberated signals.
 int run_convolve_mix(aug_ctx* ctx, int n_utt, int n_noise, const float* speech, const float* noise,
                      const float* rir, int rir_len, const float* snr_db, float* mixed_out, float* gains_out) {
     const aug::Packing& pk = ctx->packing;
@@ -243,7 +249,9 @@ int run_convolve_mix(aug_ctx* ctx, int n_utt, int n_noise, const float* speech, 
     for (int u = 0; u < n_utt; ++u) max_len = std::max(max_len, pk.offsets[u + 1] - pk.offsets[u]);
 
     AUG_HIP(ctx->rir_spec.reserve(sizeof(float2) * (size_t)n_utt * n_src * n_part * (fft_n + 1)), "spectrum workspace");
-    AUG_HIP(ctx->reverb.reserve(sizeof(float) * (size_t)n_src * total), "reverberation workspace");
+    const int64_t stride = reverb_stride(total);
+    AUG_HIP(ctx->reverb.reserve(sizeof(float) * (size_t)n_src * stride), "reverberation workspace");
+    AUG_HIP(ctx->gains.reserve(sizeof(float) * (size_t)std::max(1, n_utt * n_noise)), "gain workspace");
     AUG_HIP(ctx->energy.reserve(sizeof(double) * (size_t)n_utt * n_src), "energy workspace");
 
     AUG_TRY(mark(ctx, -1));
@@ -263,18 +271,23 @@ int run_convolve_mix(aug_ctx* ctx, int n_utt, int n_noise, const float* speech, 
     ca.spec = ctx->rir_spec.as<float2>();
     ca.n_part = n_part;
     ca.reverb = ctx->reverb.as<float>();
+    ca.reverb_stride = stride;
     ca.energy = ctx->energy.as<double>();
     AUG_HIP(aug::launch_convolve(ctx->stream, fft_n, tw, ca), "convolution kernel");
     AUG_TRY(mark(ctx, AUG_STAGE_CONVOLVE));
-    AUG_HIP(aug::launch_mix(ctx->stream, n_utt, ctx->d_offsets.as<int64_t>(), total, n_src, ctx->reverb.as<float>(),
-                            ctx->energy.as<double>(), snr_db, mixed_out, gains_out, max_len),
-            "mix kernel");
+    AUG_HIP(aug::launch_gains(ctx->stream, n_utt, n_src, ctx->energy.as<double>(), snr_db, ctx->gains.as<float>(),
+                              gains_out), "gain kernel");
+    if (mixed_out)
+        AUG_HIP(aug::launch_mix(ctx->stream, n_utt, ctx->d_offsets.as<int64_t>(), stride, n_src, ctx->reverb.as<float>(),
+                                ctx->gains.as<float>(), mixed_out, max_len), "mix kernel");
     AUG_TRY(mark(ctx, AUG_STAGE_MIX));
     return AUG_OK;
 }
 
+// n_extra > 0: the analysed signal is wave + sum_j gains[u][j] extra[j * extra_stride + .] (mixed on the fly)
 int run_mel(aug_ctx* ctx, int n_utt, const float* wave, const float* alpha, const aug_frontend_cfg* cfg,
-            float* feats_out) {
+            float* feats_out, int n_extra = 0, const float* extra = nullptr, int64_t extra_stride = 0,
+            const float* gains = nullptr) {
     const aug::Packing& pk = ctx->packing;
     if (n_utt == 0 || pk.n_frame_groups == 0) return AUG_OK;
     const float2* tw = nullptr;
@@ -294,6 +307,10 @@ int run_mel(aug_ctx* ctx, int n_utt, const float* wave, const float* alpha, cons
     ma.n_items = pk.n_frame_groups;
     ma.frames_per_group = pk.frames_per_group;
     ma.wave = wave;
+    ma.extra = extra;
+    ma.extra_stride = extra_stride;
+    ma.gains = gains;
+    ma.n_extra = n_extra;
     ma.mel_tab = ctx->mel_tab.as<float2>();
     ma.window = ctx->window.as<float>();
     ma.twiddle = tw;
@@ -365,7 +382,7 @@ int aug_destroy(aug_ctx* ctx) {
         rc = AUG_ERR_HIP;
     }
     DeviceBuffer* bufs[] = {&ctx->d_offsets, &ctx->d_frame_offsets, &ctx->d_conv_items, &ctx->d_frame_items,
-                            &ctx->rir_items, &ctx->rir_ctrl, &ctx->rir_pow, &ctx->rir, &ctx->rir_spec, &ctx->reverb, &ctx->energy, &ctx->mixed, &ctx->mel_tab,
+                            &ctx->rir_items, &ctx->rir_ctrl, &ctx->rir_pow, &ctx->rir, &ctx->rir_spec, &ctx->reverb, &ctx->energy, &ctx->gains, &ctx->mel_tab,
                             &ctx->window};
     for (DeviceBuffer* b : bufs) b->release();
     for (DeviceBuffer& b : ctx->twiddle) b.release();
@@ -470,14 +487,14 @@ int aug_pipeline_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, const fl
         AUG_HIP(ctx->rir.reserve(sizeof(float) * (size_t)n_utt * n_src * rir_len), "response workspace");
         rir = ctx->rir.as<float>();
     }
-    float* mixed = mixed_out;
-    if (!mixed) {
-        AUG_HIP(ctx->mixed.reserve(sizeof(float) * (size_t)std::max<int64_t>(total, 1)), "mixture workspace");
-        mixed = ctx->mixed.as<float>();
-    }
     AUG_TRY(run_rir(ctx, n_utt * n_src, geom, rir_len, fs, c, rir, nullptr));
-    AUG_TRY(run_convolve_mix(ctx, n_utt, n_noise, speech, noise, rir, rir_len, snr_db, mixed, gains_out));
-    return run_mel(ctx, n_utt, mixed, alpha, cfg, feats_out);
+    AUG_TRY(run_convolve_mix(ctx, n_utt, n_noise, speech, noise, rir, rir_len, snr_db, mixed_out, gains_out));
+    if (mixed_out || total == 0) return run_mel(ctx, n_utt, mixed_out, alpha, cfg, feats_out);
+    // The mixture itself is not wanted: the front end adds the scaled reverberated noises to the
+    // reverberated speech as it loads its frames, which saves one pass over the batch through HBM.
+    const float* reverb = ctx->reverb.as<float>();
+    const int64_t stride = reverb_stride(total);
+    return run_mel(ctx, n_utt, reverb, alpha, cfg, feats_out, n_noise, reverb + stride, stride, ctx->gains.as<float>());
 }
 
 }  // extern "C"

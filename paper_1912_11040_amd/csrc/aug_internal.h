@@ -55,9 +55,9 @@ struct aug_ctx {
     // intermediate results
     aug::DeviceBuffer rir;               // float [n_rir][rir_len]            (pipeline only)
     aug::DeviceBuffer rir_spec;          // float2 [n_rir][n_part][P+1]
-    aug::DeviceBuffer reverb;            // float [1+n_noise][total]
+    aug::DeviceBuffer reverb;            // float [1+n_noise][total rounded up to even]
     aug::DeviceBuffer energy;            // double [n_utt][1+n_noise]
-    aug::DeviceBuffer mixed;             // float [total]                     (pipeline only)
+    aug::DeviceBuffer gains;             // float [n_utt][n_noise]
     aug::DeviceBuffer mel_tab;           // float2 [n_utt][nfft/2+1]: (channel, weight) per bin
     aug::DeviceBuffer twiddle[16];       // per log2(n): float2 [n + n/2 + 1] FFT twiddles
     aug::DeviceBuffer window;            // float [win]
@@ -105,15 +105,18 @@ struct ConvArgs {
     int64_t total;
     const float2* spec;          // [n_utt][n_src][n_part][P+1]
     int n_part;
-    float* reverb;               // [n_src][total]
+    float* reverb;               // [n_src][reverb_stride]
+    int64_t reverb_stride;
     double* energy;              // [n_utt][n_src]
 };
 hipError_t launch_convolve(hipStream_t s, int fft_n, const float2* twiddle, const ConvArgs& a);
 
-// mixed = y_0 + sum_j g_j y_j with g_j from the energies; writes gains if asked.
-hipError_t launch_mix(hipStream_t s, int n_utt, const int64_t* d_offsets, int64_t total, int n_src,
-                      const float* reverb, const double* energy, const float* snr_db,
-                      float* mixed_out, float* gains_out, int64_t max_len);
+// gains [n_utt][n_src - 1] from the energies and the target SNRs (also copied to gains_out when given)
+hipError_t launch_gains(hipStream_t s, int n_utt, int n_src, const double* energy, const float* snr_db,
+                        float* gains, float* gains_out);
+// mixed = reverb[0] + sum_j gains[j - 1] reverb[j]; source j of the reverberated signals starts at j * stride
+hipError_t launch_mix(hipStream_t s, int n_utt, const int64_t* d_offsets, int64_t stride, int n_src,
+                      const float* reverb, const float* gains, float* mixed_out, int64_t max_len);
 
 // Per-utterance (band, weight) table of the warped mel bank followed by the lane partition of the
 // bins: tab float2 [n_utt][mel_table_stride(nfft)].
@@ -137,6 +140,12 @@ struct MelArgs {
     int64_t n_items;
     int frames_per_group;
     const float* wave;
+    // Mixing on the fly: when n_extra > 0 the analysed signal is
+    // wave[n] + sum_j gains[u][j] * extra[j * extra_stride + n], j < n_extra.
+    const float* extra;
+    int64_t extra_stride;
+    const float* gains;            // [n_utt][n_extra]
+    int n_extra;
     const float2* mel_tab;
     const float* window;
     const float2* twiddle;         // table for the nfft/2-point complex transform

@@ -203,7 +203,7 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
     }
 
     // the last N real samples of the 2N-sample window are this block's outputs: n = tid + M n1 >= N/2
-    float* y = a.reverb + (size_t)j * a.total + start;
+    float* y = a.reverb + (size_t)j * a.reverb_stride + start;
     const int out0 = b * N + 2 * tid;
     float e = 0.f;
 #pragma unroll
@@ -223,34 +223,37 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
     }
 }
 
+// One thread per (utterance, noise source): the gain that puts the reverberated noise at its target
+// SNR against the reverberated speech; a silent signal on either side gives gain 0.
+__global__ void gain_kernel(int n_utt, int n_src, const double* __restrict__ energy, const float* __restrict__ snr_db,
+                            float* __restrict__ gains, float* __restrict__ gains_out) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    const int n_noise = n_src - 1;
+    if (i >= n_utt * n_noise) return;
+    const int u = i / n_noise, j = 1 + i % n_noise;
+    const double e0 = energy[(size_t)u * n_src];
+    const double ej = energy[(size_t)u * n_src + j];
+    const double snr = (double)snr_db[i];
+    const float gain = (e0 > 0.0 && ej > 0.0) ? (float)sqrt(e0 / (ej * pow(10.0, snr / 10.0))) : 0.f;
+    gains[i] = gain;
+    if (gains_out) gains_out[i] = gain;
+}
+
 __global__ __launch_bounds__(256) void mix_kernel(
-    const int64_t* __restrict__ offsets, int64_t total, int n_src, const float* __restrict__ reverb,
-    const double* __restrict__ energy, const float* __restrict__ snr_db, float* __restrict__ mixed,
-    float* __restrict__ gains_out) {
-    __shared__ float g[AUG_MAX_NOISE + 1];
+    const int64_t* __restrict__ offsets, int64_t stride, int n_src, const float* __restrict__ reverb,
+    const float* __restrict__ gains, float* __restrict__ mixed) {
     const int u = blockIdx.y;
     const int64_t start = offsets[u];
     const int64_t len = offsets[u + 1] - start;
     const int64_t first = (int64_t)blockIdx.x * blockDim.x * 4;
-    if (first >= len && !(blockIdx.x == 0)) return;
-    if (threadIdx.x < n_src) {
-        float gain = 1.f;
-        if (threadIdx.x > 0) {
-            const double e0 = energy[(size_t)u * n_src];
-            const double ej = energy[(size_t)u * n_src + threadIdx.x];
-            const double snr = (double)snr_db[(size_t)u * (n_src - 1) + threadIdx.x - 1];
-            gain = (e0 > 0.0 && ej > 0.0) ? (float)sqrt(e0 / (ej * pow(10.0, snr / 10.0))) : 0.f;
-            if (blockIdx.x == 0 && gains_out) gains_out[(size_t)u * (n_src - 1) + threadIdx.x - 1] = gain;
-        }
-        g[threadIdx.x] = gain;
-    }
-    __syncthreads();
+    if (first >= len) return;
+    const float* g = gains + (size_t)u * (n_src - 1);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int64_t n = first + (int64_t)i * blockDim.x + threadIdx.x;
         if (n < len) {
             float acc = reverb[start + n];
-            for (int j = 1; j < n_src; ++j) acc += g[j] * reverb[(size_t)j * total + start + n];
+            for (int j = 1; j < n_src; ++j) acc += g[j - 1] * reverb[(size_t)j * stride + start + n];
             mixed[start + n] = acc;
         }
     }
@@ -324,14 +327,21 @@ hipError_t launch_convolve(hipStream_t s, int fft_n, const float2* twiddle, cons
 #undef CALL
 }
 
-hipError_t launch_mix(hipStream_t s, int n_utt, const int64_t* d_offsets, int64_t total, int n_src,
-                      const float* reverb, const double* energy, const float* snr_db,
-                      float* mixed_out, float* gains_out, int64_t max_len) {
+hipError_t launch_gains(hipStream_t s, int n_utt, int n_src, const double* energy, const float* snr_db,
+                        float* gains, float* gains_out) {
+    const int n = n_utt * (n_src - 1);
+    if (n <= 0) return hipSuccess;
+    gain_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(n_utt, n_src, energy, snr_db, gains, gains_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_mix(hipStream_t s, int n_utt, const int64_t* d_offsets, int64_t stride, int n_src,
+                      const float* reverb, const float* gains, float* mixed_out, int64_t max_len) {
     if (n_utt <= 0) return hipSuccess;
     int64_t chunks = (max_len + 1023) / 1024;
     if (chunks < 1) chunks = 1;
     mix_kernel<<<dim3((unsigned)chunks, (unsigned)n_utt), dim3(256), 0, s>>>(
-        d_offsets, total, n_src, reverb, energy, snr_db, mixed_out, gains_out);
+        d_offsets, stride, n_src, reverb, gains, mixed_out);
     return hipGetLastError();
 }
 

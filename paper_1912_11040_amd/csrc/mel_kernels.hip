@@ -88,7 +88,10 @@ constexpr int kMelSlots = kMelThreads / kMelLanes;       // frames in flight per
 
 // K = 512: 256-point complex FFT per frame, 16 lanes per frame, 16 frames per pass of the group.
 // WIN: the window length when it is known at compile time (the paper's front end uses 400), else 0.
-template <int NC, int WIN>
+// two consecutive samples; only their 4-byte alignment is promised (global loads of two dwords need no more)
+struct __attribute__((aligned(4))) SamplePair { float x, y; };
+
+template <int NC, int WIN, bool MIX>
 __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const float2* __restrict__ tw, int tab_stride) {
     static_assert(NC == 256 && NC / 16 == kMelLanes, "two radix-16 passes, sixteen lanes per frame");
     extern __shared__ __align__(16) unsigned char smem[];
@@ -134,8 +137,9 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
     for (int m = 1; m < 16; ++m) twp[m] = tw[(sub * m) & (NC - 1)];
     __syncthreads();
     const int k_lo = s_kstart[sub], k_hi = s_kstart[sub + 1];
-    const bool pairs_aligned = ((start & 1) == 0) && ((hop & 1) == 0) && ((win & 1) == 0) &&
-                               ((reinterpret_cast<uintptr_t>(a.wave) & 7) == 0);
+    const bool even_win = (win & 1) == 0;
+    const float* extra = MIX ? a.extra + start : nullptr;
+    const float* gains = MIX ? a.gains + (size_t)u * a.n_extra : nullptr;
 
     for (int it = 0; it < a.frames_per_group / kMelSlots; ++it) {
         const int64_t t = (int64_t)first + it * kMelSlots + slot;
@@ -143,22 +147,50 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
         float2 v[16];
         // Loads are unconditional: a slot past the utterance's last frame recomputes that last frame (its
         // result is dropped) and inputs past the window are read from the frame's last samples and meet a
-        // zero window weight.
+        // zero window weight.  With MIX the analysed signal is formed here, in source order:
+        // x + sum_j gains[j] extra_j.
         const int x0 = (int)(live ? t : n_frames_u - 1) * hop;
-        if (pairs_aligned) {                              // even sample offset: one 8-byte load per complex input
+        if (even_win) {                                   // one 8-byte load per complex input
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int i0 = min(2 * (sub + kMelLanes * i), win - 2);
-                const float2 s2 = *reinterpret_cast<const float2*>(x + (x0 + i0));
-                v[i] = make_float2(s2.x * wnd[i].x, s2.y * wnd[i].y);
+                const SamplePair s2 = *reinterpret_cast<const SamplePair*>(x + (x0 + i0));
+                v[i] = make_float2(s2.x, s2.y);
+            }
+            if (MIX) {
+                for (int j = 0; j < a.n_extra; ++j) {
+                    const float g = gains[j];
+                    const float* xj = extra + (size_t)j * a.extra_stride;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int i0 = min(2 * (sub + kMelLanes * i), win - 2);
+                        const SamplePair s2 = *reinterpret_cast<const SamplePair*>(xj + (x0 + i0));
+                        v[i].x += g * s2.x;
+                        v[i].y += g * s2.y;
+                    }
+                }
             }
         } else {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int i0 = 2 * (sub + kMelLanes * i);
-                v[i] = make_float2(x[x0 + min(i0, win - 1)] * wnd[i].x, x[x0 + min(i0 + 1, win - 1)] * wnd[i].y);
+                v[i] = make_float2(x[x0 + min(i0, win - 1)], x[x0 + min(i0 + 1, win - 1)]);
+            }
+            if (MIX) {
+                for (int j = 0; j < a.n_extra; ++j) {
+                    const float g = gains[j];
+                    const float* xj = extra + (size_t)j * a.extra_stride;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int i0 = 2 * (sub + kMelLanes * i);
+                        v[i].x += g * xj[x0 + min(i0, win - 1)];
+                        v[i].y += g * xj[x0 + min(i0 + 1, win - 1)];
+                    }
+                }
             }
         }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = make_float2(v[i].x * wnd[i].x, v[i].y * wnd[i].y);
         // 256 = 16 x 16: first pass without twiddles (inputs past the window are zero and fold away when
         // WIN is known), exchange through LDS, second pass with this lane's fixed twiddles
         SmallDft<16, false>::run(v);
@@ -260,10 +292,10 @@ hipError_t launch_mel(hipStream_t s, const MelArgs& a) {
     constexpr int NC = 256;
     const size_t lds = sizeof(float2) * (kMelSlots * lds_padded_size(NC) + 2 * (NC + 1)) +
                        sizeof(float) * kMelSlots * 2 * (a.cfg.n_mel + 2) + sizeof(int) * 20;
-    if (a.cfg.win == 400)
-        mel_kernel<NC, 400><<<dim3((unsigned)a.n_items), dim3(kMelThreads), lds, s>>>(a, a.twiddle, mel_table_stride(a.cfg.nfft));
-    else
-        mel_kernel<NC, 0><<<dim3((unsigned)a.n_items), dim3(kMelThreads), lds, s>>>(a, a.twiddle, mel_table_stride(a.cfg.nfft));
+    const bool mix = a.n_extra > 0;
+    auto k = a.cfg.win == 400 ? (mix ? &mel_kernel<NC, 400, true> : &mel_kernel<NC, 400, false>)
+                              : (mix ? &mel_kernel<NC, 0, true> : &mel_kernel<NC, 0, false>);
+    k<<<dim3((unsigned)a.n_items), dim3(kMelThreads), lds, s>>>(a, a.twiddle, mel_table_stride(a.cfg.nfft));
     return hipGetLastError();
 }
 

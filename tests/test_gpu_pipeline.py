@@ -49,26 +49,43 @@ def _compare(got, ref, w):
     assert feat_err(got["feats"], ref["feats"]) <= FEAT_TOL
 
 
+def _compare_unmaterialised(aug, w, ref):
+    # without mixed_out the front end mixes the reverberated signals while it loads its frames:
+    # a different kernel instantiation, held to the same bar against the oracle
+    got = _run(aug, w, want_rir=False, want_mixed=False)
+    print(f"  mixture not materialised: feat err {feat_err(got['feats'], ref['feats']):.2e}", flush=True)
+    assert got["feats"].shape == ref["feats"].shape
+    assert feat_err(got["feats"], ref["feats"]) <= FEAT_TOL
+    if w.n_noise:
+        np.testing.assert_allclose(got["gains"], ref["gains"], rtol=GAIN_TOL)
+    return got
+
+
 def test_tiny_config_end_to_end(aug):
     w = W.tiny()
     print("case: tiny pipeline, direct convolution + DFT-matrix oracle", flush=True)
     got = _run(aug, w)
-    _compare(got, _oracle(w), w)
+    ref = _oracle(w)
+    _compare(got, ref, w)
     # internal buffers instead of caller outputs give the same features
-    again = _run(aug, w, want_rir=False, want_mixed=False)
+    again = _compare_unmaterialised(aug, w, ref)
     assert feat_err(again["feats"], got["feats"].astype(np.float64)) <= 1e-5
 
 
 def test_batch_config_subset(aug):
     w = W.batch(n_utt=4, seconds=4.0)
     print("case: batch config, 4 utterances, L=8000, direct oracle", flush=True)
-    _compare(_run(aug, w), _oracle(w), w)
+    ref = _oracle(w)
+    _compare(_run(aug, w), ref, w)
+    _compare_unmaterialised(aug, w, ref)
 
 
 def test_varlen_config_small(aug):
     w = W.varlen(n_utt=5, rir_len=2000, min_s=0.02, max_s=1.5)
     print("case: varlen small, 3 noises", flush=True)
-    _compare(_run(aug, w), _oracle(w), w)
+    ref = _oracle(w)
+    _compare(_run(aug, w), ref, w)
+    _compare_unmaterialised(aug, w, ref)
 
 
 def test_varlen_full_size_sampled(aug):
@@ -79,6 +96,8 @@ def test_varlen_full_size_sampled(aug):
     print(f"case: varlen full size, {w.n_utt} utterances, {w.total} samples, L={w.rir_len}", flush=True)
     got = _run(aug, w, want_rir=True, want_mixed=True)
     assert not np.isnan(got["feats"]).any() and not np.isnan(got["mixed"]).any()
+    lean = _run(aug, w, want_rir=False, want_mixed=False)       # the call the benchmark times
+    assert not np.isnan(lean["feats"]).any()
     foff = w.frame_offsets()
     lens = w.lengths()
     rng = np.random.default_rng(0)
@@ -90,6 +109,7 @@ def test_varlen_full_size_sampled(aug):
         sub = dict(rir=got["rir"][u:u + 1], mixed=got["mixed"][w.offsets[u]:w.offsets[u + 1]],
                    gains=got["gains"][u:u + 1], feats=got["feats"][foff[u]:foff[u + 1]])
         _compare(sub, ref, s)
+        assert feat_err(lean["feats"][foff[u]:foff[u + 1]], ref["feats"]) <= FEAT_TOL
         pos = rng.integers(0, lens[u], 32)
         for j in range(1 + w.n_noise):
             x = s.speech if j == 0 else s.noise[j - 1]
@@ -102,4 +122,6 @@ def test_no_noise_pipeline(aug):
     w = W.tiny(n_utt=2)
     w = dataclasses.replace(w, noise=None, snr_db=None, geom=np.ascontiguousarray(w.geom[:, :1]))
     got = _run(aug, w)
-    _compare(got, _oracle(w), w)
+    ref = _oracle(w)
+    _compare(got, ref, w)
+    _compare_unmaterialised(aug, w, ref)
