@@ -119,6 +119,19 @@ def test_three_noise_sources_16000_taps(aug):
     _check(aug, offsets, speech, noise, rir, snr)
 
 
+def test_most_noise_sources_the_interface_takes(aug):
+    rng = np.random.default_rng(12)
+    lens = [1500, 0, 2600, 700]
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    total = int(offsets[-1])
+    speech = rng.standard_normal(total).astype(np.float32)
+    noise = rng.standard_normal((8, total)).astype(np.float32)
+    rir = _decaying_rirs(rng, 4, 9, 300)
+    snr = rng.uniform(-5, 30, (4, 8)).astype(np.float32)
+    print("case: 8 noises, L=300, one empty utterance", flush=True)
+    _check(aug, offsets, speech, noise, rir, snr)
+
+
 def test_silent_noise_gets_zero_gain(aug):
     rng = np.random.default_rng(3)
     offsets = np.array([0, 2000], np.int64)

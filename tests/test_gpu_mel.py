@@ -94,6 +94,17 @@ def test_other_mel_counts_and_band(aug):
     assert feat_err(f, ref) <= FEAT_TOL
 
 
+def test_most_mel_channels_the_interface_takes(aug):
+    import dataclasses
+    fe = dataclasses.replace(FE, n_mel=128)
+    w = W.tiny(n_utt=3)
+    alpha = np.array([0.8, 1.0, 1.2], np.float32)
+    f = _run(aug, w.offsets, w.speech, alpha, fe)
+    ref = O.vtlp_mel_batch(w.offsets, w.speech, alpha, fe)
+    assert f.shape == ref.shape and f.shape[1] == 128
+    assert feat_err(f, ref) <= FEAT_TOL
+
+
 @pytest.mark.parametrize("win,hop", [(320, 128), (400, 161), (512, 256), (33, 7)])
 def test_other_window_and_hop(aug, win, hop):
     import dataclasses

@@ -117,6 +117,27 @@ def test_varlen_full_size_sampled(aug):
             np.testing.assert_allclose(O.convolve_fft(x, ref["rir"][0, j])[pos], direct, atol=1e-9)
 
 
+def test_throughput_full_size_sampled(aug):
+    # The largest configuration (32768-tap responses in two partitions), as the benchmark launches it
+    # with --workload throughput: one sampled utterance through the oracle, features of the call that
+    # does not materialise the mixture included.
+    w = W.throughput()
+    print(f"case: throughput full size, {w.n_utt} utterances, {w.total} samples, L={w.rir_len}", flush=True)
+    got = _run(aug, w, want_rir=True, want_mixed=True)
+    assert not np.isnan(got["feats"]).any() and not np.isnan(got["mixed"]).any()
+    lean = _run(aug, w, want_rir=False, want_mixed=False)
+    assert not np.isnan(lean["feats"]).any()
+    foff = w.frame_offsets()
+    u = int(np.random.default_rng(1).integers(0, w.n_utt))
+    print(f"  utterance {u}", flush=True)
+    s = w.slice([u])
+    ref = _oracle(s, conv="fft")
+    sub = dict(rir=got["rir"][u:u + 1], mixed=got["mixed"][w.offsets[u]:w.offsets[u + 1]],
+               gains=got["gains"][u:u + 1], feats=got["feats"][foff[u]:foff[u + 1]])
+    _compare(sub, ref, s)
+    assert feat_err(lean["feats"][foff[u]:foff[u + 1]], ref["feats"]) <= FEAT_TOL
+
+
 def test_no_noise_pipeline(aug):
     import dataclasses
     w = W.tiny(n_utt=2)

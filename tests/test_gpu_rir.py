@@ -68,6 +68,12 @@ def test_split_over_several_groups_16000_taps(aug):
     assert cnt[0].sum() > 5_000_000
 
 
+def test_longest_response_the_interface_takes(aug):
+    w = W.throughput(n_utt=1, seconds=0.1)
+    print("case: throughput geom, 3 rirs, L=32768", flush=True)
+    _check(aug, w.geom, 32768)
+
+
 def test_zero_reflection_closed_form(aug):
     g = np.array([[5, 4, 3, 1.0, 1.5, 1.2, 3.5, 2.0, 1.7, 0.0]], np.float32)
     h, _ = _run(aug, g, 2048)
