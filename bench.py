@@ -29,6 +29,33 @@ PEAK_FP32_TFLOPS = 157.3
 PEAK_FP64_TFLOPS = 78.6
 RIR_FLOP_PER_IMAGE = 12.0     # 2 add, sqrt, mul, add, floor, table product, divide, scale, accumulate ...
 
+# HBM bytes per launch (read + written) of each stage's kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE
+# runs summarised in profiles/hbm_traffic_<workload>.md, scaled there by a 1 GiB copy.  They describe the
+# kernel sources with this digest only; for any other sources `traffic` is reported as null.
+RECORDED_TRAFFIC = {
+    "digest": "e3229111e87adce8",
+    "varlen": {"rir": 138614335, "rir_spectrum": 202034512, "convolve": 1264696902, "mel": 627146410},
+    "throughput": {"rir": 737488843, "rir_spectrum": 1220228518, "convolve": 5814572643, "mel": 2221519388},
+}
+
+
+def kernel_source_digest() -> str:
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_1912_11040_amd", "csrc", "*"))):
+        if f.endswith((".hip", ".h")):
+            h.update(os.path.basename(f).encode())
+            with open(f, "rb") as fh:
+                h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def recorded_traffic(workload: str, stage: str):
+    if kernel_source_digest() != RECORDED_TRAFFIC["digest"]:
+        return None
+    return RECORDED_TRAFFIC.get(workload, {}).get(stage)
+
 
 def describe(w) -> str:
     n = w.lengths()
@@ -49,11 +76,11 @@ def stage_work(w, n_images: float):
     n_src = 1 + w.n_noise
     frames = int(w.frame_offsets()[-1])
     fe = w.frontend
-    work = {
-        "mel": ("hbm", 4.0 * w.total + 4.0 * fe.n_mel * frames),
-        "mix": ("hbm", 4.0 * w.total * (n_src + 1)),
-    }
+    work = {"mel": ("hbm", 4.0 * w.total + 4.0 * fe.n_mel * frames)}
     if w.geom is not None:
+        # the timed call does not materialise the mixture: the front end reads every reverberated source
+        # and scales it on the way in; what is left of the mix stage is the gain kernel (no roofline line)
+        work["mel"] = ("hbm", 4.0 * w.total * n_src + 4.0 * fe.n_mel * frames)
         work["rir"] = ("alu", RIR_FLOP_PER_IMAGE * n_images)
         work["convolve"] = ("alu32", conv_flop_per_sample(w.rir_len) * w.total * n_src)
         work["rir_spectrum"] = ("alu32", 2.5 * (2 * w.rir_len) * math.log2(2 * w.rir_len) * w.n_utt * n_src)
@@ -195,6 +222,7 @@ def main() -> int:
     roof["kernel"] = {"rir": "rir_image_kernel", "convolve": "convolve_kernel", "mel": "mel_kernel",
                       "mix": "mix_kernel", "rir_spectrum": "rir_spectrum_kernel"}[dominant]
     roof["avg_launch_ms"] = stages[dominant][0]
+    roof["traffic"] = recorded_traffic(args.workload, dominant)     # HBM bytes per launch, or null
 
     out = {
         "metric": METRIC,
