@@ -214,6 +214,22 @@ def main() -> int:
     aug.aug_profile_enable(False)
 
     ms_per_step = dt * 1e3 / args.steps
+
+    # The same step when the waveforms start in pinned host memory (never `value`: the boundary takes
+    # device pointers): host-to-device copies of speech and noise, then the call.
+    h_speech = torch.from_numpy(np.ascontiguousarray(w.speech)).pin_memory()
+    h_noise = None if w.noise is None else torch.from_numpy(np.ascontiguousarray(w.noise)).pin_memory()
+    reps = max(3, min(10, args.steps))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        speech.copy_(h_speech, non_blocking=True)
+        if h_noise is not None:
+            noise.copy_(h_noise, non_blocking=True)
+        step()
+    torch.cuda.synchronize()
+    ms_with_h2d = (time.perf_counter() - t0) * 1e3 / reps
+    del h_speech, h_noise
     stages = {k: (ms / max(n, 1), n) for k, (ms, n) in prof.items() if n > 0}
     work = stage_work(w, n_images)
     dominant = max((k for k in stages if k in work), key=lambda k: stages[k][0] * stages[k][1])
@@ -240,6 +256,8 @@ def main() -> int:
         "config": {"workload": describe(w), "entry_point": "aug_pipeline_batch" if full else "aug_vtlp_mel_batch",
                    "images_per_step": n_images},
         "roofline": roof,
+        "with_h2d": {"ms_per_step": ms_with_h2d, "value": w.audio_seconds / (ms_with_h2d * 1e-3),
+                     "note": "waveforms copied from pinned host memory before every call; not the headline"},
         "stage_ms": {k: round(v[0] * v[1] / args.steps, 4) for k, v in stages.items()},
         "stage_roofline_frac": {k: round(roofline_for(k, work, stages[k][0] * stages[k][1] / args.steps)["frac"], 4)
                                 for k in stages if k in work},
