@@ -158,6 +158,38 @@ int aug_vtlp_mel_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, const fl
                        const float* alpha, const aug_frontend_cfg* cfg,
                        const int64_t* frame_offsets, float* feats_out);
 
+/* Analysis constants of the waveform VTLP.  Kernels are built for 800 / 400 / 2048. */
+typedef struct aug_vtlp_cfg {
+    int win;        /* frame length in samples (periodic Hann), 50 ms in the paper's best setting */
+    int hop;        /* frame shift, win / 2 */
+    int nfft;       /* DFT size K of Eq. (1), a power of two >= 2 win */
+} aug_vtlp_cfg;
+
+/*
+ * VTLP on the waveform by resynthesis, the step the paper places before the
+ * acoustic simulator (Sec. 2.3, Eq. (1); window length from Sec. 3).
+ *
+ *   offsets   HOST int64 [n_utt+1] as above.
+ *   wave      DEVICE float [total].
+ *   alpha     DEVICE float [n_utt]: warp factor of each utterance (1 returns
+ *             the input; the paper's best range is [0.8, 1.2]).
+ *   wave_out  DEVICE float [total], overwritten; must not overlap wave.
+ *
+ * Per utterance of N samples: frame t = 0 .. (N-1)/hop + 1 is centred on sample
+ * t hop, covers win samples (zeros outside the utterance) under
+ * w[i] = 0.5 - 0.5 cos(2 pi i / win), and is placed around time zero of an
+ * nfft-point DFT X.  The warped spectrum is Y[k'] = (1-f) X[j] + f X[j+1] with
+ * j + f = nfft/(2 pi) (w' - 2 atan(a sin w' / (1 + a cos w'))), w' = 2 pi k'/nfft,
+ * a = 1 - alpha, k' = 0..nfft/2: the frequency that Eq. (1) maps onto w'.
+ * All nfft samples of the inverse DFT of Y are added at the frame's position.
+ * Sums of overlapping frames use floating-point atomics, so the last bits of
+ * wave_out can differ between runs.
+ * Errors: AUG_ERR_UNSUPPORTED for any cfg other than 800 / 400 / 2048 or more
+ * than 65535 utterances.
+ */
+int aug_vtlp_resynth_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, const float* wave,
+                           const float* alpha, const aug_vtlp_cfg* cfg, float* wave_out);
+
 /*
  * The whole path in one call: aug_rir_batch on geom, aug_convolve_mix_batch
  * with those responses, aug_vtlp_mel_batch on the mixture.  Arguments as in
@@ -188,6 +220,7 @@ enum {
     AUG_STAGE_MIX,            /* SNR gains and mixture */
     AUG_STAGE_MEL,            /* STFT power, warped mel, power law */
     AUG_STAGE_OTHER,          /* clears and small tables */
+    AUG_STAGE_VTLP,           /* waveform VTLP (aug_vtlp_resynth_batch) */
     AUG_N_STAGES
 };
 int aug_profile_enable(aug_ctx* ctx, int on);

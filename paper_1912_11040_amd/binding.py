@@ -22,10 +22,15 @@ AUG_ERR_NOMEM = -3
 AUG_ERR_HIP = -4
 
 EXPORTS = ("aug_create", "aug_destroy", "aug_last_error", "aug_frame_count", "aug_rir_batch",
-           "aug_convolve_mix_batch", "aug_vtlp_mel_batch", "aug_pipeline_batch",
+           "aug_convolve_mix_batch", "aug_vtlp_mel_batch", "aug_vtlp_resynth_batch", "aug_pipeline_batch",
            "aug_profile_enable", "aug_profile_read")
 
-STAGES = ("rir", "rir_spectrum", "convolve", "mix", "mel", "other")
+STAGES = ("rir", "rir_spectrum", "convolve", "mix", "mel", "other", "vtlp")
+
+
+class VtlpCfg(ctypes.Structure):
+    """Mirror of aug_vtlp_cfg."""
+    _fields_ = [("win", ctypes.c_int), ("hop", ctypes.c_int), ("nfft", ctypes.c_int)]
 
 
 class AugError(RuntimeError):
@@ -76,6 +81,8 @@ def load_library() -> ctypes.CDLL:
     lib.aug_convolve_mix_batch.restype = ci
     lib.aug_vtlp_mel_batch.argtypes = [vp, ci, p_i64, vp, vp, p_cfg, p_i64, vp]
     lib.aug_vtlp_mel_batch.restype = ci
+    lib.aug_vtlp_resynth_batch.argtypes = [vp, ci, p_i64, vp, vp, ctypes.POINTER(VtlpCfg), vp]
+    lib.aug_vtlp_resynth_batch.restype = ci
     lib.aug_pipeline_batch.argtypes = [vp, ci, p_i64, vp, ci, vp, vp, ci, cf, cf, vp, vp, p_cfg,
                                        p_i64, vp, vp, vp, vp]
     lib.aug_pipeline_batch.restype = ci
@@ -186,6 +193,16 @@ class Augmenter:
             self._h, len(off) - 1, off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
             _ptr(wave, torch.float32), _ptr(alpha, torch.float32), ctypes.byref(c),
             foff.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), _ptr(feats_out, torch.float32)))
+
+    def aug_vtlp_resynth_batch(self, offsets, wave, alpha, wave_out, win: int = 800, hop: int = 400,
+                               nfft: int = 2048):
+        import torch
+        off = _host_i64(offsets)
+        c = VtlpCfg(int(win), int(hop), int(nfft))
+        self._check(self._lib.aug_vtlp_resynth_batch(
+            self._h, len(off) - 1, off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+            _ptr(wave, torch.float32), _ptr(alpha, torch.float32), ctypes.byref(c),
+            _ptr(wave_out, torch.float32)))
 
     def aug_pipeline_batch(self, offsets, speech, noise, geom, rir_len: int, fs: float, c: float,
                            snr_db, alpha, cfg, frame_offsets, feats_out, rir_out=None,

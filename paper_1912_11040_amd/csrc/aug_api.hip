@@ -382,7 +382,7 @@ int aug_destroy(aug_ctx* ctx) {
         rc = AUG_ERR_HIP;
     }
     DeviceBuffer* bufs[] = {&ctx->d_offsets, &ctx->d_frame_offsets, &ctx->d_conv_items, &ctx->d_frame_items,
-                            &ctx->rir_items, &ctx->rir_ctrl, &ctx->rir_pow, &ctx->rir, &ctx->rir_spec, &ctx->reverb, &ctx->energy, &ctx->gains, &ctx->mel_tab,
+                            &ctx->rir_items, &ctx->rir_ctrl, &ctx->rir_pow, &ctx->rir, &ctx->rir_spec, &ctx->reverb, &ctx->energy, &ctx->gains, &ctx->vtlp_tab, &ctx->mel_tab,
                             &ctx->window};
     for (DeviceBuffer* b : bufs) b->release();
     for (DeviceBuffer& b : ctx->twiddle) b.release();
@@ -462,6 +462,36 @@ int aug_vtlp_mel_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, const fl
     if (!wave || !alpha || !feats_out) return fail(ctx, AUG_ERR_INVALID_ARG, "wave, alpha or feats_out is null");
     AUG_TRY(sync_packing(ctx, n_utt, offsets, frame_offsets, 0, aug::mel_frames_per_group()));
     return run_mel(ctx, n_utt, wave, alpha, cfg, feats_out);
+}
+
+int aug_vtlp_resynth_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, const float* wave, const float* alpha,
+                           const aug_vtlp_cfg* cfg, float* wave_out) {
+    AUG_TRY(enter(ctx));
+    AUG_TRY(check_offsets(ctx, n_utt, offsets));
+    if (!cfg) return fail(ctx, AUG_ERR_INVALID_ARG, "vtlp config is null");
+    if (cfg->win < 2 || cfg->hop < 1 || cfg->nfft < cfg->win)
+        return fail(ctx, AUG_ERR_INVALID_ARG, "need win >= 2, hop >= 1, nfft >= win");
+    if (!aug::vtlp_supported(cfg->win, cfg->hop, cfg->nfft))
+        return fail(ctx, AUG_ERR_UNSUPPORTED, "kernels are built for win 800, hop 400, nfft 2048");
+    if (n_utt > 65535) return fail(ctx, AUG_ERR_UNSUPPORTED, "more than 65535 utterances in one call");
+    if (!wave || !alpha || !wave_out) return fail(ctx, AUG_ERR_INVALID_ARG, "wave, alpha or wave_out is null");
+    const int64_t total = offsets[n_utt];
+    if (wave_out < wave + total && wave < wave_out + total)
+        return fail(ctx, AUG_ERR_INVALID_ARG, "wave_out overlaps wave");
+    AUG_TRY(sync_packing(ctx, n_utt, offsets, nullptr, 0, 0));
+    if (n_utt == 0 || total == 0) return AUG_OK;
+    int64_t max_len = 0;
+    for (int u = 0; u < n_utt; ++u) max_len = std::max(max_len, offsets[u + 1] - offsets[u]);
+    const float2* tw = nullptr;
+    AUG_TRY(ensure_twiddle(ctx, aug::vtlp_fft_size(), &tw));
+    AUG_HIP(ctx->vtlp_tab.reserve(sizeof(float2) * (size_t)n_utt * aug::vtlp_table_entries()), "warp table");
+    AUG_TRY(mark(ctx, -1));
+    AUG_HIP(aug::launch_vtlp_table(ctx->stream, n_utt, alpha, ctx->vtlp_tab.as<float2>()), "warp table kernel");
+    AUG_HIP(aug::launch_fill_u32(ctx->stream, wave_out, 0u, total), "output clear");
+    AUG_HIP(aug::launch_vtlp_resynth(ctx->stream, n_utt, ctx->d_offsets.as<int64_t>(), max_len, wave,
+                                     ctx->vtlp_tab.as<float2>(), tw, wave_out), "resynthesis kernel");
+    AUG_TRY(mark(ctx, AUG_STAGE_VTLP));
+    return AUG_OK;
 }
 
 int aug_pipeline_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, const float* speech, int n_noise,

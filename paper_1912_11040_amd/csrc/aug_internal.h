@@ -61,6 +61,7 @@ struct aug_ctx {
     aug::DeviceBuffer mel_tab;           // float2 [n_utt][nfft/2+1]: (channel, weight) per bin
     aug::DeviceBuffer twiddle[16];       // per log2(n): float2 [n + n/2 + 1] FFT twiddles
     aug::DeviceBuffer window;            // float [win]
+    aug::DeviceBuffer vtlp_tab;          // float2 [n_utt][vtlp_table_entries()]: (source bin, weight) per output bin
     int window_n = 0;
 
     // stage timing: events recorded in stream order, each tagged with the stage it ends (-1 = a start mark)
@@ -154,6 +155,15 @@ struct MelArgs {
 };
 int mel_frames_per_group();
 hipError_t launch_mel(hipStream_t s, const MelArgs& a);
+
+// Waveform VTLP: per-utterance table of (lower source bin, interpolation weight) for every output bin,
+// then analysis, warp and overlap-add, one wavefront per frame; `out` must be zero on entry.
+int vtlp_table_entries();
+int vtlp_fft_size();                 // length of the complex transform whose twiddle table the kernel needs
+bool vtlp_supported(int win, int hop, int nfft);
+hipError_t launch_vtlp_table(hipStream_t s, int n_utt, const float* alpha, float2* tab);
+hipError_t launch_vtlp_resynth(hipStream_t s, int n_utt, const int64_t* d_offsets, int64_t max_len,
+                               const float* wave, const float2* tab, const float2* twiddle, float* out);
 
 // fill n 32-bit words with a value (used instead of memset so that calls stay graph-capturable)
 hipError_t launch_fill_u32(hipStream_t s, void* p, uint32_t v, int64_t n);
