@@ -24,6 +24,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 METRIC = "augmented audio-sec/sec (RIR+conv+mix+VTLP mel) on 1 GPU"
+METRIC_BY_VTLP = {"mel": METRIC,
+                  "waveform": "augmented audio-sec/sec (waveform VTLP+RIR+conv+mix+mel) on 1 GPU",
+                  "waveform-only": "waveform-VTLP audio-sec/sec on 1 GPU"}
 PEAK_HBM_GBS = 8000.0
 PEAK_FP32_TFLOPS = 157.3
 PEAK_FP64_TFLOPS = 78.6
@@ -76,7 +79,11 @@ def stage_work(w, n_images: float):
     n_src = 1 + w.n_noise
     frames = int(w.frame_offsets()[-1])
     fe = w.frontend
+    n_len = w.lengths()
     work = {"mel": ("hbm", 4.0 * w.total + 4.0 * fe.n_mel * frames)}
+    # waveform VTLP: two 2048-point real transforms, the window and two interpolated bins per output pair, per frame
+    vtlp_frames = float(np.sum((n_len[n_len > 0] - 1) // 400 + 2))
+    work["vtlp"] = ("alu32", vtlp_frames * (2 * 2.5 * 2048 * 11 + 800 + 8 * 1025))
     if w.geom is not None:
         # the timed call does not materialise the mixture: the front end reads every reverberated source
         # and scales it on the way in; what is left of the mix stage is the gain kernel (no roofline line)
@@ -100,7 +107,7 @@ def roofline_for(stage: str, work, ms: float):
             "traffic": None}
 
 
-def cpu_baseline(w, budget_s: float = 15.0):
+def cpu_baseline(w, budget_s: float = 15.0, vtlp: str = "mel"):
     """The oracle as it stands, one thread, on the first utterances of the workload: utterances are
     fed to it one at a time until the time budget is used up."""
     from oracle import aug_oracle as O
@@ -114,7 +121,14 @@ def cpu_baseline(w, budget_s: float = 15.0):
         for u in range(w.n_utt):
             s = w.slice([u])
             t0 = time.perf_counter()
-            if s.geom is not None:
+            if vtlp != "mel":
+                from oracle import vtlp_resynth_oracle as V
+                import dataclasses
+                warped = V.vtlp_resynth_batch(s.offsets, s.speech, s.alpha)
+                s = dataclasses.replace(s, speech=warped.astype(np.float32), alpha=np.ones_like(s.alpha))
+            if vtlp == "waveform-only":
+                pass
+            elif s.geom is not None:
                 O.pipeline_batch(s.offsets, s.speech, s.noise, s.geom, s.rir_len, s.fs, s.c, s.snr_db,
                                  s.alpha, s.frontend)
             else:
@@ -143,6 +157,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="varlen",
                     choices=["tiny", "features", "batch", "varlen", "throughput"])
+    ap.add_argument("--vtlp", default="mel", choices=["mel", "waveform", "waveform-only"],
+                    help="mel: the warp is applied to the mel bank inside the front end (the headline path); "
+                         "waveform: aug_vtlp_resynth_batch on the speech first, then the same path with "
+                         "alpha = 1 (the paper's own order); waveform-only: aug_vtlp_resynth_batch alone")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one untimed 1 GiB device-to-device copy, the known-size kernel that "
@@ -170,17 +188,26 @@ def main() -> int:
     full = w.geom is not None
 
     aug = Augmenter(0)
+    warped = torch.empty_like(speech) if args.vtlp != "mel" else None
+    ones = torch.ones_like(alpha)
 
     def step():
+        if args.vtlp == "waveform-only":
+            aug.aug_vtlp_resynth_batch(w.offsets, speech, alpha, warped)
+            return
+        x, a = speech, alpha
+        if args.vtlp == "waveform":
+            aug.aug_vtlp_resynth_batch(w.offsets, speech, alpha, warped)
+            x, a = warped, ones
         if full:
-            aug.aug_pipeline_batch(w.offsets, speech, noise, geom, w.rir_len, w.fs, w.c, snr, alpha,
+            aug.aug_pipeline_batch(w.offsets, x, noise, geom, w.rir_len, w.fs, w.c, snr, a,
                                    w.frontend, foff, feats)
         else:
-            aug.aug_vtlp_mel_batch(w.offsets, speech, alpha, w.frontend, foff, feats)
+            aug.aug_vtlp_mel_batch(w.offsets, x, a, w.frontend, foff, feats)
 
     # images per step, for the image-sum kernel's algorithmic work (counted once, untimed)
     n_images = 0.0
-    if full:
+    if full and args.vtlp != "waveform-only":
         n_rir = w.n_utt * (1 + w.n_noise)
         chunk = max(1, min(n_rir, (1 << 28) // w.rir_len))
         g2 = geom.reshape(-1, 10)
@@ -232,16 +259,19 @@ def main() -> int:
     del h_speech, h_noise
     stages = {k: (ms / max(n, 1), n) for k, (ms, n) in prof.items() if n > 0}
     work = stage_work(w, n_images)
+    if args.vtlp == "waveform-only":
+        work = {k: v for k, v in work.items() if k == "vtlp"}
     dominant = max((k for k in stages if k in work), key=lambda k: stages[k][0] * stages[k][1])
     per_step_launches = stages[dominant][1] / args.steps
     roof = roofline_for(dominant, work, stages[dominant][0] * per_step_launches)
     roof["kernel"] = {"rir": "rir_image_kernel", "convolve": "convolve_kernel", "mel": "mel_kernel",
-                      "mix": "mix_kernel", "rir_spectrum": "rir_spectrum_kernel"}[dominant]
+                      "mix": "mix_kernel", "rir_spectrum": "rir_spectrum_kernel",
+                      "vtlp": "vtlp_resynth_kernel"}[dominant]
     roof["avg_launch_ms"] = stages[dominant][0]
     roof["traffic"] = recorded_traffic(args.workload, dominant)     # HBM bytes per launch, or null
 
     out = {
-        "metric": METRIC,
+        "metric": METRIC_BY_VTLP[args.vtlp],
         "value": w.audio_seconds / (ms_per_step * 1e-3),
         "unit": "audio-s/s",
         "n_gpus": 1,
@@ -253,8 +283,12 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": describe(w), "entry_point": "aug_pipeline_batch" if full else "aug_vtlp_mel_batch",
-                   "images_per_step": n_images},
+        "config": {"workload": describe(w),
+                   "entry_point": {"mel": "", "waveform": "aug_vtlp_resynth_batch + ",
+                                   "waveform-only": "aug_vtlp_resynth_batch"}[args.vtlp] +
+                                  ("" if args.vtlp == "waveform-only" else
+                                   "aug_pipeline_batch" if full else "aug_vtlp_mel_batch"),
+                   "vtlp": args.vtlp, "images_per_step": n_images},
         "roofline": roof,
         "with_h2d": {"ms_per_step": ms_with_h2d, "value": w.audio_seconds / (ms_with_h2d * 1e-3),
                      "note": "waveforms copied from pinned host memory before every call; not the headline"},
@@ -263,7 +297,7 @@ def main() -> int:
                                 for k in stages if k in work},
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w)
+        out["cpu_baseline"] = cpu_baseline(w, vtlp=args.vtlp)
     aug.close()
     print(json.dumps(out))
     return 0

@@ -488,6 +488,7 @@ int aug_vtlp_resynth_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, cons
     AUG_TRY(mark(ctx, -1));
     AUG_HIP(aug::launch_vtlp_table(ctx->stream, n_utt, alpha, ctx->vtlp_tab.as<float2>()), "warp table kernel");
     AUG_HIP(aug::launch_fill_u32(ctx->stream, wave_out, 0u, total), "output clear");
+    AUG_TRY(mark(ctx, AUG_STAGE_OTHER));
     AUG_HIP(aug::launch_vtlp_resynth(ctx->stream, n_utt, ctx->d_offsets.as<int64_t>(), max_len, wave,
                                      ctx->vtlp_tab.as<float2>(), tw, wave_out), "resynthesis kernel");
     AUG_TRY(mark(ctx, AUG_STAGE_VTLP));

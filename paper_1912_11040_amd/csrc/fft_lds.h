@@ -254,6 +254,59 @@ __device__ inline void fft_passes(float2 (&v)[16], float2* buf, const float2* __
     }
 }
 
+// The base twiddle of every butterfly a thread computes, fetched once.  A thread that repeats the same
+// transform with the same tid (one frame after another) keeps them in registers, which takes the table
+// loads, and their latency, out of its loop.
+template <int N, int T>
+struct FftLaneTwiddles {
+    using Plan = FftPlan<N>;
+    float2 w[Plan::kPasses][8];
+    template <int P = 0> __device__ inline void load(const float2* __restrict__ tw, int tid) {
+        if constexpr (P < Plan::kPasses) {
+            constexpr int R = Plan::radix(P), NS = Plan::ns(P);
+            if constexpr (NS > 1) {
+#pragma unroll
+                for (int bi = 0; bi < 16 / R; ++bi) w[P][bi] = tw[((tid + bi * T) % NS) * (N / (NS * R))];
+            }
+            load<P + 1>(tw, tid);
+        }
+    }
+    // Hides the values from the optimiser inside a loop: otherwise every power of every twiddle is also
+    // hoisted out of the loop and the register file overflows.
+    template <int P = 0> __device__ inline void keep_in_loop() {
+        if constexpr (P < Plan::kPasses) {
+            if constexpr (Plan::ns(P) > 1) {
+#pragma unroll
+                for (int bi = 0; bi < 16 / Plan::radix(P); ++bi) asm volatile("" : "+v"(w[P][bi].x), "+v"(w[P][bi].y));
+            }
+            keep_in_loop<P + 1>();
+        }
+    }
+};
+
+// fft_passes with the thread's twiddles supplied from registers
+template <int N, int T, bool INV, FftSync S, int P = 0>
+__device__ inline void fft_passes_cached(float2 (&v)[16], float2* buf, const FftLaneTwiddles<N, T>& lt, int tid) {
+    using Plan = FftPlan<N>;
+    constexpr int R = Plan::radix(P), NS = Plan::ns(P);
+#pragma unroll
+    for (int bi = 0; bi < 16 / R; ++bi) {
+        if constexpr (NS > 1) {
+            float2 w1 = lt.w[P][bi];
+            if (INV) w1.y = -w1.y;
+            twiddle_inputs<R>(&v[bi * R], w1);
+        }
+        SmallDft<R, INV>::run(&v[bi * R]);
+    }
+    if constexpr (P + 1 < Plan::kPasses) {
+        fft_store<N, T, R, NS>(v, buf, tid);
+        fft_sync<S>();
+        fft_load<N, T, Plan::radix(P + 1)>(v, buf, tid);
+        fft_sync<S>();
+        fft_passes_cached<N, T, INV, S, P + 1>(v, buf, lt, tid);
+    }
+}
+
 // Store the last pass's outputs in natural order.
 template <int N, int T>
 __device__ inline void fft_store_natural(const float2 (&v)[16], float2* buf, int tid) {
