@@ -142,9 +142,16 @@ typedef struct aug_frontend_cfg {
  *   wave           DEVICE float [total].
  *   alpha          DEVICE float [n_utt]: warp factor of each utterance
  *                  (1 = no warp; the paper's best range is [0.8, 1.2]).
- *   frame_offsets  HOST int64 [n_utt+1]: prefix sum of
- *                  aug_frame_count(length_u, win, hop); checked.
- *   feats_out      DEVICE float [total_frames][n_mel], row major, overwritten:
+ *   frame_offsets  HOST int64 [n_utt+1]: first output row of each utterance;
+ *                  frame_offsets[0] = 0 and utterance u owns rows
+ *                  frame_offsets[u] .. frame_offsets[u+1], at least
+ *                  aug_frame_count(length_u, win, hop) of them (checked).  The
+ *                  prefix sum of the frame counts gives the packed layout; rows
+ *                  an utterance owns beyond its frames are set to zero, so
+ *                  frame_offsets[u] = u * Tmax gives the padded batch
+ *                  [n_utt][Tmax][n_mel] that the paper's padded_batch step
+ *                  produces (Sec. 2.2).
+ *   feats_out      DEVICE float [frame_offsets[n_utt]][n_mel], row major, overwritten:
  *                  frame t of utterance u = (sum_k W[m][k] P_t[k])^power with
  *                  P_t[k] = |DFT_nfft(hamming * x[t hop .. t hop + win))[k]|^2,
  *                  k = 0..nfft/2, and W[m][k] the unit-peak triangular mel

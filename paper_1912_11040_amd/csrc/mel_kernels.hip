@@ -108,9 +108,13 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
     const int u = a.items[blockIdx.x].x;
     const int first = a.items[blockIdx.x].y;
     const int64_t start = a.offsets[u];
-    const int64_t n_frames_u = a.frame_offsets[u + 1] - a.frame_offsets[u];
     const float* x = a.wave + start;
     const int win = WIN ? WIN : a.cfg.win, hop = a.cfg.hop;
+    // The utterance owns rows_u rows of the output; the first n_frames_u hold its frames and the rest,
+    // if the caller reserved more (padded batches), are set to zero.
+    const int64_t len = a.offsets[u + 1] - start;
+    const int64_t rows_u = a.frame_offsets[u + 1] - a.frame_offsets[u];
+    const int64_t n_frames_u = len >= win ? 1 + (len - win) / hop : 0;
     const float power = a.cfg.power;
     float* feats = a.feats + (size_t)a.frame_offsets[u] * n_mel;
     float2* buf = fft_buf + slot * lds_padded_size(NC);
@@ -143,6 +147,11 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
 
     for (int it = 0; it < a.frames_per_group / kMelSlots; ++it) {
         const int64_t t = (int64_t)first + it * kMelSlots + slot;
+        if ((int64_t)first + it * kMelSlots >= n_frames_u) {      // only padding rows are left in this group
+            if (t < rows_u)
+                for (int m = sub; m < n_mel; m += kMelLanes) feats[t * n_mel + m] = 0.f;
+            continue;
+        }
         const bool live = t < n_frames_u;
         float2 v[16];
         // Loads are unconditional: a slot past the utterance's last frame recomputes that last frame (its
@@ -257,6 +266,8 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
                 const float e = A[m] + B[m + 1];
                 feats[t * n_mel + m] = e > 0.f ? __powf(e, power) : 0.f;
             }
+        } else if (t < rows_u) {
+            for (int m = sub; m < n_mel; m += kMelLanes) feats[t * n_mel + m] = 0.f;
         }
         fft_sync<FftSync::Wave>();                       // sums are read before the next frame clears them
     }

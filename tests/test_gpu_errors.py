@@ -45,8 +45,11 @@ def test_offsets_and_frontend_errors(aug):
     bad = np.array([0, 600, 500], np.int64)
     assert _code(aug.aug_vtlp_mel_batch, bad, x, alpha, fe, [0, 2, 2], feats)[0] == binding.AUG_ERR_INVALID_ARG
     good = np.array([0, 600, 1000], np.int64)
-    code, msg = _code(aug.aug_vtlp_mel_batch, good, x, alpha, fe, [0, 2, 4], feats)
+    code, msg = _code(aug.aug_vtlp_mel_batch, good, x, alpha, fe, [0, 2, 2], feats)     # one frame, no row for it
     assert code == binding.AUG_ERR_INVALID_ARG and "frame" in msg
+    aug.aug_vtlp_mel_batch(good, x, alpha, fe, [0, 2, 4], feats)                          # a spare row is padding
+    torch.cuda.synchronize()
+    assert float(feats[3].abs().max()) == 0.0
     fe256 = dataclasses.replace(fe, nfft=256, win=200)
     assert _code(aug.aug_vtlp_mel_batch, good, x, alpha, fe256, [0, 3, 5], feats)[0] == binding.AUG_ERR_UNSUPPORTED
     fe_bad = dataclasses.replace(fe, n_mel=0)

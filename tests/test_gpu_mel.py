@@ -94,6 +94,36 @@ def test_other_mel_counts_and_band(aug):
     assert feat_err(f, ref) <= FEAT_TOL
 
 
+def test_padded_batch_layout(aug):
+    # frame_offsets[u] = u * Tmax: every utterance owns Tmax rows, the ones past its frames come back zero
+    import torch
+    from paper_1912_11040_amd.binding import AugError
+    rng = np.random.default_rng(31)
+    lens = [5000, 0, 399, 16000, 400, 12001, 27000]
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    x = rng.standard_normal(int(offsets[-1])).astype(np.float32)
+    alpha = rng.uniform(0.8, 1.2, len(lens)).astype(np.float32)
+    t = np.array([O.frame_count(n, FE.win, FE.hop) for n in lens])
+    t_max = int(t.max()) + 3
+    foff = (np.arange(len(lens) + 1) * t_max).astype(np.int64)
+    feats = torch.full((len(lens), t_max, FE.n_mel), float("nan"), dtype=torch.float32, device="cuda")
+    aug.aug_vtlp_mel_batch(offsets, dev(x), dev(alpha), FE, foff, feats)
+    torch.cuda.synchronize()
+    got = feats.cpu().numpy()
+    ref = O.vtlp_mel_batch(offsets, x, alpha, FE)
+    packed = np.concatenate([[0], np.cumsum(t)])
+    for u in range(len(lens)):
+        assert np.all(got[u, t[u]:] == 0.0)
+        if t[u]:
+            assert feat_err(got[u, :t[u]], ref[packed[u]:packed[u + 1]]) <= FEAT_TOL
+    # fewer rows than frames is an error
+    short = foff.copy()
+    short[4:] -= t_max - int(t[3]) + 1
+    with pytest.raises(AugError) as e:
+        aug.aug_vtlp_mel_batch(offsets, dev(x), dev(alpha), FE, short, feats)
+    assert e.value.code == -1
+
+
 def test_most_mel_channels_the_interface_takes(aug):
     import dataclasses
     fe = dataclasses.replace(FE, n_mel=128)

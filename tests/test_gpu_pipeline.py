@@ -138,6 +138,29 @@ def test_throughput_full_size_sampled(aug):
     assert feat_err(lean["feats"][foff[u]:foff[u + 1]], ref["feats"]) <= FEAT_TOL
 
 
+@pytest.mark.parametrize("want_mixed", [False, True])
+def test_padded_batch_layout(aug, want_mixed):
+    # the padded [n_utt][Tmax][n_mel] output through the fused call, with and without the mixture as an output
+    import torch
+    w = W.varlen(n_utt=4, rir_len=1500, min_s=0.01, max_s=1.2)
+    d = DeviceWorkload(w)
+    t = np.diff(w.frame_offsets())
+    t_max = int(t.max()) + 2
+    foff = (np.arange(w.n_utt + 1) * t_max).astype(np.int64)
+    feats = torch.full((w.n_utt, t_max, w.frontend.n_mel), float("nan"), dtype=torch.float32, device="cuda")
+    mixed = torch.empty((w.total,), dtype=torch.float32, device="cuda") if want_mixed else None
+    aug.aug_pipeline_batch(w.offsets, d.speech, d.noise, d.geom, w.rir_len, w.fs, w.c, d.snr_db, d.alpha,
+                           w.frontend, foff, feats, None, mixed, None)
+    torch.cuda.synchronize()
+    got = feats.cpu().numpy()
+    ref = _oracle(w)["feats"]
+    packed = w.frame_offsets()
+    for u in range(w.n_utt):
+        assert np.all(got[u, t[u]:] == 0.0)
+        if t[u]:
+            assert feat_err(got[u, :t[u]], ref[packed[u]:packed[u + 1]]) <= FEAT_TOL
+
+
 def test_no_noise_pipeline(aug):
     import dataclasses
     w = W.tiny(n_utt=2)
