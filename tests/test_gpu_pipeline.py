@@ -161,6 +161,30 @@ def test_padded_batch_layout(aug, want_mixed):
             assert feat_err(got[u, :t[u]], ref[packed[u]:packed[u + 1]]) <= FEAT_TOL
 
 
+def test_two_contexts_on_two_streams(aug):
+    # double buffering: batches alternate between two contexts, each on a stream of its own with its own
+    # workspace; every batch must come out as it does on a single stream
+    import torch
+    from paper_1912_11040_amd.binding import Augmenter
+    ws = [W.varlen(n_utt=3, rir_len=1200, min_s=0.05, max_s=0.8, seed=s) for s in (7, 8, 9, 10)]
+    want = [_run(aug, w, want_rir=False, want_mixed=False)["feats"] for w in ws]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    ctxs = [Augmenter(0, s) for s in streams]
+    keep = []
+    for k, w in enumerate(ws):
+        with torch.cuda.stream(streams[k % 2]):
+            d = DeviceWorkload(w)
+            feats = d.empty_feats()
+            ctxs[k % 2].aug_pipeline_batch(w.offsets, d.speech, d.noise, d.geom, w.rir_len, w.fs, w.c, d.snr_db,
+                                           d.alpha, w.frontend, d.frame_offsets, feats)
+        keep.append((d, feats))
+    torch.cuda.synchronize()
+    for (d, feats), ref in zip(keep, want):
+        assert feat_err(feats.cpu().numpy(), ref.astype(np.float64)) <= 1e-6
+    for c in ctxs:
+        c.close()
+
+
 def test_no_noise_pipeline(aug):
     import dataclasses
     w = W.tiny(n_utt=2)
