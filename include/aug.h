@@ -53,6 +53,8 @@ typedef struct aug_ctx aug_ctx;
 #define AUG_MAX_NOISE 8
 /* Largest number of mel channels. */
 #define AUG_MAX_MEL 128
+#define AUG_MAX_UTT 65535        /* utterances per call */
+#define AUG_MAX_UTT_SAMPLES ((1 << 30) - 1)   /* samples per utterance */
 
 /*
  * Create a context bound to GPU `device_id` and to `hip_stream` (a hipStream_t
@@ -104,7 +106,9 @@ int aug_rir_batch(aug_ctx* ctx, int n_rir, const float* geom, int rir_len,
  *
  *   offsets     HOST int64 [n_utt+1], ascending, offsets[0] == 0: utterance u
  *               occupies samples offsets[u] .. offsets[u+1]-1 of every packed
- *               signal array.  Empty utterances are allowed.
+ *               signal array.  Empty utterances are allowed; n_utt <=
+ *               AUG_MAX_UTT and every utterance <= AUG_MAX_UTT_SAMPLES samples
+ *               (AUG_ERR_UNSUPPORTED otherwise).
  *   speech      DEVICE float [total], total = offsets[n_utt].
  *   n_noise     0..AUG_MAX_NOISE noise sources per utterance.
  *   noise       DEVICE float [n_noise][total] (NULL iff n_noise == 0).
@@ -191,8 +195,7 @@ typedef struct aug_vtlp_cfg {
  * All nfft samples of the inverse DFT of Y are added at the frame's position.
  * Sums of overlapping frames use floating-point atomics, so the last bits of
  * wave_out can differ between runs.
- * Errors: AUG_ERR_UNSUPPORTED for any cfg other than 800 / 400 / 2048 or more
- * than 65535 utterances.
+ * Errors: AUG_ERR_UNSUPPORTED for any cfg other than 800 / 400 / 2048.
  */
 int aug_vtlp_resynth_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, const float* wave,
                            const float* alpha, const aug_vtlp_cfg* cfg, float* wave_out);

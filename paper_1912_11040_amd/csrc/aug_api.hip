@@ -81,6 +81,7 @@ int fail_hip(aug_ctx* ctx, hipError_t e, const char* what) {
 
 int check_offsets(aug_ctx* ctx, int n_utt, const int64_t* offsets) {
     if (n_utt < 0) return fail(ctx, AUG_ERR_INVALID_ARG, "n_utt is negative");
+    if (n_utt > AUG_MAX_UTT) return fail(ctx, AUG_ERR_UNSUPPORTED, "more than %d utterances in one call", AUG_MAX_UTT);
     if (!offsets) return fail(ctx, AUG_ERR_INVALID_ARG, "offsets is null");
     if (offsets[0] != 0) return fail(ctx, AUG_ERR_INVALID_ARG, "offsets[0] must be 0");
     for (int u = 0; u < n_utt; ++u) {
@@ -473,7 +474,6 @@ int aug_vtlp_resynth_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, cons
         return fail(ctx, AUG_ERR_INVALID_ARG, "need win >= 2, hop >= 1, nfft >= win");
     if (!aug::vtlp_supported(cfg->win, cfg->hop, cfg->nfft))
         return fail(ctx, AUG_ERR_UNSUPPORTED, "kernels are built for win 800, hop 400, nfft 2048");
-    if (n_utt > 65535) return fail(ctx, AUG_ERR_UNSUPPORTED, "more than 65535 utterances in one call");
     if (!wave || !alpha || !wave_out) return fail(ctx, AUG_ERR_INVALID_ARG, "wave, alpha or wave_out is null");
     const int64_t total = offsets[n_utt];
     if (wave_out < wave + total && wave < wave_out + total)
