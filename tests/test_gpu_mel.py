@@ -46,6 +46,22 @@ def test_features_config_subset(aug):
     assert feat_err(f, ref) <= FEAT_TOL
 
 
+def test_features_config_full_size_sampled(aug):
+    # the whole features-only configuration in one call, as the benchmark launches it with
+    # --workload features; the oracle checks sampled utterances frame by frame
+    w = W.features_only()
+    print(f"case: features config, {w.n_utt} utterances, {w.total} samples", flush=True)
+    f = _run(aug, w.offsets, w.speech, w.alpha)
+    assert f.shape == (w.n_utt * 798, 40) and not np.isnan(f).any()
+    foff = w.frame_offsets()
+    for u in [0, 1, 2047, w.n_utt - 1, int(np.random.default_rng(2).integers(0, w.n_utt))]:
+        a, b = int(w.offsets[u]), int(w.offsets[u + 1])
+        ref = O.vtlp_mel_batch(np.array([0, b - a]), w.speech[a:b], w.alpha[u:u + 1], FE)
+        err = feat_err(f[foff[u]:foff[u + 1]], ref)
+        print(f"  utterance {u}: feature error {err:.2e}", flush=True)
+        assert err <= FEAT_TOL
+
+
 def test_ragged_short_and_empty_utterances(aug):
     rng = np.random.default_rng(0)
     lens = [0, 399, 400, 559, 560, 12345, 1, 400 + 160 * 63, 400 + 160 * 64, 400 + 160 * 65]

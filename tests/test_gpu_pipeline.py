@@ -80,6 +80,22 @@ def test_batch_config_subset(aug):
     _compare_unmaterialised(aug, w, ref)
 
 
+def test_batch_config_full_size(aug):
+    # all 64 utterances in one call; the direct-convolution oracle checks eight of them
+    w = W.batch()
+    print(f"case: batch config full, {w.n_utt} utterances, L={w.rir_len}", flush=True)
+    got = _run(aug, w)
+    lean = _run(aug, w, want_rir=False, want_mixed=False)
+    foff = w.frame_offsets()
+    for u in range(0, w.n_utt, 8):
+        s = w.slice([u])
+        ref = _oracle(s)
+        sub = dict(rir=got["rir"][u:u + 1], mixed=got["mixed"][w.offsets[u]:w.offsets[u + 1]],
+                   gains=got["gains"][u:u + 1], feats=got["feats"][foff[u]:foff[u + 1]])
+        _compare(sub, ref, s)
+        assert feat_err(lean["feats"][foff[u]:foff[u + 1]], ref["feats"]) <= FEAT_TOL
+
+
 def test_varlen_config_small(aug):
     w = W.varlen(n_utt=5, rir_len=2000, min_s=0.02, max_s=1.5)
     print("case: varlen small, 3 noises", flush=True)
