@@ -33,7 +33,7 @@ __all__ = [
     "frame_count", "rir_single", "rir_batch", "convolve_direct", "convolve_fft",
     "convolve_at", "reverberate", "snr_gains", "convolve_mix_batch", "hamming",
     "dft_matrix", "stft_power", "bilinear_warp", "mel_edges_hz", "warped_mel_matrix",
-    "vtlp_mel_batch", "pipeline_batch",
+    "dct2_matrix", "mel_epilogue", "vtlp_mel_batch", "pipeline_batch",
 ]
 
 
@@ -293,11 +293,40 @@ def warped_mel_matrix(alpha, n_mel: int, nfft: int, fs: float, f_lo: float, f_hi
     return w
 
 
-def vtlp_mel_batch(offsets, wave, alpha, fe, method="dft"):
-    """Power-mel features [total_frames, n_mel] fp64: (W_alpha P_t)^(power), 0 -> 0.
+def dct2_matrix(n_ceps: int, n_mel: int):
+    """Orthonormal DCT-II: D[q, m] = s_q cos(pi q (m + 1/2) / M), s_0 = sqrt(1/M), s_q = sqrt(2/M)."""
+    q = np.arange(n_ceps, dtype=np.float64)[:, None]
+    m = np.arange(n_mel, dtype=np.float64)[None, :]
+    d = np.cos(np.pi * q * (m + 0.5) / n_mel) * np.sqrt(2.0 / n_mel)
+    d[0] *= np.sqrt(0.5)
+    return d
 
-    `fe` has fields fs, win, hop, nfft, n_mel, f_lo, f_hi, power.  One warp
-    factor per utterance (Sec. 2.3); exponent 1/15 in the paper.
+
+def mel_epilogue(energies, fe):
+    """What is kept of the mel energies E[t, m] (Sec. 2.3 names all three).
+
+    "power" (the paper's feature): E^power, 0 -> 0.  "log": the conventional log-mel, natural logarithm
+    of max(E, log_floor).  "mfcc": the first n_ceps coefficients of the orthonormal DCT-II of the log-mel
+    vector (no liftering, no energy term).  The floor and the DCT normalisation are readings: the paper
+    only names these features as the ones it replaces.
+    """
+    kind = getattr(fe, "feature", "power")
+    if kind == "power":
+        return np.power(energies, fe.power)
+    logmel = np.log(np.maximum(energies, fe.log_floor))
+    if kind == "log":
+        return logmel
+    if kind == "mfcc":
+        return logmel @ dct2_matrix(fe.n_ceps, fe.n_mel).T
+    raise ValueError(f"unknown feature kind {kind!r}")
+
+
+def vtlp_mel_batch(offsets, wave, alpha, fe, method="dft"):
+    """Mel features [total_frames, feature_dim] fp64 from the warped mel energies W_alpha P_t.
+
+    `fe` has fields fs, win, hop, nfft, n_mel, f_lo, f_hi, power and, optionally, feature, n_ceps,
+    log_floor (see mel_epilogue).  One warp factor per utterance (Sec. 2.3); the paper's feature is
+    the power law with exponent 1/15.
     """
     offsets = np.asarray(offsets, dtype=np.int64)
     rows = []
@@ -305,9 +334,10 @@ def vtlp_mel_batch(offsets, wave, alpha, fe, method="dft"):
         x = np.asarray(wave[int(offsets[u]):int(offsets[u + 1])], dtype=np.float64)
         p = stft_power(x, fe.win, fe.hop, fe.nfft, method)
         w = warped_mel_matrix(alpha[u], fe.n_mel, fe.nfft, fe.fs, fe.f_lo, fe.f_hi)
-        rows.append(np.power(p @ w.T, fe.power))
+        rows.append(mel_epilogue(p @ w.T, fe))
     if not rows:
-        return np.zeros((0, fe.n_mel))
+        dim = fe.n_ceps if getattr(fe, "feature", "power") == "mfcc" else fe.n_mel
+        return np.zeros((0, dim))
     return np.concatenate(rows, axis=0)
 
 

@@ -37,6 +37,13 @@ class FrontendConfig:
     f_lo: float = 0.0
     f_hi: float = 8000.0
     power: float = 1.0 / 15.0
+    feature: str = "power"      # "power": E^power;  "log": ln max(E, log_floor);  "mfcc": DCT-II of the log energies
+    n_ceps: int = 13            # coefficients kept when feature == "mfcc"
+    log_floor: float = 1e-10
+
+    @property
+    def feature_dim(self) -> int:
+        return self.n_ceps if self.feature == "mfcc" else self.n_mel
 
 
 @dataclass

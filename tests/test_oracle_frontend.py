@@ -169,3 +169,33 @@ def test_ragged_and_short_utterances():
     assert f.shape == (0 + 0 + 3 + 2, 40)
     g = O.vtlp_mel_batch(np.array([0, 560], np.int64), x[1200:], a[3:], FE)
     np.testing.assert_array_equal(f[3:], g)
+
+
+def test_log_mel_and_mfcc_epilogues():
+    import dataclasses
+    from scipy.fft import dct
+    fe = FrontendConfig()
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal(4000).astype(np.float32)
+    off, alpha = np.array([0, 4000]), np.array([0.9])
+    power = O.vtlp_mel_batch(off, x, alpha, fe)
+    logmel = O.vtlp_mel_batch(off, x, alpha, dataclasses.replace(fe, feature="log"))
+    # the same energies under two epilogues: exp(log E) = (E^(1/15))^15
+    np.testing.assert_allclose(np.exp(logmel), power ** 15, rtol=1e-10)
+    # DCT: rows are orthonormal, the full transform is invertible, and it is the library's type-II "ortho" DCT
+    d = O.dct2_matrix(40, 40)
+    np.testing.assert_allclose(d @ d.T, np.eye(40), atol=1e-12)
+    full = O.vtlp_mel_batch(off, x, alpha, dataclasses.replace(fe, feature="mfcc", n_ceps=40))
+    np.testing.assert_allclose(full @ d, logmel, atol=1e-10)
+    np.testing.assert_allclose(full, dct(logmel, type=2, norm="ortho", axis=1), atol=1e-10)
+    mfcc = O.vtlp_mel_batch(off, x, alpha, dataclasses.replace(fe, feature="mfcc", n_ceps=13))
+    assert mfcc.shape == (power.shape[0], 13)
+    np.testing.assert_allclose(mfcc, full[:, :13], atol=1e-12)
+    np.testing.assert_allclose(mfcc[:, 0], logmel.sum(axis=1) / np.sqrt(40.0), atol=1e-10)
+    # a constant log-mel vector has only the zeroth coefficient
+    flat = O.mel_epilogue(np.full((2, 40), 3.0), dataclasses.replace(fe, feature="mfcc", n_ceps=40))
+    assert np.max(np.abs(flat[:, 1:])) < 1e-12
+    # the floor: silence gives ln(floor) in every channel
+    sil = O.vtlp_mel_batch(np.array([0, 800]), np.zeros(800, np.float32), np.array([1.0]),
+                           dataclasses.replace(fe, feature="log", log_floor=1e-6))
+    np.testing.assert_allclose(sil, np.log(1e-6))
