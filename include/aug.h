@@ -126,6 +126,15 @@ int aug_convolve_mix_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets,
                            const float* rir, int rir_len, const float* snr_db,
                            float* mixed_out, float* gains_out);
 
+/* What is kept of the mel energies E[m] of a frame (Sec. 2.3 names all three). */
+enum {
+    AUG_FEAT_POWER_LAW = 0,   /* E^power: the paper's power-mel filterbank coefficients; 0 -> 0 */
+    AUG_FEAT_LOG = 1,         /* ln max(E, log_floor): conventional log-mel */
+    AUG_FEAT_MFCC = 2         /* first n_ceps coefficients of the orthonormal DCT-II of the log-mel vector:
+                                 c[q] = s_q sum_m ln max(E[m], log_floor) cos(pi q (m + 1/2) / n_mel),
+                                 s_0 = sqrt(1/n_mel), s_q = sqrt(2/n_mel) */
+};
+
 /* Front-end constants.  win <= nfft, nfft a power of two in 64..2048 (kernels
  * are built for 512), hop >= 1, 1 <= n_mel <= AUG_MAX_MEL, 0 <= f_lo < f_hi <= fs/2. */
 typedef struct aug_frontend_cfg {
@@ -136,8 +145,14 @@ typedef struct aug_frontend_cfg {
     int   n_mel;    /* mel channels */
     float f_lo;     /* lowest band edge, Hz */
     float f_hi;     /* highest band edge, Hz */
-    float power;    /* power-law exponent, 1/15 in the paper */
+    float power;    /* power-law exponent, 1/15 in the paper (AUG_FEAT_POWER_LAW) */
+    int   feature;  /* AUG_FEAT_* */
+    int   n_ceps;   /* AUG_FEAT_MFCC: coefficients kept, 1..n_mel; ignored otherwise */
+    float log_floor;/* AUG_FEAT_LOG / AUG_FEAT_MFCC: energies are raised to it before the logarithm, > 0 */
 } aug_frontend_cfg;
+
+/* Values per output row: n_ceps for AUG_FEAT_MFCC, else n_mel (host helper; 0 if cfg is NULL). */
+int aug_feature_dim(const aug_frontend_cfg* cfg);
 
 /*
  * Power-mel features with the VTLP warp (Sec. 2.3, Eq. (1)).
@@ -155,7 +170,8 @@ typedef struct aug_frontend_cfg {
  *                  frame_offsets[u] = u * Tmax gives the padded batch
  *                  [n_utt][Tmax][n_mel] that the paper's padded_batch step
  *                  produces (Sec. 2.2).
- *   feats_out      DEVICE float [frame_offsets[n_utt]][n_mel], row major, overwritten:
+ *   feats_out      DEVICE float [frame_offsets[n_utt]][aug_feature_dim(cfg)], row
+ *                  major, overwritten.  With AUG_FEAT_POWER_LAW:
  *                  frame t of utterance u = (sum_k W[m][k] P_t[k])^power with
  *                  P_t[k] = |DFT_nfft(hamming * x[t hop .. t hop + win))[k]|^2,
  *                  k = 0..nfft/2, and W[m][k] the unit-peak triangular mel

@@ -21,9 +21,11 @@ AUG_ERR_UNSUPPORTED = -2
 AUG_ERR_NOMEM = -3
 AUG_ERR_HIP = -4
 
-EXPORTS = ("aug_create", "aug_destroy", "aug_last_error", "aug_frame_count", "aug_rir_batch",
+EXPORTS = ("aug_create", "aug_destroy", "aug_last_error", "aug_frame_count", "aug_feature_dim", "aug_rir_batch",
            "aug_convolve_mix_batch", "aug_vtlp_mel_batch", "aug_vtlp_resynth_batch", "aug_pipeline_batch",
            "aug_profile_enable", "aug_profile_read")
+
+FEATURE_KINDS = {"power": 0, "log": 1, "mfcc": 2}      # AUG_FEAT_*
 
 STAGES = ("rir", "rir_spectrum", "convolve", "mix", "mel", "other", "vtlp")
 
@@ -43,12 +45,15 @@ class FrontendCfg(ctypes.Structure):
     """Mirror of aug_frontend_cfg."""
     _fields_ = [("fs", ctypes.c_float), ("win", ctypes.c_int), ("hop", ctypes.c_int),
                 ("nfft", ctypes.c_int), ("n_mel", ctypes.c_int), ("f_lo", ctypes.c_float),
-                ("f_hi", ctypes.c_float), ("power", ctypes.c_float)]
+                ("f_hi", ctypes.c_float), ("power", ctypes.c_float), ("feature", ctypes.c_int),
+                ("n_ceps", ctypes.c_int), ("log_floor", ctypes.c_float)]
 
     @classmethod
     def of(cls, fe) -> "FrontendCfg":
         return cls(float(fe.fs), int(fe.win), int(fe.hop), int(fe.nfft), int(fe.n_mel),
-                   float(fe.f_lo), float(fe.f_hi), float(fe.power))
+                   float(fe.f_lo), float(fe.f_hi), float(fe.power),
+                   FEATURE_KINDS[getattr(fe, "feature", "power")], int(getattr(fe, "n_ceps", 0)),
+                   float(getattr(fe, "log_floor", 1e-10)))
 
 
 _lib = None
@@ -75,6 +80,8 @@ def load_library() -> ctypes.CDLL:
     lib.aug_last_error.restype = ctypes.c_char_p
     lib.aug_frame_count.argtypes = [i64, ci, ci]
     lib.aug_frame_count.restype = i64
+    lib.aug_feature_dim.argtypes = [p_cfg]
+    lib.aug_feature_dim.restype = ci
     lib.aug_rir_batch.argtypes = [vp, ci, vp, ci, cf, cf, vp, vp]
     lib.aug_rir_batch.restype = ci
     lib.aug_convolve_mix_batch.argtypes = [vp, ci, p_i64, vp, ci, vp, vp, ci, vp, vp, vp]

@@ -103,7 +103,15 @@ int check_frontend(aug_ctx* ctx, const aug_frontend_cfg* cfg) {
         return fail(ctx, AUG_ERR_INVALID_ARG, "n_mel must be in 1..%d", AUG_MAX_MEL);
     if (!(cfg->f_lo >= 0.f) || !(cfg->f_hi > cfg->f_lo) || !(cfg->f_hi <= 0.5f * cfg->fs))
         return fail(ctx, AUG_ERR_INVALID_ARG, "need 0 <= f_lo < f_hi <= fs/2");
-    if (!(cfg->power > 0.f)) return fail(ctx, AUG_ERR_INVALID_ARG, "power must be positive");
+    if (cfg->feature == AUG_FEAT_POWER_LAW) {
+        if (!(cfg->power > 0.f)) return fail(ctx, AUG_ERR_INVALID_ARG, "power must be positive");
+    } else if (cfg->feature == AUG_FEAT_LOG || cfg->feature == AUG_FEAT_MFCC) {
+        if (!(cfg->log_floor > 0.f)) return fail(ctx, AUG_ERR_INVALID_ARG, "log_floor must be positive");
+        if (cfg->feature == AUG_FEAT_MFCC && (cfg->n_ceps < 1 || cfg->n_ceps > cfg->n_mel))
+            return fail(ctx, AUG_ERR_INVALID_ARG, "n_ceps must be in 1..n_mel");
+    } else {
+        return fail(ctx, AUG_ERR_INVALID_ARG, "unknown feature kind %d", cfg->feature);
+    }
     if (cfg->nfft != 512) return fail(ctx, AUG_ERR_UNSUPPORTED, "kernels are built for nfft = 512");
     return AUG_OK;
 }
@@ -298,6 +306,17 @@ int run_mel(aug_ctx* ctx, int n_utt, const float* wave, const float* alpha, cons
         AUG_HIP(aug::launch_window(ctx->stream, cfg->win, ctx->window.as<float>()), "window kernel");
         ctx->window_n = cfg->win;
     }
+    const float* dct = nullptr;
+    if (cfg->feature == AUG_FEAT_MFCC) {
+        if (ctx->dct_ceps != cfg->n_ceps || ctx->dct_mel != cfg->n_mel) {
+            AUG_HIP(hipStreamSynchronize(ctx->stream), "stream synchronize");      // earlier work may read the old table
+            AUG_HIP(ctx->dct.reserve(sizeof(float) * (size_t)cfg->n_ceps * cfg->n_mel), "cosine table");
+            AUG_HIP(aug::launch_dct_table(ctx->stream, cfg->n_ceps, cfg->n_mel, ctx->dct.as<float>()), "cosine table kernel");
+            ctx->dct_ceps = cfg->n_ceps;
+            ctx->dct_mel = cfg->n_mel;
+        }
+        dct = ctx->dct.as<float>();
+    }
     AUG_HIP(ctx->mel_tab.reserve(sizeof(float2) * (size_t)n_utt * aug::mel_table_stride(cfg->nfft)), "mel table");
     AUG_TRY(mark(ctx, -1));
     AUG_HIP(aug::launch_mel_table(ctx->stream, n_utt, alpha, *cfg, ctx->mel_tab.as<float2>()), "mel table kernel");
@@ -313,6 +332,7 @@ int run_mel(aug_ctx* ctx, int n_utt, const float* wave, const float* alpha, cons
     ma.gains = gains;
     ma.n_extra = n_extra;
     ma.mel_tab = ctx->mel_tab.as<float2>();
+    ma.dct = dct;
     ma.window = ctx->window.as<float>();
     ma.twiddle = tw;
     ma.cfg = *cfg;
@@ -383,7 +403,7 @@ int aug_destroy(aug_ctx* ctx) {
         rc = AUG_ERR_HIP;
     }
     DeviceBuffer* bufs[] = {&ctx->d_offsets, &ctx->d_frame_offsets, &ctx->d_conv_items, &ctx->d_frame_items,
-                            &ctx->rir_items, &ctx->rir_ctrl, &ctx->rir_pow, &ctx->rir, &ctx->rir_spec, &ctx->reverb, &ctx->energy, &ctx->gains, &ctx->vtlp_tab, &ctx->mel_tab,
+                            &ctx->rir_items, &ctx->rir_ctrl, &ctx->rir_pow, &ctx->rir, &ctx->rir_spec, &ctx->reverb, &ctx->energy, &ctx->gains, &ctx->vtlp_tab, &ctx->dct, &ctx->mel_tab,
                             &ctx->window};
     for (DeviceBuffer* b : bufs) b->release();
     for (DeviceBuffer& b : ctx->twiddle) b.release();
@@ -463,6 +483,11 @@ int aug_vtlp_mel_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, const fl
     if (!wave || !alpha || !feats_out) return fail(ctx, AUG_ERR_INVALID_ARG, "wave, alpha or feats_out is null");
     AUG_TRY(sync_packing(ctx, n_utt, offsets, frame_offsets, 0, aug::mel_frames_per_group()));
     return run_mel(ctx, n_utt, wave, alpha, cfg, feats_out);
+}
+
+int aug_feature_dim(const aug_frontend_cfg* cfg) {
+    if (!cfg) return 0;
+    return cfg->feature == AUG_FEAT_MFCC ? cfg->n_ceps : cfg->n_mel;
 }
 
 int aug_vtlp_resynth_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, const float* wave, const float* alpha,

@@ -61,6 +61,8 @@ struct aug_ctx {
     aug::DeviceBuffer mel_tab;           // float2 [n_utt][nfft/2+1]: (channel, weight) per bin
     aug::DeviceBuffer twiddle[16];       // per log2(n): float2 [n + n/2 + 1] FFT twiddles
     aug::DeviceBuffer window;            // float [win]
+    aug::DeviceBuffer dct;               // float [n_ceps][n_mel]
+    int dct_ceps = 0, dct_mel = 0;       // shape the table was built for
     aug::DeviceBuffer vtlp_tab;          // float2 [n_utt][vtlp_table_entries()]: (source bin, weight) per output bin
     int window_n = 0;
 
@@ -148,12 +150,15 @@ struct MelArgs {
     const float* gains;            // [n_utt][n_extra]
     int n_extra;
     const float2* mel_tab;
+    const float* dct;              // [n_ceps][n_mel] orthonormal DCT-II rows (AUG_FEAT_MFCC), else null
     const float* window;
     const float2* twiddle;         // table for the nfft/2-point complex transform
     aug_frontend_cfg cfg;
     float* feats;
 };
 int mel_frames_per_group();
+// dct float [n_ceps][n_mel]: s_q cos(pi q (m + 1/2) / n_mel), computed in fp64
+hipError_t launch_dct_table(hipStream_t s, int n_ceps, int n_mel, float* dct);
 hipError_t launch_mel(hipStream_t s, const MelArgs& a);
 
 // Waveform VTLP: per-utterance table of (lower source bin, interpolation weight) for every output bin,

@@ -96,6 +96,8 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
     static_assert(NC == 256 && NC / 16 == kMelLanes, "two radix-16 passes, sixteen lanes per frame");
     extern __shared__ __align__(16) unsigned char smem[];
     const int n_mel = a.cfg.n_mel;
+    const int feature = a.cfg.feature;
+    const int n_out = feature == AUG_FEAT_MFCC ? a.cfg.n_ceps : n_mel;     // values per output row
     const int n_seg = n_mel + 2;                         // band sums A[c], B[c] for c = 0..n_mel (+1 pad)
     float2* fft_buf = reinterpret_cast<float2*>(smem);                       // [slots][padded NC]
     float2* s_tab = fft_buf + kMelSlots * lds_padded_size(NC);               // [NC + 1]: (c, w) per bin
@@ -116,7 +118,7 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
     const int64_t rows_u = a.frame_offsets[u + 1] - a.frame_offsets[u];
     const int64_t n_frames_u = len >= win ? 1 + (len - win) / hop : 0;
     const float power = a.cfg.power;
-    float* feats = a.feats + (size_t)a.frame_offsets[u] * n_mel;
+    float* feats = a.feats + (size_t)a.frame_offsets[u] * n_out;
     float2* buf = fft_buf + slot * lds_padded_size(NC);
     float* A = s_ab + (slot * 2) * n_seg;
     float* B = A + n_seg;
@@ -149,7 +151,7 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
         const int64_t t = (int64_t)first + it * kMelSlots + slot;
         if ((int64_t)first + it * kMelSlots >= n_frames_u) {      // only padding rows are left in this group
             if (t < rows_u)
-                for (int m = sub; m < n_mel; m += kMelLanes) feats[t * n_mel + m] = 0.f;
+                for (int m = sub; m < n_out; m += kMelLanes) feats[t * n_out + m] = 0.f;
             continue;
         }
         const bool live = t < n_frames_u;
@@ -261,19 +263,56 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
         fft_sync<FftSync::Wave>();
 
         // channel m collects the rising side of band m and the falling side of band m + 1
-        if (live) {
-            for (int m = sub; m < n_mel; m += kMelLanes) {
-                const float e = A[m] + B[m + 1];
-                feats[t * n_mel + m] = e > 0.f ? __powf(e, power) : 0.f;
+        if (feature == AUG_FEAT_POWER_LAW) {
+            if (live) {
+                for (int m = sub; m < n_mel; m += kMelLanes) {
+                    const float e = A[m] + B[m + 1];
+                    feats[t * n_mel + m] = e > 0.f ? __powf(e, power) : 0.f;
+                }
             }
-        } else if (t < rows_u) {
-            for (int m = sub; m < n_mel; m += kMelLanes) feats[t * n_mel + m] = 0.f;
+        } else {
+            // log-mel; for cepstra the log energies go back to A[m] (read by the lane of channel m only),
+            // then every lane takes the dot products of its coefficients with the whole vector
+            for (int m = sub; m < n_mel; m += kMelLanes) {
+                const float le = logf(fmaxf(A[m] + B[m + 1], a.cfg.log_floor));
+                if (feature == AUG_FEAT_LOG) {
+                    if (live) feats[t * n_mel + m] = le;
+                } else {
+                    A[m] = le;
+                }
+            }
+            if (feature == AUG_FEAT_MFCC) {
+                fft_sync<FftSync::Wave>();
+                for (int q = sub; q < n_out; q += kMelLanes) {
+                    const float* row = a.dct + q * n_mel;
+                    float acc = 0.f;
+                    for (int m = 0; m < n_mel; ++m) acc += row[m] * A[m];
+                    if (live) feats[t * n_out + q] = acc;
+                }
+            }
         }
+        if (!live && t < rows_u)
+            for (int m = sub; m < n_out; m += kMelLanes) feats[t * n_out + m] = 0.f;
         fft_sync<FftSync::Wave>();                       // sums are read before the next frame clears them
     }
 }
 
+__global__ void dct_table_kernel(int n_ceps, int n_mel, float* dct) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_ceps * n_mel) return;
+    const int q = i / n_mel, m = i % n_mel;
+    const double s = q == 0 ? sqrt(1.0 / (double)n_mel) : sqrt(2.0 / (double)n_mel);
+    dct[i] = (float)(s * cos(M_PI * (double)q * ((double)m + 0.5) / (double)n_mel));
+}
+
 }  // namespace
+
+hipError_t launch_dct_table(hipStream_t s, int n_ceps, int n_mel, float* dct) {
+    const int n = n_ceps * n_mel;
+    if (n <= 0) return hipSuccess;
+    dct_table_kernel<<<dim3((n + 255) / 256), dim3(256), 0, s>>>(n_ceps, n_mel, dct);
+    return hipGetLastError();
+}
 
 int mel_frames_per_group() { return kFramesPerGroup; }
 

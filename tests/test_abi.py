@@ -45,9 +45,26 @@ def test_frame_count_helper(lib):
 
 
 def test_frontend_struct_matches_header():
-    assert ctypes.sizeof(binding.FrontendCfg) == 32
+    assert ctypes.sizeof(binding.FrontendCfg) == 44
     assert [f[0] for f in binding.FrontendCfg._fields_] == \
-        ["fs", "win", "hop", "nfft", "n_mel", "f_lo", "f_hi", "power"]
+        ["fs", "win", "hop", "nfft", "n_mel", "f_lo", "f_hi", "power", "feature", "n_ceps", "log_floor"]
+    # the field order and the enumerators are the header's
+    hdr = open(os.path.join(ROOT, "include", "aug.h")).read()
+    body = hdr[hdr.index("typedef struct aug_frontend_cfg {"):hdr.index("} aug_frontend_cfg;")]
+    names = re.findall(r"^\s*(?:float|int)\s+(\w+);", body, flags=re.M)
+    assert names == [f[0] for f in binding.FrontendCfg._fields_]
+    for name, value in (("AUG_FEAT_POWER_LAW", "power"), ("AUG_FEAT_LOG", "log"), ("AUG_FEAT_MFCC", "mfcc")):
+        assert int(re.search(name + r"\s*=\s*(\d+)", hdr).group(1)) == binding.FEATURE_KINDS[value]
+
+
+def test_feature_dim_helper(lib):
+    from paper_1912_11040_amd.workloads import FrontendConfig
+    import dataclasses
+    fe = FrontendConfig()
+    assert lib.aug_feature_dim(ctypes.byref(binding.FrontendCfg.of(fe))) == 40
+    assert lib.aug_feature_dim(ctypes.byref(binding.FrontendCfg.of(dataclasses.replace(fe, feature="log")))) == 40
+    assert lib.aug_feature_dim(ctypes.byref(binding.FrontendCfg.of(dataclasses.replace(fe, feature="mfcc")))) == 13
+    assert lib.aug_feature_dim(None) == 0
 
 
 def test_null_context_is_rejected(lib):

@@ -54,6 +54,10 @@ def test_offsets_and_frontend_errors(aug):
     assert _code(aug.aug_vtlp_mel_batch, good, x, alpha, fe256, [0, 3, 5], feats)[0] == binding.AUG_ERR_UNSUPPORTED
     fe_bad = dataclasses.replace(fe, n_mel=0)
     assert _code(aug.aug_vtlp_mel_batch, good, x, alpha, fe_bad, [0, 2, 3], feats)[0] == binding.AUG_ERR_INVALID_ARG
+    fe_kind = dataclasses.replace(fe, feature="mfcc", n_ceps=41)
+    assert _code(aug.aug_vtlp_mel_batch, good, x, alpha, fe_kind, [0, 2, 3], feats)[0] == binding.AUG_ERR_INVALID_ARG
+    fe_floor = dataclasses.replace(fe, feature="log", log_floor=0.0)
+    assert _code(aug.aug_vtlp_mel_batch, good, x, alpha, fe_floor, [0, 2, 3], feats)[0] == binding.AUG_ERR_INVALID_ARG
     # a good call after failures still works
     aug.aug_vtlp_mel_batch(good, x, alpha, fe, [0, 2, 3], feats)
     torch.cuda.synchronize()

@@ -23,7 +23,7 @@ def _run(aug, offsets, wave, alpha, fe=FE):
     n = np.diff(offsets)
     t = np.where(n >= fe.win, 1 + (n - fe.win) // fe.hop, 0)
     foff = np.concatenate([[0], np.cumsum(t)]).astype(np.int64)
-    feats = torch.full((int(foff[-1]), fe.n_mel), float("nan"), dtype=torch.float32, device="cuda")
+    feats = torch.full((int(foff[-1]), fe.feature_dim), float("nan"), dtype=torch.float32, device="cuda")
     aug.aug_vtlp_mel_batch(offsets, dev(wave), dev(alpha), fe, foff, feats)
     torch.cuda.synchronize()
     return feats.cpu().numpy()
@@ -138,6 +138,26 @@ def test_padded_batch_layout(aug):
     with pytest.raises(AugError) as e:
         aug.aug_vtlp_mel_batch(offsets, dev(x), dev(alpha), FE, short, feats)
     assert e.value.code == -1
+
+
+@pytest.mark.parametrize("feature,n_ceps", [("log", 0), ("mfcc", 13), ("mfcc", 40), ("mfcc", 1)])
+def test_log_mel_and_mfcc(aug, feature, n_ceps):
+    # the conventional features that Sec. 2.3 names beside the power law: other epilogues of the same energies
+    import dataclasses
+    fe = dataclasses.replace(FE, feature=feature, n_ceps=n_ceps or 13, log_floor=1e-8)
+    rng = np.random.default_rng(41)
+    lens = [4000, 0, 399, 16000, 560]
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    x = rng.standard_normal(int(offsets[-1])).astype(np.float32)
+    x[offsets[3] + 3000:offsets[3] + 9000] = 0.0            # a silent stretch meets the floor
+    alpha = rng.uniform(0.8, 1.2, len(lens)).astype(np.float32)
+    print(f"case: feature={feature} n_ceps={n_ceps}", flush=True)
+    f = _run(aug, offsets, x, alpha, fe)
+    ref = O.vtlp_mel_batch(offsets, x, alpha, fe)
+    assert f.shape == ref.shape and f.shape[1] == (40 if feature == "log" else n_ceps)
+    err = feat_err(f, ref)
+    print(f"  feature error {err:.2e}", flush=True)
+    assert err <= FEAT_TOL
 
 
 def test_most_mel_channels_the_interface_takes(aug):
