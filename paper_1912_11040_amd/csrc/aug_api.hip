@@ -223,7 +223,7 @@ int run_rir(aug_ctx* ctx, int n_rir, const float* geom, int rir_len, float fs, f
     AUG_HIP(ctx->rir_pow.reserve(sizeof(float) * (size_t)n_rir * aug::rir_pow_entries()), "reflection table");
     const int n_groups = 2 * ctx->n_cu;
     AUG_TRY(mark(ctx, -1));
-    AUG_HIP(aug::launch_rir_plan(ctx->stream, n_rir, geom, rir_len, k, ctx->rir_items.ptr,
+    AUG_HIP(aug::launch_rir_plan(ctx->stream, n_groups, n_rir, geom, rir_len, k, ctx->rir_items.ptr,
                                  ctx->rir_ctrl.as<int>(), ctx->rir_pow.as<float>()), "rir plan kernel");
     AUG_TRY(mark(ctx, AUG_STAGE_OTHER));
     AUG_HIP(aug::launch_rir(ctx->stream, n_groups, n_rir, geom, rir_len, k, ctx->rir_items.ptr,

@@ -84,7 +84,7 @@ int rir_items_per_response(int rir_len);
 size_t rir_item_bytes();
 int rir_ctrl_ints();
 int rir_pow_entries();
-hipError_t launch_rir_plan(hipStream_t s, int n_rir, const float* geom, int rir_len, double fs_over_c,
+hipError_t launch_rir_plan(hipStream_t s, int n_groups, int n_rir, const float* geom, int rir_len, double fs_over_c,
                            void* items, int* ctrl, float* pow_table);
 hipError_t launch_rir(hipStream_t s, int n_groups, int n_rir, const float* geom, int rir_len, double fs_over_c,
                       const void* items, int* ctrl, const float* pow_table, float* rir_out, int32_t* cnt_out);
