@@ -365,14 +365,53 @@ __device__ inline void build_sorted_images(const Axis& ax, int nm, int* s_split,
     __syncthreads();
 }
 
-// number of entries of a sorted table with key <= bound
-__device__ inline int count_not_above(const AxisImage* tab, int n, double bound) {
-    int lo = 0, hi = n;
-    while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (tab[mid].key <= bound) lo = mid + 1; else hi = mid;
+// Position in an axis's sorted table without searching it.  The table holds the images c_q + 2 n L,
+// q in {0,1}, |n| <= nm, ordered by squared distance, so the number of entries within distance s of the
+// microphone is the number of terms of the two arithmetic progressions that lie in [-s, s].
+struct AxisCount {
+    double c0, c1;       // (1 - 2q) src - mic
+    double inv2l;        // 1 / (2 L)
+    double nm;
+};
+
+__device__ inline AxisCount axis_count(const Axis& a, int nm) {
+    return AxisCount{a.src - a.mic, -a.src - a.mic, 1.0 / (2.0 * a.room), (double)nm};
+}
+
+__device__ inline int count_within(const AxisCount& a, double s) {
+    int total = 0;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const double c = q ? a.c1 : a.c0;
+        const double hi = fmin(floor((s - c) * a.inv2l), a.nm);
+        const double lo = fmax(ceil((-s - c) * a.inv2l), -a.nm);
+        total += max((int)hi - (int)lo + 1, 0);
     }
-    return lo;
+    return total;
+}
+
+// sqrt(b) to about 1e-13 relative for b > 0 (fp32 rsq and one fp64 Newton step), 0 for b <= 0
+__device__ inline double quick_sqrt(double b) {
+    if (!(b > 1e-30)) return 0.0;
+    const float bf = (float)b;
+    const float y = __frsqrt_rn(bf);
+    const double s0 = (double)(bf * y);
+    return fma(fma(-s0, s0, b), (double)(0.5f * y), s0);
+}
+
+// The table's keys and these counts round differently, so a bound is widened (or narrowed) by far more
+// than either rounding error before counting.  An entry that close to a bound is then visited although
+// it may lie outside; every visited image is tested against the item's taps anyway.
+// number of entries with key <= bound, or a few more
+__device__ inline int count_not_above(const AxisCount& a, int n, double bound) {
+    if (!(bound >= 0.0)) return 0;
+    const double s = quick_sqrt(bound);
+    return min(count_within(a, s * (1.0 + 1e-9) + 1e-9), n);
+}
+// number of entries with key < bound, or a few fewer
+__device__ inline int count_below(const AxisCount& a, double bound) {
+    const double s = quick_sqrt(bound) * (1.0 - 1e-9) - 1e-9;
+    return s > 0.0 ? count_within(a, s) : 0;
 }
 
 template <bool COUNT>
@@ -430,6 +469,7 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
             nmx = min(nmx, k_cut_item / 2 + 1);          // |n - q| + |n| >= 2 |n| - 1
             nmy = min(nmy, k_cut_item / 2 + 1);
             const int nix = 2 * (2 * nmx + 1), niy = 2 * (2 * nmy + 1), niz = 2 * (2 * nmz + 1);
+            const AxisCount cy = axis_count(ay, nmy), cz = axis_count(az, nmz);
             Column* wc = cols[wave];
             WalkCtx wctx;
             wctx.k_fs_c = k_fs_c;
@@ -465,7 +505,7 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
                     double bound = r_out2 - __dmul_rn(dx, dx);
                     const int ky_max = k_cut_item - (iabs(nx - qx) + iabs(nx));
                     if (ky_max < (1 << 18)) bound = fmin(bound, reach2(y0_max, lyf, ky_max));
-                    row_pfx[ix] = (bound >= 0.0 && ky_max >= 0) ? count_not_above(ytab, niy, bound) : 0;
+                    row_pfx[ix] = (bound >= 0.0 && ky_max >= 0) ? count_not_above(cy, niy, bound) : 0;
                 }
                 __syncthreads();
                 if (wave == 0) {                              // inclusive scan over the rows, 64 at a time
@@ -526,15 +566,8 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
                             double hi2 = r_out2 - col.a;
                             if (kz_max < (1 << 18)) hi2 = fmin(hi2, reach2(z0_max, lzf, kz_max));
                             const double lo2 = r_in2 - col.a;
-                            int first = 0;
-                            if (lo2 > 0.0) {                   // first entry with dz2 >= lo2
-                                int hi = niz;
-                                while (first < hi) {
-                                    const int mid = (first + hi) >> 1;
-                                    if (ztab[mid].key < lo2) first = mid + 1; else hi = mid;
-                                }
-                            }
-                            const int last = count_not_above(ztab, niz, hi2);
+                            const int first = lo2 > 0.0 ? count_below(cz, lo2) : 0;     // entries with dz2 < lo2
+                            const int last = count_not_above(cz, niz, hi2);
                             if (last > first) {
                                 col.start = (unsigned short)first;
                                 col.len = (unsigned short)(last - first);
