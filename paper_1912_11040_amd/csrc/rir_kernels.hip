@@ -303,9 +303,14 @@ __device__ inline void walk_piece_table(const WalkCtx& w, double a, float cxy, c
     }
 }
 
+// beta^k for reflection counts past the LDS table; out of line so that the double-precision pow does not
+// weigh on the register allocation of the loops that call it once in a long while
+__device__ __attribute__((noinline)) float beta_pow_slow(double beta, int k) { return (float)pow(beta, (double)k); }
+
+// (out of line for the same reason: only rooms too flat or narrow for the tables come here)
 template <bool COUNT>
-__device__ inline void walk_column_direct(const WalkCtx& w, const Axis& az, double a, float cxy, int nmz,
-                                          unsigned long long* hist, unsigned int* hist32) {
+__device__ __attribute__((noinline)) void walk_column_direct(const WalkCtx w, const Axis az, double a, float cxy, int nmz,
+                                                             unsigned long long* hist, unsigned int* hist32) {
     for (int q = 0; q < 2; ++q)
         for (int n = -nmz; n <= nmz; ++n) {
             const double dz = axis_delta(az, q, n);
@@ -313,7 +318,7 @@ __device__ inline void walk_column_direct(const WalkCtx& w, const Axis& az, doub
             float y;
             const int idx = tap_index(w, d2, y);
             float bz = 0.f;
-            if (!COUNT) bz = (float)pow(w.beta, (double)(iabs(n - q) + iabs(n)));
+            if (!COUNT) bz = beta_pow_slow(w.beta, iabs(n - q) + iabs(n));
             deposit<COUNT>(w, idx, (bz * y) * cxy, hist, hist32);
         }
 }
@@ -494,7 +499,7 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
                 build_sorted_images(az, nmz, s_split, ztab, tid, [&](int q, int n) {
                     if (COUNT) return 0;
                     const int k = iabs(n - q) + iabs(n);
-                    return __float_as_int(k < kPow ? bpow[k] : (float)pow(beta, (double)k));
+                    return __float_as_int(k < kPow ? bpow[k] : beta_pow_slow(beta, k));
                 });
                 build_sorted_images(ay, nmy, s_split, ytab, tid, [&](int q, int n) { return iabs(n - q) + iabs(n); });
                 // live columns of x image ix: the y images with dy^2 <= r_out^2 - dx^2 that the reflection
@@ -595,7 +600,7 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
                     const int local = p - (slot ? wc[slot - 1].pfx : 0);
                     float cxy = 0.f;       // beta^kxy / (4 pi) * 2^24
                     if (!COUNT)
-                        cxy = (c.kxy < kPow ? bpow[c.kxy] : (float)pow(beta, (double)c.kxy)) * (0.07957747154594767f * 16777216.0f);
+                        cxy = (c.kxy < kPow ? bpow[c.kxy] : beta_pow_slow(beta, c.kxy)) * (0.07957747154594767f * 16777216.0f);
                     if (fast) {
                         const int first = (int)c.start + local * kPiece;
                         const int len = min(kPiece, (int)c.len - local * kPiece);
