@@ -36,9 +36,9 @@ RIR_FLOP_PER_IMAGE = 12.0     # 2 add, sqrt, mul, add, floor, table product, div
 # runs summarised in profiles/hbm_traffic_<workload>.md, scaled there by a 1 GiB copy.  They describe the
 # kernel sources with this digest only; for any other sources `traffic` is reported as null.
 RECORDED_TRAFFIC = {
-    "digest": "6975f231724c907a",
-    "varlen": {"rir": 202162550, "rir_spectrum": 202036528, "convolve": 1265304597, "mel": 627050920},
-    "throughput": {"rir": 999883947, "rir_spectrum": 1220223839, "convolve": 5830156255, "mel": 2221163147},
+    "digest": "e458ac480fd88e92",
+    "varlen": {"rir": 110854190, "rir_spectrum": 202025848, "convolve": 1268548110, "mel": 627038137},
+    "throughput": {"rir": 577701457, "rir_spectrum": 1220177770, "convolve": 5807745351, "mel": 2221330309},
 }
 
 
