@@ -74,6 +74,20 @@ def test_longest_response_the_interface_takes(aug):
     _check(aug, w.geom, 32768)
 
 
+def test_unusable_rooms_give_silence_and_leave_the_rest_alone(aug):
+    # the library's guard against an unbounded image lattice: a side under 10 cm or not a number
+    w = W.tiny(n_utt=2)
+    geom = np.asarray(w.geom, np.float32).reshape(-1, 10).copy()
+    good = geom.copy()
+    geom[1, 0] = 0.05
+    geom[2, 1] = np.nan
+    h, cnt = _run(aug, geom, 1500)
+    assert np.all(h[1] == 0.0) and np.all(cnt[1] == 0) and np.all(h[2] == 0.0) and np.all(cnt[2] == 0)
+    h_ref, cnt_ref = O.rir_batch(good[[0, 3]], 1500, FS, C)
+    np.testing.assert_array_equal(cnt[[0, 3]], cnt_ref)
+    assert rir_err(h[[0, 3]], h_ref) <= RIR_TOL
+
+
 def test_zero_reflection_closed_form(aug):
     g = np.array([[5, 4, 3, 1.0, 1.5, 1.2, 3.5, 2.0, 1.7, 0.0]], np.float32)
     h, _ = _run(aug, g, 2048)
