@@ -8,8 +8,10 @@
 // falls between band edges c and c+1 feeds only filter c (rising side, weight w) and
 // filter c-1 (falling side, weight 1-w).  A small kernel writes (c, w) per bin and
 // utterance; the main kernel runs each K-point real transform as a K/2-point complex
-// FFT in LDS (16 lanes per frame, two radix-16 passes), then scatters the power of
-// each bin into its two mel channels.
+// FFT in LDS (16 lanes per frame, two radix-16 passes).  The bins are cut into 16 contiguous ranges that
+// end where the band changes, one per lane, so a lane owns every band sum it forms (no atomics); channel m
+// is the rising side of band m plus the falling side of band m + 1.  Other epilogues of the same
+// energies (log-mel, MFCC) and the on-the-fly mixture of reverberated sources are options of the kernel.
 
 #include "aug_internal.h"
 #include "fft_lds.h"

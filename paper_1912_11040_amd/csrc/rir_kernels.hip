@@ -15,13 +15,15 @@
 //
 // Layout of the work
 //   * plan kernels: one thread per response cuts its taps into shells [n0, n1) of about
-//     equal image count (equal volume of the spherical shell) and at most kMaxTaps taps, with an
-//     estimate of each shell's work; a counting sort orders the items heaviest first.
+//     equal image count (equal volume of the spherical shell) and at most kMaxTaps taps; the shell size
+//     follows the batch's estimated work per persistent group.  Every shell gets an estimate of its work
+//     and a counting sort orders the items heaviest first.
 //   * image kernel: persistent work groups fetch items from a counter.  An item owns its
 //     taps, so sums live in LDS and are stored once, without global atomics.
 //     The z images of the response (both q, both signs) are merged into one LDS table sorted by
 //     dz*dz, so the images of an (x image, y image) column that can fall inside the shell are one
-//     contiguous range of that table, found by two binary searches on r_in^2 - a and r_out^2 - a.
+//     contiguous range of that table between r_in^2 - a and r_out^2 - a, whose ends are counted from the
+//     two arithmetic progressions that the axis's images form rather than searched for.
 //     The y images are sorted the same way, so the live columns of an x image are a prefix of the
 //     y table; a prefix sum over the x images numbers the live columns and dead ones are never seen.
 //     A wave takes 64 live columns at a time; their z ranges are cut into pieces of at most kPiece
