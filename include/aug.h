@@ -122,6 +122,10 @@ int aug_rir_batch(aug_ctx* ctx, int n_rir, const float* geom, int rir_len,
  *               length kept, the tail past the end is dropped),
  *               E_j = sum_n y_j[n]^2,  g_j = sqrt(E_0 / (E_j 10^(snr_j/10)))
  *               (0 if E_0 or E_j is 0),  mixed = y_0 + sum_j g_j y_j.
+ *               An energy counts as 0 when it is below 1e-10 of (energy of
+ *               x_j) * (energy of h_j): where the exact y_j is zero (the
+ *               utterance ends before the response's first tap) the transforms
+ *               leave rounding noise, not a signal.
  *   gains_out   DEVICE float [n_utt][n_noise] or NULL: the g_j.
  */
 int aug_convolve_mix_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets,

@@ -261,12 +261,15 @@ int run_convolve_mix(aug_ctx* ctx, int n_utt, int n_noise, const float* speech, 
     const int64_t stride = reverb_stride(total);
     AUG_HIP(ctx->reverb.reserve(sizeof(float) * (size_t)n_src * stride), "reverberation workspace");
     AUG_HIP(ctx->gains.reserve(sizeof(float) * (size_t)std::max(1, n_utt * n_noise)), "gain workspace");
-    AUG_HIP(ctx->energy.reserve(sizeof(double) * (size_t)n_utt * n_src), "energy workspace");
+    AUG_HIP(ctx->energy.reserve(sizeof(double) * 3 * (size_t)n_utt * n_src), "energy workspace");
+    double* const energy = ctx->energy.as<double>();
+    double* const energy_in = energy + (size_t)n_utt * n_src;
+    double* const h2 = energy_in + (size_t)n_utt * n_src;
 
     AUG_TRY(mark(ctx, -1));
-    AUG_HIP(aug::launch_fill_u32(ctx->stream, ctx->energy.ptr, 0u, (int64_t)n_utt * n_src * 2), "energy clear");
+    AUG_HIP(aug::launch_fill_u32(ctx->stream, energy, 0u, (int64_t)n_utt * n_src * 6), "energy clear");
     AUG_TRY(mark(ctx, AUG_STAGE_OTHER));
-    AUG_HIP(aug::launch_rir_spectrum(ctx->stream, n_utt * n_src, rir, rir_len, fft_n, tw, ctx->rir_spec.as<float2>()),
+    AUG_HIP(aug::launch_rir_spectrum(ctx->stream, n_utt * n_src, rir, rir_len, fft_n, tw, ctx->rir_spec.as<float2>(), h2),
             "spectrum kernel");
     AUG_TRY(mark(ctx, AUG_STAGE_RIR_SPECTRUM));
     aug::ConvArgs ca;
@@ -281,10 +284,11 @@ int run_convolve_mix(aug_ctx* ctx, int n_utt, int n_noise, const float* speech, 
     ca.n_part = n_part;
     ca.reverb = ctx->reverb.as<float>();
     ca.reverb_stride = stride;
-    ca.energy = ctx->energy.as<double>();
+    ca.energy = energy;
+    ca.energy_in = energy_in;
     AUG_HIP(aug::launch_convolve(ctx->stream, fft_n, tw, ca), "convolution kernel");
     AUG_TRY(mark(ctx, AUG_STAGE_CONVOLVE));
-    AUG_HIP(aug::launch_gains(ctx->stream, n_utt, n_src, ctx->energy.as<double>(), snr_db, ctx->gains.as<float>(),
+    AUG_HIP(aug::launch_gains(ctx->stream, n_utt, n_src, energy, energy_in, h2, snr_db, ctx->gains.as<float>(),
                               gains_out), "gain kernel");
     if (mixed_out)
         AUG_HIP(aug::launch_mix(ctx->stream, n_utt, ctx->d_offsets.as<int64_t>(), stride, n_src, ctx->reverb.as<float>(),

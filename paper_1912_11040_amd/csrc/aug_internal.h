@@ -56,7 +56,7 @@ struct aug_ctx {
     aug::DeviceBuffer rir;               // float [n_rir][rir_len]            (pipeline only)
     aug::DeviceBuffer rir_spec;          // float2 [n_rir][n_part][P+1]
     aug::DeviceBuffer reverb;            // float [1+n_noise][total rounded up to even]
-    aug::DeviceBuffer energy;            // double [n_utt][1+n_noise]
+    aug::DeviceBuffer energy;            // double [3][n_utt][1+n_noise]: reverberated signals, inputs, responses
     aug::DeviceBuffer gains;             // float [n_utt][n_noise]
     aug::DeviceBuffer mel_tab;           // float2 [n_utt][nfft/2+1]: (channel, weight) per bin
     aug::DeviceBuffer twiddle[16];       // per log2(n): float2 [n + n/2 + 1] FFT twiddles
@@ -92,9 +92,10 @@ hipError_t launch_rir(hipStream_t s, int n_groups, int n_rir, const float* geom,
 // Largest complex FFT size the convolution kernels are built for, and the size chosen for a response length.
 int conv_fft_size(int rir_len);
 
-// Spectra of the zero-padded partitions of each response: spec float2 [n_rir][n_part][P+1], P = fft_n.
+// Spectra of the zero-padded partitions of each response: spec float2 [n_rir][n_part][P+1], P = fft_n;
+// the sum of every response's squared taps is added to h2[n_rir] (zero on entry).
 hipError_t launch_rir_spectrum(hipStream_t s, int n_rir, const float* rir, int rir_len, int fft_n,
-                               const float2* twiddle, float2* spec);
+                               const float2* twiddle, float2* spec, double* h2);
 
 // Overlap-save convolution of every (utterance, source) with its response; adds the block's energy
 // to energy[u][j] (double, must be zero on entry).  src_base[j] points at source j's packed signal.
@@ -110,13 +111,15 @@ struct ConvArgs {
     int n_part;
     float* reverb;               // [n_src][reverb_stride]
     int64_t reverb_stride;
-    double* energy;              // [n_utt][n_src]
+    double* energy;              // [n_utt][n_src] of the reverberated signals
+    double* energy_in;           // [n_utt][n_src] of the inputs
 };
 hipError_t launch_convolve(hipStream_t s, int fft_n, const float2* twiddle, const ConvArgs& a);
 
 // gains [n_utt][n_src - 1] from the energies and the target SNRs (also copied to gains_out when given)
-hipError_t launch_gains(hipStream_t s, int n_utt, int n_src, const double* energy, const float* snr_db,
-                        float* gains, float* gains_out);
+// energy, energy_in, h2: [n_utt][n_src] energies of the reverberated signals, of the inputs and of the responses
+hipError_t launch_gains(hipStream_t s, int n_utt, int n_src, const double* energy, const double* energy_in,
+                        const double* h2, const float* snr_db, float* gains, float* gains_out);
 // mixed = reverb[0] + sum_j gains[j - 1] reverb[j]; source j of the reverberated signals starts at j * stride
 hipError_t launch_mix(hipStream_t s, int n_utt, const int64_t* d_offsets, int64_t stride, int n_src,
                       const float* reverb, const float* gains, float* mixed_out, int64_t max_len);

@@ -112,6 +112,8 @@ class Workload:
 # --------------------------------------------------------------------------
 
 def _unit_rms(x: np.ndarray) -> np.ndarray:
+    if x.size == 0:
+        return x
     r = np.sqrt(np.mean(np.square(x, dtype=np.float64)))
     return x / r if r > 0 else x
 
@@ -143,6 +145,8 @@ def white_noise(rng: np.random.Generator, n: int, fs: float = FS) -> np.ndarray:
 def pink_noise(rng: np.random.Generator, n: int, fs: float = FS) -> np.ndarray:
     """White noise whose spectrum is scaled by 1/sqrt(max(f, 20 Hz)); unit RMS."""
     u = rng.standard_normal(n)
+    if n == 0:
+        return u.astype(np.float32)
     spec = np.fft.rfft(u)
     f = np.fft.rfftfreq(n, d=1.0 / fs)
     spec /= np.sqrt(np.maximum(f, 20.0))

@@ -7,14 +7,21 @@ RIR_TOL = 1e-5       # relative error of summed tap amplitudes
 GAIN_TOL = 1e-4      # relative error of SNR gains
 
 
-def wave_err(got, ref, offsets):
-    """Largest per-utterance max|got - ref| / RMS(ref)."""
+def wave_err(got, ref, offsets, silent_scale=None):
+    """Largest per-utterance max|got - ref| / RMS(ref).
+
+    An utterance whose reference is identically zero (it ends before the direct path arrives) has no RMS
+    to scale by; with `silent_scale` (the signal that was convolved) the RMS of that utterance's input is
+    the scale instead, since a transform-based convolution leaves rounding noise where the exact result is 0.
+    """
     worst = 0.0
     for u in range(len(offsets) - 1):
         a, b = int(offsets[u]), int(offsets[u + 1])
         if b == a:
             continue
         rms = np.sqrt(np.mean(ref[a:b] ** 2))
+        if rms == 0 and silent_scale is not None:
+            rms = np.sqrt(np.mean(np.asarray(silent_scale[a:b], np.float64) ** 2))
         err = np.max(np.abs(got[a:b].astype(np.float64) - ref[a:b]))
         worst = max(worst, err / rms if rms > 0 else (0.0 if err == 0 else np.inf))
     return worst

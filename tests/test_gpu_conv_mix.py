@@ -144,6 +144,28 @@ def test_silent_noise_gets_zero_gain(aug):
     assert wave_err(mixed, ref, offsets) <= WAVE_TOL
 
 
+def test_noise_that_never_arrives_gets_zero_gain(aug):
+    # The noise's response starts after the utterance has ended, so its reverberated signal is exactly zero
+    # and the rule "zero energy gives gain 0" applies; a transform-based convolution returns rounding noise
+    # there, which must not be mistaken for a signal (its gain would be astronomical).
+    rng = np.random.default_rng(17)
+    lens = [1500, 900]
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    total = int(offsets[-1])
+    speech = rng.standard_normal(total).astype(np.float32)
+    noise = rng.standard_normal((2, total)).astype(np.float32)
+    rir = _decaying_rirs(rng, 2, 3, 4000)
+    rir[0, 1, :1500] = 0.0          # utterance 0, noise 0: first tap at 1500 = its length
+    rir[1, 0, :900] = 0.0           # utterance 1: the speech itself never arrives
+    snr = np.full((2, 2), 5.0, np.float32)
+    mixed, gains = _run(aug, offsets, speech, noise, rir, snr)
+    ref, g_ref = O.convolve_mix_batch(offsets, speech, noise, rir.astype(np.float64), snr)
+    assert g_ref[0, 0] == 0.0 and g_ref[0, 1] > 0.0 and np.all(g_ref[1] == 0.0)
+    assert gains[0, 0] == 0.0 and np.all(gains[1] == 0.0)
+    np.testing.assert_allclose(gains[0, 1], g_ref[0, 1], rtol=GAIN_TOL)
+    assert wave_err(mixed, ref, offsets, silent_scale=speech) <= WAVE_TOL
+
+
 def test_measured_snr_equals_target(aug):
     rng = np.random.default_rng(5)
     offsets = np.array([0, 30000], np.int64)
