@@ -125,7 +125,8 @@ int aug_rir_batch(aug_ctx* ctx, int n_rir, const float* geom, int rir_len,
  *               An energy counts as 0 when it is below 1e-10 of (energy of
  *               x_j) * (energy of h_j): where the exact y_j is zero (the
  *               utterance ends before the response's first tap) the transforms
- *               leave rounding noise, not a signal.
+ *               leave rounding noise, not a signal.  Samples before the
+ *               first non-zero tap of h_j are written as exact zeros.
  *   gains_out   DEVICE float [n_utt][n_noise] or NULL: the g_j.
  */
 int aug_convolve_mix_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets,

@@ -267,9 +267,12 @@ int run_convolve_mix(aug_ctx* ctx, int n_utt, int n_noise, const float* speech, 
     double* const h2 = energy_in + (size_t)n_utt * n_src;
 
     AUG_TRY(mark(ctx, -1));
+    AUG_HIP(ctx->first_tap.reserve(sizeof(int) * (size_t)n_utt * n_src), "first-tap workspace");
     AUG_HIP(aug::launch_fill_u32(ctx->stream, energy, 0u, (int64_t)n_utt * n_src * 6), "energy clear");
+    AUG_HIP(aug::launch_fill_u32(ctx->stream, ctx->first_tap.ptr, 0x7fffffffu, (int64_t)n_utt * n_src), "first-tap reset");
     AUG_TRY(mark(ctx, AUG_STAGE_OTHER));
-    AUG_HIP(aug::launch_rir_spectrum(ctx->stream, n_utt * n_src, rir, rir_len, fft_n, tw, ctx->rir_spec.as<float2>(), h2),
+    AUG_HIP(aug::launch_rir_spectrum(ctx->stream, n_utt * n_src, rir, rir_len, fft_n, tw, ctx->rir_spec.as<float2>(), h2,
+                                     ctx->first_tap.as<int>()),
             "spectrum kernel");
     AUG_TRY(mark(ctx, AUG_STAGE_RIR_SPECTRUM));
     aug::ConvArgs ca;
@@ -286,6 +289,7 @@ int run_convolve_mix(aug_ctx* ctx, int n_utt, int n_noise, const float* speech, 
     ca.reverb_stride = stride;
     ca.energy = energy;
     ca.energy_in = energy_in;
+    ca.first_tap = ctx->first_tap.as<int>();
     AUG_HIP(aug::launch_convolve(ctx->stream, fft_n, tw, ca), "convolution kernel");
     AUG_TRY(mark(ctx, AUG_STAGE_CONVOLVE));
     AUG_HIP(aug::launch_gains(ctx->stream, n_utt, n_src, energy, energy_in, h2, snr_db, ctx->gains.as<float>(),
@@ -407,7 +411,7 @@ int aug_destroy(aug_ctx* ctx) {
         rc = AUG_ERR_HIP;
     }
     DeviceBuffer* bufs[] = {&ctx->d_offsets, &ctx->d_frame_offsets, &ctx->d_conv_items, &ctx->d_frame_items,
-                            &ctx->rir_items, &ctx->rir_ctrl, &ctx->rir_pow, &ctx->rir, &ctx->rir_spec, &ctx->reverb, &ctx->energy, &ctx->gains, &ctx->vtlp_tab, &ctx->dct, &ctx->mel_tab,
+                            &ctx->rir_items, &ctx->rir_ctrl, &ctx->rir_pow, &ctx->rir, &ctx->rir_spec, &ctx->reverb, &ctx->energy, &ctx->gains, &ctx->first_tap, &ctx->vtlp_tab, &ctx->dct, &ctx->mel_tab,
                             &ctx->window};
     for (DeviceBuffer* b : bufs) b->release();
     for (DeviceBuffer& b : ctx->twiddle) b.release();

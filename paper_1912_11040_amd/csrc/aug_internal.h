@@ -58,6 +58,7 @@ struct aug_ctx {
     aug::DeviceBuffer reverb;            // float [1+n_noise][total rounded up to even]
     aug::DeviceBuffer energy;            // double [3][n_utt][1+n_noise]: reverberated signals, inputs, responses
     aug::DeviceBuffer gains;             // float [n_utt][n_noise]
+    aug::DeviceBuffer first_tap;         // int [n_utt][1+n_noise]
     aug::DeviceBuffer mel_tab;           // float2 [n_utt][nfft/2+1]: (channel, weight) per bin
     aug::DeviceBuffer twiddle[16];       // per log2(n): float2 [n + n/2 + 1] FFT twiddles
     aug::DeviceBuffer window;            // float [win]
@@ -93,9 +94,10 @@ hipError_t launch_rir(hipStream_t s, int n_groups, int n_rir, const float* geom,
 int conv_fft_size(int rir_len);
 
 // Spectra of the zero-padded partitions of each response: spec float2 [n_rir][n_part][P+1], P = fft_n;
-// the sum of every response's squared taps is added to h2[n_rir] (zero on entry).
+// the sum of every response's squared taps is added to h2[n_rir] (zero on entry) and the index of its first
+// non-zero tap is taken into first_tap[n_rir] (INT_MAX on entry).
 hipError_t launch_rir_spectrum(hipStream_t s, int n_rir, const float* rir, int rir_len, int fft_n,
-                               const float2* twiddle, float2* spec, double* h2);
+                               const float2* twiddle, float2* spec, double* h2, int* first_tap);
 
 // Overlap-save convolution of every (utterance, source) with its response; adds the block's energy
 // to energy[u][j] (double, must be zero on entry).  src_base[j] points at source j's packed signal.
@@ -113,6 +115,7 @@ struct ConvArgs {
     int64_t reverb_stride;
     double* energy;              // [n_utt][n_src] of the reverberated signals
     double* energy_in;           // [n_utt][n_src] of the inputs
+    const int* first_tap;        // [n_utt][n_src] first non-zero tap of each response
 };
 hipError_t launch_convolve(hipStream_t s, int fft_n, const float2* twiddle, const ConvArgs& a);
 

@@ -71,7 +71,7 @@ template <int N> __device__ inline float2 pair_twiddle(const float2* __restrict_
 template <int N, int T>
 __global__ __launch_bounds__(T) void rir_spectrum_kernel(
     const float* __restrict__ rir, int rir_len, int n_part, const float2* __restrict__ tw,
-    float2* __restrict__ spec, double* __restrict__ h2) {
+    float2* __restrict__ spec, double* __restrict__ h2, int* __restrict__ first_tap) {
     extern __shared__ float2 buf[];
     __shared__ double red[T / 64];
     constexpr int M = N / 16;
@@ -79,8 +79,9 @@ __global__ __launch_bounds__(T) void rir_spectrum_kernel(
     const int r = blockIdx.x / n_part, p = blockIdx.x % n_part;
     const float* h = rir + (size_t)r * rir_len;
     float2 v[16];
+    int first = 0x7fffffff;                          // index of this thread's first non-zero tap
 #pragma unroll
-    for (int n1 = 0; n1 < 16; ++n1) {
+    for (int n1 = 15; n1 >= 0; --n1) {
         const int n = tid + M * n1;
         const int t = p * N + 2 * n;                 // taps of this partition: [pN, (p+1)N), then N zeros
         float a = 0.f, b = 0.f;
@@ -89,7 +90,12 @@ __global__ __launch_bounds__(T) void rir_spectrum_kernel(
             if (t + 1 < rir_len) b = h[t + 1];
         }
         v[n1] = make_float2(a, b);
+        if (b != 0.f) first = t + 1;
+        if (a != 0.f) first = t;
     }
+    // the response is zero before its first non-zero tap, and so is everything convolved with it
+    for (int off = 32; off > 0; off >>= 1) first = min(first, __shfl_down(first, off, 64));
+    if ((tid & 63) == 0 && first != 0x7fffffff) atomicMin(&first_tap[r], first);
     // the partition's share of the response's energy, sum of squared taps (h2 must be zero on entry)
     double e = 0.0;
 #pragma unroll
@@ -160,6 +166,7 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
     const int len = (int)(a.offsets[u + 1] - start);      // utterances are shorter than 2^30 samples (checked on the host)
     const float* x = (j == 0 ? a.speech : a.noise + (size_t)(j - 1) * a.total) + start;
     const float2* H = a.spec + ((size_t)u * a.n_src + j) * a.n_part * (size_t)(N + 1);
+    const int first = a.first_tap[(size_t)u * a.n_src + j];   // first non-zero tap of the response
 
     // Responses longer than N taps: every partition p convolves the window p blocks back with its own
     // spectrum and the N output samples are summed in registers (eight complex values per thread), which
@@ -223,13 +230,16 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
 
     // the last N real samples of the 2N-sample window are this block's outputs: n = tid + M n1 >= N/2
     float* y = a.reverb + (size_t)j * a.reverb_stride + start;
+    // Before the response's first non-zero tap the exact result is zero; the transforms leave rounding noise
+    // there, which the power law of the front end would turn into a visible feature value.
     const int out0 = b * N + 2 * tid;
     float e = 0.f;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int g = out0 + 2 * M * i;
-        if (g < len) { y[g] = out[i].x; e += out[i].x * out[i].x; }
-        if (g + 1 < len) { y[g + 1] = out[i].y; e += out[i].y * out[i].y; }
+        const float s0 = g >= first ? out[i].x : 0.f, s1 = g + 1 >= first ? out[i].y : 0.f;
+        if (g < len) { y[g] = s0; e += s0 * s0; }
+        if (g + 1 < len) { y[g + 1] = s1; e += s1 * s1; }
     }
     double es = (double)e, es_in = (double)e_in;
     for (int off = 32; off > 0; off >>= 1) {
@@ -298,7 +308,7 @@ __global__ __launch_bounds__(256) void mix_kernel(
 
 template <int N>
 hipError_t spectrum_n(hipStream_t s, int n_rir, const float* rir, int rir_len, const float2* tw,
-                      float2* spec, double* h2) {
+                      float2* spec, double* h2, int* first_tap) {
     constexpr int T = conv_threads(N);
     const int n_part = (rir_len + N - 1) / N;
     const size_t lds = sizeof(float2) * lds_padded_size(N);
@@ -306,7 +316,7 @@ hipError_t spectrum_n(hipStream_t s, int n_rir, const float* rir, int rir_len, c
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    k<<<dim3((unsigned)(n_rir * n_part)), dim3(T), lds, s>>>(rir, rir_len, n_part, tw, spec, h2);
+    k<<<dim3((unsigned)(n_rir * n_part)), dim3(T), lds, s>>>(rir, rir_len, n_part, tw, spec, h2, first_tap);
     return hipGetLastError();
 }
 
@@ -350,9 +360,9 @@ hipError_t launch_twiddle(hipStream_t s, int n, float2* tw) {
     }
 
 hipError_t launch_rir_spectrum(hipStream_t s, int n_rir, const float* rir, int rir_len, int fft_n,
-                               const float2* twiddle, float2* spec, double* h2) {
+                               const float2* twiddle, float2* spec, double* h2, int* first_tap) {
     if (n_rir <= 0) return hipSuccess;
-#define CALL(NN) spectrum_n<NN>(s, n_rir, rir, rir_len, twiddle, spec, h2)
+#define CALL(NN) spectrum_n<NN>(s, n_rir, rir, rir_len, twiddle, spec, h2, first_tap)
     AUG_FFT_DISPATCH(fft_n, CALL)
 #undef CALL
 }

@@ -215,6 +215,26 @@ def test_many_short_utterances(aug):
     assert int(np.sum(w.lengths() == 0)) >= 0 and int(np.sum(w.lengths() < 400)) > 50
 
 
+def test_frames_before_any_sound_arrives(aug):
+    # every source is more than 400 samples of travel away from the microphone, so the first analysis frame
+    # of the mixture is exactly zero and its features must be zero, not the power law of rounding noise
+    import dataclasses
+    w = W.tiny(n_utt=2)
+    geom = np.array(w.geom, np.float32)
+    geom[:, :, 0:3] = [10.0, 8.0, 4.0]
+    geom[:, 0, 3:6] = [0.6, 0.7, 0.5]
+    geom[:, 1, 3:6] = [0.5, 7.4, 3.4]
+    geom[:, :, 6:9] = [9.4, 4.0, 2.0]
+    w = dataclasses.replace(w, geom=geom)
+    ref = _oracle(w)
+    foff = w.frame_offsets()
+    assert np.all(ref["feats"][foff[0]] == 0.0) and np.all(ref["mixed"][:440] == 0.0)
+    got = _run(aug, w)
+    _compare(got, ref, w)
+    _compare_unmaterialised(aug, w, ref)
+    assert np.all(got["mixed"][:440] == 0.0) and np.all(got["feats"][foff[0]] == 0.0)
+
+
 def test_no_noise_pipeline(aug):
     import dataclasses
     w = W.tiny(n_utt=2)
