@@ -84,9 +84,10 @@ int64_t aug_frame_count(int64_t n_samples, int win, int hop);
  *                  microphone x,y,z, wall reflection coefficient beta.  The box
  *                  is [0,Lx]x[0,Ly]x[0,Lz]; source and microphone must lie
  *                  inside it and not coincide (not checked on the device).
- *                  A room with a side under 0.1 m, or a side that is not a
- *                  number, yields an all-zero response (and zero counts)
- *                  instead of an unbounded image lattice.
+ *                  beta must lie in [0, 1].  A room with a side under 0.1 m, a
+ *                  beta outside [0, 1], or either not a number, yields an
+ *                  all-zero response (and zero counts) instead of an unbounded
+ *                  image lattice or an overflowing sum.
  *   rir_len        taps per response, 1..AUG_MAX_RIR_LEN.
  *   fs, c          sample rate (Hz) and speed of sound (m/s), both > 0.
  *   rir_out        DEVICE float [n_rir][rir_len], overwritten:

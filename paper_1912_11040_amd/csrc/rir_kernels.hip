@@ -71,8 +71,12 @@ __device__ inline double axis_delta(const Axis& a, int q, int n) {
 
 __device__ inline int iabs(int v) { return v < 0 ? -v : v; }
 
+// A usable room has sides of at least 10 cm (else the image lattice is unbounded) and a reflection
+// coefficient in [0, 1] (amplitudes are summed as unsigned fixed point and must not grow with the
+// reflection count); the comparisons are false for values that are not numbers.
 __device__ inline bool room_ok(const float* g) {
-    return (g[0] >= 0.1f) && (g[1] >= 0.1f) && (g[2] >= 0.1f) && (g[0] * g[1] * g[2] < 1e30f);
+    return (g[0] >= 0.1f) && (g[1] >= 0.1f) && (g[2] >= 0.1f) && (g[0] * g[1] * g[2] < 1e30f) &&
+           (g[9] >= 0.f) && (g[9] <= 1.f);
 }
 
 struct Item { int rir, n0, n1, cls; };

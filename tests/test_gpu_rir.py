@@ -82,6 +82,11 @@ def test_unusable_rooms_give_silence_and_leave_the_rest_alone(aug):
     geom[1, 0] = 0.05
     geom[2, 1] = np.nan
     h, cnt = _run(aug, geom, 1500)
+    for bad_beta in (-0.5, 1.5, np.nan):
+        g2 = good.copy()
+        g2[1, 9] = bad_beta
+        h2, cnt2 = _run(aug, g2, 700)
+        assert np.all(h2[1] == 0.0) and np.all(cnt2[1] == 0) and np.any(h2[0] != 0.0)
     assert np.all(h[1] == 0.0) and np.all(cnt[1] == 0) and np.all(h[2] == 0.0) and np.all(cnt[2] == 0)
     h_ref, cnt_ref = O.rir_batch(good[[0, 3]], 1500, FS, C)
     np.testing.assert_array_equal(cnt[[0, 3]], cnt_ref)
