@@ -227,11 +227,11 @@ int run_rir(aug_ctx* ctx, int n_rir, const float* geom, int rir_len, float fs, f
                                  ctx->rir_ctrl.as<int>(), ctx->rir_pow.as<float>()), "rir plan kernel");
     AUG_TRY(mark(ctx, AUG_STAGE_OTHER));
     AUG_HIP(aug::launch_rir(ctx->stream, n_groups, n_rir, geom, rir_len, k, ctx->rir_items.ptr,
-                            ctx->rir_ctrl.as<int>(), ctx->rir_pow.as<float>(), rir_out, nullptr), "rir kernel");
+                            ctx->rir_ctrl.as<int>(), ctx->rir_pow.as<float>(), rir_out, nullptr, false), "rir kernel");
     AUG_TRY(mark(ctx, AUG_STAGE_RIR));
     if (tap_count_out) {
         AUG_HIP(aug::launch_rir(ctx->stream, n_groups, n_rir, geom, rir_len, k, ctx->rir_items.ptr,
-                                ctx->rir_ctrl.as<int>(), ctx->rir_pow.as<float>(), nullptr, tap_count_out),
+                                ctx->rir_ctrl.as<int>(), ctx->rir_pow.as<float>(), nullptr, tap_count_out, true),
                 "rir count kernel");
         AUG_TRY(mark(ctx, AUG_STAGE_OTHER));
     }
@@ -268,8 +268,8 @@ int run_convolve_mix(aug_ctx* ctx, int n_utt, int n_noise, const float* speech, 
 
     AUG_TRY(mark(ctx, -1));
     AUG_HIP(ctx->first_tap.reserve(sizeof(int) * (size_t)n_utt * n_src), "first-tap workspace");
-    AUG_HIP(aug::launch_fill_u32(ctx->stream, energy, 0u, (int64_t)n_utt * n_src * 6), "energy clear");
-    AUG_HIP(aug::launch_fill_u32(ctx->stream, ctx->first_tap.ptr, 0x7fffffffu, (int64_t)n_utt * n_src), "first-tap reset");
+    AUG_HIP(aug::launch_fill2_u32(ctx->stream, energy, 0u, (int64_t)n_utt * n_src * 6, ctx->first_tap.ptr, 0x7fffffffu,
+                                  (int64_t)n_utt * n_src), "energy and first-tap reset");
     AUG_TRY(mark(ctx, AUG_STAGE_OTHER));
     AUG_HIP(aug::launch_rir_spectrum(ctx->stream, n_utt * n_src, rir, rir_len, fft_n, tw, ctx->rir_spec.as<float2>(), h2,
                                      ctx->first_tap.as<int>()),

@@ -79,7 +79,8 @@ namespace aug {
 // Image-method impulse responses.  launch_rir_plan cuts every response into items (tap ranges of
 // about equal image count) ordered heaviest first, fills the beta^k tables and resets ctrl (item count,
 // next item, class counters: rir_ctrl_ints() ints); `items` needs room for 2 n_rir rir_items_per_response items;
-// launch_rir then runs n_groups persistent work groups over the items, writing either
+// launch_rir then runs n_groups persistent work groups over the items (restart: once more over the
+// same plan), writing either
 // rir_out float [n_rir][rir_len] or, if rir_out is null, tap counts cnt_out int32 [n_rir][rir_len].
 int rir_items_per_response(int rir_len);
 size_t rir_item_bytes();
@@ -88,7 +89,8 @@ int rir_pow_entries();
 hipError_t launch_rir_plan(hipStream_t s, int n_groups, int n_rir, const float* geom, int rir_len, double fs_over_c,
                            void* items, int* ctrl, float* pow_table);
 hipError_t launch_rir(hipStream_t s, int n_groups, int n_rir, const float* geom, int rir_len, double fs_over_c,
-                      const void* items, int* ctrl, const float* pow_table, float* rir_out, int32_t* cnt_out);
+                      const void* items, int* ctrl, const float* pow_table, float* rir_out, int32_t* cnt_out,
+                      bool restart);
 
 // Largest complex FFT size the convolution kernels are built for, and the size chosen for a response length.
 int conv_fft_size(int rir_len);
@@ -178,5 +180,7 @@ hipError_t launch_vtlp_resynth(hipStream_t s, int n_utt, const int64_t* d_offset
 
 // fill n 32-bit words with a value (used instead of memset so that calls stay graph-capturable)
 hipError_t launch_fill_u32(hipStream_t s, void* p, uint32_t v, int64_t n);
+// the same for two arrays in one launch
+hipError_t launch_fill2_u32(hipStream_t s, void* p, uint32_t v, int64_t n, void* q, uint32_t w, int64_t m);
 
 }  // namespace aug

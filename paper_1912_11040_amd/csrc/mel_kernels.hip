@@ -30,13 +30,9 @@ __global__ void window_kernel(int win, float* w) {
     w[i] = (float)(0.54 - 0.46 * c);
 }
 
-__global__ void mel_table_kernel(int n_utt, const float* __restrict__ alpha, aug_frontend_cfg cfg,
-                                 int stride, float2* __restrict__ tab) {
-    const int bins = cfg.nfft / 2 + 1;
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n_utt * bins) return;
-    const int u = i / bins, k = i % bins;
-    const double a = 1.0 - (double)alpha[u];
+// (band, weight) of bin k for one utterance: where Eq. (1) puts the bin on the mel scale
+__device__ inline float2 mel_bin_entry(const aug_frontend_cfg& cfg, float alpha_u, int k) {
+    const double a = 1.0 - (double)alpha_u;
     double sn, cs;
     sincospi(2.0 * (double)k / (double)cfg.nfft, &sn, &cs);
     const double omega = 2.0 * M_PI * (double)k / (double)cfg.nfft;
@@ -57,19 +53,27 @@ __global__ void mel_table_kernel(int n_utt, const float* __restrict__ alpha, aug
         ch = (float)c;
         wgt = (float)w;
     }
-    tab[(size_t)u * stride + k] = make_float2(ch, wgt);
+    return make_float2(ch, wgt);
 }
 
 // Cut the bins of one utterance into 16 contiguous lane ranges that end on changes of the band
 // index c, so that every (c, utterance) sum is formed by one lane alone.  Range i ends at the band
 // change nearest to (i + 1) bins / 16; the ends are non-decreasing because the targets are.
-// One work group of 64 threads per utterance; threads 0..14 each place one boundary.
-__global__ __launch_bounds__(64) void mel_partition_kernel(int n_utt, int bins, int stride, float2* __restrict__ tab) {
+// One work group of 64 threads per utterance writes the utterance's table, then threads 0..14 each place
+// one boundary.
+__global__ __launch_bounds__(64) void mel_table_kernel(int n_utt, const float* __restrict__ alpha, aug_frontend_cfg cfg,
+                                                       int stride, float2* __restrict__ tab) {
     __shared__ float band[2050];
+    const int bins = cfg.nfft / 2 + 1;
     const int u = blockIdx.x;
-    const float2* t = tab + (size_t)u * stride;
+    float2* t = tab + (size_t)u * stride;
     int* kstart = reinterpret_cast<int*>(tab + (size_t)u * stride + bins);
-    for (int k = threadIdx.x; k < bins; k += 64) band[k] = t[k].x;
+    const float alpha_u = alpha[u];
+    for (int k = threadIdx.x; k < bins; k += 64) {
+        const float2 e = mel_bin_entry(cfg, alpha_u, k);
+        t[k] = e;
+        band[k] = e.x;
+    }
     __syncthreads();
     const int lane = threadIdx.x;
     if (lane == 0) { kstart[0] = 0; kstart[16] = bins; }
@@ -327,14 +331,8 @@ int mel_table_stride(int nfft) { return nfft / 2 + 1 + 9; }   // (c, w) per bin,
 
 hipError_t launch_mel_table(hipStream_t s, int n_utt, const float* alpha, const aug_frontend_cfg& cfg,
                             float2* tab) {
-    const int bins = cfg.nfft / 2 + 1;
-    const int64_t n = (int64_t)n_utt * bins;
-    if (n <= 0) return hipSuccess;
-    mel_table_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(n_utt, alpha, cfg,
-                                                                             mel_table_stride(cfg.nfft), tab);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    mel_partition_kernel<<<dim3((unsigned)n_utt), dim3(64), 0, s>>>(n_utt, bins, mel_table_stride(cfg.nfft), tab);
+    if (n_utt <= 0) return hipSuccess;
+    mel_table_kernel<<<dim3((unsigned)n_utt), dim3(64), 0, s>>>(n_utt, alpha, cfg, mel_table_stride(cfg.nfft), tab);
     return hipGetLastError();
 }
 

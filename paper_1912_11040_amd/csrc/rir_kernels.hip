@@ -173,9 +173,17 @@ __global__ void rir_plan_kernel(int n_rir, const float* __restrict__ geom, int r
     }
 }
 
-// one thread per item: its cost class (0 = heaviest), and the class census
+// one thread per item: its cost class (0 = heaviest), and the class census; the groups past
+// `item_groups` fill the beta^k tables instead (kPow / 256 groups per response)
 __global__ void rir_classify_kernel(const float* __restrict__ geom, int rir_len, double k_fs_c,
-                                    Item* __restrict__ unsorted, int* __restrict__ ctrl) {
+                                    Item* __restrict__ unsorted, int* __restrict__ ctrl, int item_groups,
+                                    float* __restrict__ pow_table) {
+    if ((int)blockIdx.x >= item_groups) {
+        const int g = blockIdx.x - item_groups;
+        const int r = g / (kPow / 256), k = (g % (kPow / 256)) * 256 + threadIdx.x;
+        pow_table[(size_t)r * kPow + k] = (float)pow((double)geom[(size_t)r * 10 + 9], (double)k);
+        return;
+    }
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= ctrl[0]) return;
     Item it = unsorted[i];
@@ -192,31 +200,23 @@ __global__ void rir_classify_kernel(const float* __restrict__ geom, int rir_len,
     atomicAdd(&ctrl[2 + cls], 1);
 }
 
-// first slot of each class in the sorted table, heaviest class first
-__global__ void rir_class_offsets_kernel(int* __restrict__ ctrl) {
+// Items move to their class's stretch of the sorted table, heaviest class first: persistent groups then take
+// the heaviest items first and finish on the light ones, which evens out their finishing times.
+// ctrl[2 + c] is the census of class c, ctrl[2 + kClasses + c] the cursor within its stretch.
+__global__ void rir_sort_items_kernel(const Item* __restrict__ unsorted, Item* __restrict__ sorted, int* __restrict__ ctrl) {
+    __shared__ int first_slot[kClasses];
     if (threadIdx.x == 0) {
         int at = 0;
         for (int c = 0; c < kClasses; ++c) {
-            ctrl[2 + kClasses + c] = at;
+            first_slot[c] = at;
             at += ctrl[2 + c];
         }
     }
-}
-
-// Items move to their class's stretch of the sorted table: persistent groups then take the heaviest
-// items first and finish on the light ones, which evens out their finishing times.
-__global__ void rir_sort_items_kernel(const Item* __restrict__ unsorted, Item* __restrict__ sorted, int* __restrict__ ctrl) {
+    __syncthreads();
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= ctrl[0]) return;
     const Item it = unsorted[i];
-    sorted[atomicAdd(&ctrl[2 + kClasses + it.cls], 1)] = it;
-}
-
-__global__ void rir_pow_kernel(int n_rir, const float* __restrict__ geom, float* __restrict__ table) {
-    const int r = blockIdx.y;
-    const int k = blockIdx.x * blockDim.x + threadIdx.x;
-    if (k >= kPow) return;
-    table[(size_t)r * kPow + k] = (float)pow((double)geom[(size_t)r * 10 + 9], (double)k);
+    sorted[first_slot[it.cls] + atomicAdd(&ctrl[2 + kClasses + it.cls], 1)] = it;
 }
 
 // per-column record shared through LDS between the lane that built it and the lanes that walk its pieces
@@ -642,6 +642,13 @@ __global__ void fill_u32_kernel(uint32_t* p, uint32_t v, int64_t n) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = v;
 }
 
+__global__ void fill2_u32_kernel(uint32_t* p, uint32_t v, int64_t n, uint32_t* q, uint32_t w, int64_t m) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n + m; i += stride) {
+        if (i < n) p[i] = v; else q[i - n] = w;
+    }
+}
+
 }  // namespace
 
 hipError_t launch_fill_u32(hipStream_t s, void* p, uint32_t v, int64_t n) {
@@ -649,6 +656,15 @@ hipError_t launch_fill_u32(hipStream_t s, void* p, uint32_t v, int64_t n) {
     int64_t blocks = (n + 255) / 256;
     if (blocks > 8192) blocks = 8192;
     fill_u32_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(static_cast<uint32_t*>(p), v, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill2_u32(hipStream_t s, void* p, uint32_t v, int64_t n, void* q, uint32_t w, int64_t m) {
+    if (n + m <= 0) return hipSuccess;
+    int64_t blocks = (n + m + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    fill2_u32_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(static_cast<uint32_t*>(p), v, n,
+                                                                  static_cast<uint32_t*>(q), w, m);
     return hipGetLastError();
 }
 
@@ -675,24 +691,24 @@ hipError_t launch_rir_plan(hipStream_t s, int n_groups, int n_rir, const float* 
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     const size_t max_items = (size_t)n_rir * per_rir;
-    rir_classify_kernel<<<dim3((unsigned)((max_items + 255) / 256)), dim3(256), 0, s>>>(geom, rir_len, fs_over_c, unsorted, ctrl);
+    const int item_groups = (int)((max_items + 255) / 256);
+    rir_classify_kernel<<<dim3((unsigned)(item_groups + n_rir * (kPow / 256))), dim3(256), 0, s>>>(
+        geom, rir_len, fs_over_c, unsorted, ctrl, item_groups, pow_table);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    rir_class_offsets_kernel<<<dim3(1), dim3(64), 0, s>>>(ctrl);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    rir_sort_items_kernel<<<dim3((unsigned)((max_items + 255) / 256)), dim3(256), 0, s>>>(unsorted, sorted, ctrl);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    rir_pow_kernel<<<dim3(kPow / 256, (unsigned)n_rir), dim3(256), 0, s>>>(n_rir, geom, pow_table);
+    rir_sort_items_kernel<<<dim3((unsigned)item_groups), dim3(256), 0, s>>>(unsorted, sorted, ctrl);
     return hipGetLastError();
 }
 
 hipError_t launch_rir(hipStream_t s, int n_groups, int n_rir, const float* geom, int rir_len, double fs_over_c,
-                      const void* items, int* ctrl, const float* pow_table, float* rir_out, int32_t* cnt_out) {
+                      const void* items, int* ctrl, const float* pow_table, float* rir_out, int32_t* cnt_out,
+                      bool restart) {
     if (n_rir <= 0) return hipSuccess;
-    hipError_t e = launch_fill_u32(s, ctrl + 1, 0u, 1);      // restart the item counter
-    if (e != hipSuccess) return e;
+    hipError_t e = hipSuccess;
+    if (restart) {                                           // another pass over the same plan
+        e = launch_fill_u32(s, ctrl + 1, 0u, 1);
+        if (e != hipSuccess) return e;
+    }
     const Item* it = static_cast<const Item*>(items);
     if (rir_out)
         rir_image_kernel<false><<<dim3((unsigned)n_groups), dim3(kThreads), 0, s>>>(
