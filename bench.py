@@ -36,9 +36,9 @@ RIR_FLOP_PER_IMAGE = 12.0     # 2 add, sqrt, mul, add, floor, table product, div
 # runs summarised in profiles/hbm_traffic_<workload>.md, scaled there by a 1 GiB copy.  They describe the
 # kernel sources with this digest only; for any other sources `traffic` is reported as null.
 RECORDED_TRAFFIC = {
-    "digest": "9d0e4a35131a0c4e",
-    "varlen": {"rir": 110854190, "rir_spectrum": 202025848, "convolve": 1268548110, "mel": 627038137},
-    "throughput": {"rir": 577701457, "rir_spectrum": 1220177770, "convolve": 5807745351, "mel": 2221330309},
+    "digest": "4e12aa31cadefd56",
+    "varlen": {"rir": 147859279, "rir_spectrum": 202544550, "convolve": 1271217410, "mel": 627177491},
+    "throughput": {"rir": 756359102, "rir_spectrum": 1220366929, "convolve": 5749332507, "mel": 2221098812},
 }
 
 
