@@ -170,6 +170,9 @@ def main() -> int:
                          "waveform: aug_vtlp_resynth_batch on the speech first, then the same path with "
                          "alpha = 1 (the paper's own order); waveform-only: aug_vtlp_resynth_batch alone")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the step replayed from a HIP graph (extra object in the JSON line; matters for "
+                         "small batches, whose dozen launches cost as much as their kernels)")
     ap.add_argument("--no-h2d", action="store_true",
                     help="skip the extra, untimed-for-the-headline loop that copies the waveforms from host memory")
     ap.add_argument("--copy-probe", action="store_true",
@@ -269,6 +272,31 @@ def main() -> int:
         torch.cuda.synchronize()
         ms_with_h2d = (time.perf_counter() - t0) * 1e3 / reps
         del h_speech, h_noise
+    graph_ms = None
+    if args.graph:
+        # the library's context runs on torch's current stream; capture needs a stream of its own
+        side = torch.cuda.Stream()
+        aug_g = Augmenter(0, side)
+        with torch.cuda.stream(side):
+            saved, aug = aug, aug_g
+            try:
+                step()                                   # sizes this context's workspace, uploads its tables
+                side.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    step()
+            finally:
+                aug = saved
+        for _ in range(args.warmup):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        del g
+        aug_g.close()
     stages = {k: (ms / max(n, 1), n) for k, (ms, n) in prof.items() if n > 0}
     work = stage_work(w, n_images)
     if args.vtlp == "waveform-only":
@@ -305,6 +333,9 @@ def main() -> int:
         "with_h2d": None if ms_with_h2d is None else
                     {"ms_per_step": ms_with_h2d, "value": w.audio_seconds / (ms_with_h2d * 1e-3),
                      "note": "waveforms copied from pinned host memory before every call; not the headline"},
+        "graph": None if graph_ms is None else
+                 {"ms_per_step": graph_ms, "value": w.audio_seconds / (graph_ms * 1e-3),
+                  "note": "the same step replayed from a HIP graph"},
         "stage_ms": {k: round(v[0] * v[1] / args.steps, 4) for k, v in stages.items()},
         "stage_roofline_frac": {k: round(roofline_for(k, work, stages[k][0] * stages[k][1] / args.steps)["frac"], 4)
                                 for k in stages if k in work},

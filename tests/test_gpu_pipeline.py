@@ -235,6 +235,46 @@ def test_frames_before_any_sound_arrives(aug):
     assert np.all(got["mixed"][:440] == 0.0) and np.all(got["feats"][foff[0]] == 0.0)
 
 
+def test_steady_state_call_can_be_captured_in_a_graph():
+    # Once the workspace has its size and the offsets are known, a call is kernel launches only (clears are
+    # fill kernels, not memsets), so it can be recorded into a HIP graph.  Replays are interleaved with eager
+    # work and synchronisations and each one is checked against the eager result.
+    import torch
+    from paper_1912_11040_amd.binding import Augmenter
+    w = W.tiny(n_utt=4, rir_len=1500)
+    stream = torch.cuda.Stream()
+    ctx = Augmenter(0, stream)
+    with torch.cuda.stream(stream):
+        d = DeviceWorkload(w)
+        eager = d.empty_feats()
+        ctx.aug_pipeline_batch(w.offsets, d.speech, d.noise, d.geom, w.rir_len, w.fs, w.c, d.snr_db, d.alpha,
+                               w.frontend, d.frame_offsets, eager)          # sizes the workspace, uploads the tables
+        stream.synchronize()
+        out = d.empty_feats()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            ctx.aug_pipeline_batch(w.offsets, d.speech, d.noise, d.geom, w.rir_len, w.fs, w.c, d.snr_db, d.alpha,
+                                   w.frontend, d.frame_offsets, out)
+    want = eager.cpu().numpy()
+    for k in range(4):
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(out.cpu().numpy(), want)
+        # eager work of the same context between replays
+        with torch.cuda.stream(stream):
+            again = d.empty_feats()
+            ctx.aug_pipeline_batch(w.offsets, d.speech, d.noise, d.geom, w.rir_len, w.fs, w.c, d.snr_db, d.alpha,
+                                   w.frontend, d.frame_offsets, again)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(again.cpu().numpy(), want)
+    ref = _oracle(w)["feats"]
+    assert feat_err(want, ref) <= FEAT_TOL
+    del graph
+    ctx.close()
+
+
 def test_no_noise_pipeline(aug):
     import dataclasses
     w = W.tiny(n_utt=2)
