@@ -149,27 +149,30 @@ __global__ void rir_plan_kernel(int n_rir, const float* __restrict__ geom, int r
     const float shells = fminf(fmaxf(ceilf(work / target), 1.f), (float)kMaxShells);
     const double L3 = (double)rir_len * rir_len * rir_len;
     const double step = L3 / (double)shells;
-    int bounds[kMaxShells + AUG_MAX_RIR_LEN / kMaxTaps + 4];
-    int count = 0, b = 0;
-    while (b < rir_len && count < items_per_rir - 1) {
-        int nb = (int)cbrt((double)b * b * b + step);
-        nb = max(nb, b + kMinTaps);
-        nb = min(min(nb, b + kMaxTaps), rir_len);
-        bounds[count++] = nb;
-        b = nb;
+    // Shells are cut from the outside in: every shell sets up all (x, y) columns inside its outer radius, so
+    // where the tap limit, not the work, decides the width it is the inner shells, with few columns, that
+    // should be the many and the narrow ones, and the left-over sliver belongs at the centre.
+    int bounds[kMaxShells + AUG_MAX_RIR_LEN / kMaxTaps + 4];      // lower bounds, outermost shell first
+    int count = 0, hi = rir_len;
+    while (hi > 0 && count < items_per_rir - 1) {
+        const double h3 = (double)hi * hi * hi;
+        int lo = h3 > step ? (int)cbrt(h3 - step) : 0;
+        lo = min(lo, hi - kMinTaps);
+        lo = max(max(lo, hi - kMaxTaps), 0);
+        if (lo < kMinTaps && hi <= kMaxTaps) lo = 0;              // no sliver at the centre
+        bounds[count++] = lo;
+        hi = lo;
     }
-    if (b < rir_len) {          // out of table space: cannot happen with the sizes chosen by the host
-        while (b < rir_len && count < items_per_rir) {
-            const int nb = min(b + kMaxTaps, rir_len);
-            bounds[count++] = nb;
-            b = nb;
-        }
+    while (hi > 0 && count < items_per_rir) {                       // out of table space: cannot happen with the
+        const int lo = max(hi - kMaxTaps, 0);                       // sizes chosen by the host
+        bounds[count++] = lo;
+        hi = lo;
     }
     const int base = atomicAdd(&ctrl[0], count);
-    int lo = 0;
+    int top = rir_len;
     for (int i = 0; i < count; ++i) {
-        unsorted[base + i] = Item{r, lo, bounds[i], kClasses - 1};
-        lo = bounds[i];
+        unsorted[base + i] = Item{r, bounds[i], top, kClasses - 1};
+        top = bounds[i];
     }
 }
 
