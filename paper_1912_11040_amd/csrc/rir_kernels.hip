@@ -41,7 +41,7 @@ namespace {
 
 constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / 64;
-constexpr int kMaxTaps = 5120;            // taps owned by one item (LDS: 8 bytes each)
+constexpr int kMaxTaps = 5632;            // taps owned by one item (LDS: 8 bytes each)
 constexpr int kMinTaps = 64;
 constexpr int kPow = 1024;                // beta^k table entries held in LDS
 constexpr int kAxisCap = 320;             // y or z images per q held in the sorted LDS tables 
@@ -223,12 +223,15 @@ __global__ void rir_sort_items_kernel(const Item* __restrict__ unsorted, Item* _
 }
 
 // per-column record shared through LDS between the lane that built it and the lanes that walk its pieces
+// (16 bytes: reflection counts stay below 2^16 for every room the interface accepts, and a batch of 64
+// columns has at most 64 * 2 kAxisCap / kPiece pieces)
 struct __align__(8) Column {
-    double a;            // dx*dx + dy*dy
-    int kxy;             // reflections along x and y
-    int pfx;             // inclusive prefix of piece counts within the wave's batch
+    double a;                    // dx*dx + dy*dy
+    unsigned short kxy;          // reflections along x and y
+    unsigned short pfx;          // inclusive prefix of piece counts within the wave's batch
     unsigned short start, len;   // range of the sorted z table that can fall inside the shell
 };
+static_assert(sizeof(Column) == 16, "column records are packed");
 
 __device__ inline int wave_inclusive_scan(int v, int lane) {
 #pragma unroll
@@ -559,7 +562,7 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
                         const AxisImage ye = ytab[cand - (ix ? row_pfx[ix - 1] : 0)];
                         const double dx = axis_delta(ax, qx, nx);
                         col.a = __dadd_rn(__dmul_rn(dx, dx), ye.key);
-                        col.kxy = iabs(nx - qx) + iabs(nx) + ye.aux;
+                        col.kxy = (unsigned short)(iabs(nx - qx) + iabs(nx) + ye.aux);
                     } else {
                         const int ix = cand / niy, iy = cand - ix * niy;
                         const int qx = ix & 1, nx = (ix >> 1) - nmx;
@@ -567,11 +570,11 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
                         const double dx = axis_delta(ax, qx, nx);
                         const double dy = axis_delta(ay, qy, ny);
                         col.a = __dadd_rn(__dmul_rn(dx, dx), __dmul_rn(dy, dy));
-                        col.kxy = iabs(nx - qx) + iabs(nx) + iabs(ny - qy) + iabs(ny);
+                        col.kxy = (unsigned short)(iabs(nx - qx) + iabs(nx) + iabs(ny - qy) + iabs(ny));
                     }
                     // reflections left for the z axis before this column's images vanish
                     // (beyond the first shell the shell's own inner radius bounds the distance well enough)
-                    const int kz_max = (n0 > 0 ? k_cut_item : reflection_cut(log2_beta, sqrtf((float)col.a))) - col.kxy;
+                    const int kz_max = (n0 > 0 ? k_cut_item : reflection_cut(log2_beta, sqrtf((float)col.a))) - (int)col.kxy;
                     if (col.a < r_out2 && kz_max >= 0) {
                         if (fast) {
                             // images with r_in^2 - a <= dz^2 <= r_out^2 - a within reach of the reflection cut:
@@ -592,8 +595,9 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
                         }
                     }
                 }
-                col.pfx = wave_inclusive_scan(pieces, lane);
-                const int n_pieces = __shfl(col.pfx, 63, 64);
+                const int pfx = wave_inclusive_scan(pieces, lane);
+                col.pfx = (unsigned short)pfx;
+                const int n_pieces = __shfl(pfx, 63, 64);
                 wc[lane] = col;
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
