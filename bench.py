@@ -36,9 +36,9 @@ RIR_FLOP_PER_IMAGE = 12.0     # 2 add, sqrt, mul, add, floor, table product, div
 # runs summarised in profiles/hbm_traffic_<workload>.md, scaled there by a 1 GiB copy.  They describe the
 # kernel sources with this digest only; for any other sources `traffic` is reported as null.
 RECORDED_TRAFFIC = {
-    "digest": "4e12aa31cadefd56",
-    "varlen": {"rir": 147859279, "rir_spectrum": 202544550, "convolve": 1271217410, "mel": 627177491},
-    "throughput": {"rir": 756359102, "rir_spectrum": 1220366929, "convolve": 5749332507, "mel": 2221098812},
+    "digest": "4be37aefee0054d4",
+    "varlen": {"rir": 138990276, "rir_spectrum": 202532248, "convolve": 1271470510, "mel": 627145750},
+    "throughput": {"rir": 736060198, "rir_spectrum": 1220584732, "convolve": 5738003450, "mel": 2221260075},
 }
 
 
