@@ -340,6 +340,23 @@ def main() -> int:
         "stage_roofline_frac": {k: round(roofline_for(k, work, stages[k][0] * stages[k][1] / args.steps)["frac"], 4)
                                 for k in stages if k in work},
     }
+    # The whole step against the chip: all stages' algorithmic flops over the step time against the fp32
+    # vector peak (the image sum's fp64 flops count once each), and the bytes that must cross HBM at least
+    # once (inputs in, features out) against the HBM peak.
+    # front end: 2.5 K log2 K for the real transform + window + bin powers + sparse mel + power law, per frame
+    front_flop_per_frame = 2.5 * 512 * 9 + 400 + 771 + 1028 + 80
+    flops = sum(amount for k, (bound, amount) in work.items() if bound != "hbm" and k in stages)
+    if "mel" in stages:
+        flops += front_flop_per_frame * float(foff[-1])
+    n_src_in = 1 + (w.n_noise if full and args.vtlp != "waveform-only" else 0)
+    min_bytes = 4.0 * w.total * n_src_in + (4.0 * w.total if args.vtlp == "waveform-only"
+                                             else 4.0 * w.frontend.feature_dim * float(foff[-1]))
+    out["path_roofline"] = {
+        "flops_per_step": flops, "achieved_tflops": flops / (ms_per_step * 1e-3) / 1e12,
+        "frac_of_fp32_peak": flops / (ms_per_step * 1e-3) / 1e12 / PEAK_FP32_TFLOPS,
+        "min_hbm_bytes_per_step": min_bytes, "achieved_gbs": min_bytes / (ms_per_step * 1e-3) / 1e9,
+        "frac_of_hbm_peak": min_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
+    }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, vtlp=args.vtlp)
         # context only: the same oracle with its FFT forms, which is what a sensible CPU program would run
