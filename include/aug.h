@@ -26,6 +26,9 @@
  *     thrown across the boundary.  aug_last_error gives the message of the
  *     last failure on that context.  Arguments are checked on the host before
  *     anything is launched; a failed call launches nothing.
+ *   - A pointer to an array that has no elements in this call (a batch with no
+ *     utterances or no samples, an output with no rows) may be NULL; any other
+ *     NULL that the argument lists below do not allow is AUG_ERR_INVALID_ARG.
  *   - All random draws (rooms, positions, SNRs, warp factors) are inputs.
  */
 #ifndef AUG_H_

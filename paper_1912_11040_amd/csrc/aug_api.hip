@@ -253,7 +253,12 @@ int run_convolve_mix(aug_ctx* ctx, int n_utt, int n_noise, const float* speech, 
     const int n_part = (rir_len + fft_n - 1) / fft_n;
     const float2* tw = nullptr;
     AUG_TRY(ensure_twiddle(ctx, fft_n, &tw));
-    if (total == 0 || n_utt == 0) return AUG_OK;
+    if (n_utt == 0) return AUG_OK;
+    if (total == 0) {       // no signal anywhere: every energy is zero, so every gain is
+        if (gains_out && n_noise > 0)
+            AUG_HIP(aug::launch_fill_u32(ctx->stream, gains_out, 0u, (int64_t)n_utt * n_noise), "gain clear");
+        return AUG_OK;
+    }
     int64_t max_len = 0;
     for (int u = 0; u < n_utt; ++u) max_len = std::max(max_len, pk.offsets[u + 1] - pk.offsets[u]);
 
@@ -358,11 +363,14 @@ int check_rir_args(aug_ctx* ctx, int rir_len, float fs, float c) {
     return AUG_OK;
 }
 
-int check_mix_args(aug_ctx* ctx, int n_noise, const void* speech, const void* noise, const void* snr_db) {
+// A pointer may be null only where the array it stands for has no elements.
+int check_mix_args(aug_ctx* ctx, int n_utt, int64_t total, int n_noise, const void* speech, const void* noise,
+                   const void* snr_db) {
     if (n_noise < 0 || n_noise > AUG_MAX_NOISE)
         return fail(ctx, AUG_ERR_INVALID_ARG, "n_noise must be in 0..%d", AUG_MAX_NOISE);
-    if (!speech) return fail(ctx, AUG_ERR_INVALID_ARG, "speech is null");
-    if (n_noise > 0 && (!noise || !snr_db)) return fail(ctx, AUG_ERR_INVALID_ARG, "noise or snr_db is null");
+    if (!speech && total > 0) return fail(ctx, AUG_ERR_INVALID_ARG, "speech is null");
+    if (n_noise > 0 && ((!noise && total > 0) || (!snr_db && n_utt > 0)))
+        return fail(ctx, AUG_ERR_INVALID_ARG, "noise or snr_db is null");
     return AUG_OK;
 }
 
@@ -473,11 +481,12 @@ int aug_convolve_mix_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, cons
                            float* mixed_out, float* gains_out) {
     AUG_TRY(enter(ctx));
     AUG_TRY(check_offsets(ctx, n_utt, offsets));
-    AUG_TRY(check_mix_args(ctx, n_noise, speech, noise, snr_db));
+    AUG_TRY(check_mix_args(ctx, n_utt, offsets[n_utt], n_noise, speech, noise, snr_db));
     if (rir_len < 1 || rir_len > AUG_MAX_RIR_LEN)
         return fail(ctx, rir_len < 1 ? AUG_ERR_INVALID_ARG : AUG_ERR_UNSUPPORTED,
                     "rir_len must be in 1..%d", AUG_MAX_RIR_LEN);
-    if (!rir || !mixed_out) return fail(ctx, AUG_ERR_INVALID_ARG, "rir or mixed_out is null");
+    if ((!rir && n_utt > 0) || (!mixed_out && offsets[n_utt] > 0))
+        return fail(ctx, AUG_ERR_INVALID_ARG, "rir or mixed_out is null");
     AUG_TRY(sync_packing(ctx, n_utt, offsets, nullptr, aug::conv_fft_size(rir_len), 0));
     return run_convolve_mix(ctx, n_utt, n_noise, speech, noise, rir, rir_len, snr_db, mixed_out, gains_out);
 }
@@ -488,7 +497,8 @@ int aug_vtlp_mel_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, const fl
     AUG_TRY(check_offsets(ctx, n_utt, offsets));
     AUG_TRY(check_frontend(ctx, cfg));
     AUG_TRY(check_frame_offsets(ctx, n_utt, offsets, frame_offsets, cfg));
-    if (!wave || !alpha || !feats_out) return fail(ctx, AUG_ERR_INVALID_ARG, "wave, alpha or feats_out is null");
+    if ((!wave && offsets[n_utt] > 0) || (!alpha && n_utt > 0) || (!feats_out && frame_offsets[n_utt] > 0))
+        return fail(ctx, AUG_ERR_INVALID_ARG, "wave, alpha or feats_out is null");
     AUG_TRY(sync_packing(ctx, n_utt, offsets, frame_offsets, 0, aug::mel_frames_per_group()));
     return run_mel(ctx, n_utt, wave, alpha, cfg, feats_out);
 }
@@ -507,9 +517,10 @@ int aug_vtlp_resynth_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, cons
         return fail(ctx, AUG_ERR_INVALID_ARG, "need win >= 2, hop >= 1, nfft >= win");
     if (!aug::vtlp_supported(cfg->win, cfg->hop, cfg->nfft))
         return fail(ctx, AUG_ERR_UNSUPPORTED, "kernels are built for win 800, hop 400, nfft 2048");
-    if (!wave || !alpha || !wave_out) return fail(ctx, AUG_ERR_INVALID_ARG, "wave, alpha or wave_out is null");
     const int64_t total = offsets[n_utt];
-    if (wave_out < wave + total && wave < wave_out + total)
+    if (((!wave || !wave_out) && total > 0) || (!alpha && n_utt > 0))
+        return fail(ctx, AUG_ERR_INVALID_ARG, "wave, alpha or wave_out is null");
+    if (total > 0 && wave_out < wave + total && wave < wave_out + total)
         return fail(ctx, AUG_ERR_INVALID_ARG, "wave_out overlaps wave");
     AUG_TRY(sync_packing(ctx, n_utt, offsets, nullptr, 0, 0));
     if (n_utt == 0 || total == 0) return AUG_OK;
@@ -535,11 +546,13 @@ int aug_pipeline_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, const fl
                        float* gains_out) {
     AUG_TRY(enter(ctx));
     AUG_TRY(check_offsets(ctx, n_utt, offsets));
-    AUG_TRY(check_mix_args(ctx, n_noise, speech, noise, snr_db));
+    AUG_TRY(check_mix_args(ctx, n_utt, offsets[n_utt], n_noise, speech, noise, snr_db));
     AUG_TRY(check_rir_args(ctx, rir_len, fs, c));
     AUG_TRY(check_frontend(ctx, cfg));
     AUG_TRY(check_frame_offsets(ctx, n_utt, offsets, frame_offsets, cfg));
-    if (!geom || !alpha || !feats_out) return fail(ctx, AUG_ERR_INVALID_ARG, "geom, alpha or feats_out is null");
+    if (((!geom || !alpha) && n_utt > 0) || (!feats_out && frame_offsets[n_utt] > 0))
+        return fail(ctx, AUG_ERR_INVALID_ARG, "geom, alpha or feats_out is null");
+    if (n_utt == 0) return AUG_OK;
     const int n_src = 1 + n_noise;
     if ((int64_t)n_utt * n_src * aug::rir_items_per_response(rir_len) > 0x7fffffffLL)
         return fail(ctx, AUG_ERR_UNSUPPORTED, "too many responses in one call");

@@ -283,3 +283,32 @@ def test_no_noise_pipeline(aug):
     ref = _oracle(w)
     _compare(got, ref, w)
     _compare_unmaterialised(aug, w, ref)
+
+
+def test_batch_with_no_frames_and_batch_with_no_samples(aug):
+    # Every utterance shorter than one analysis window: the feature output has no rows, and an array with no
+    # elements may be passed as a null pointer (torch's empty tensors are).  The waveform side still runs.
+    import dataclasses
+    import torch
+    w = W.varlen(n_utt=3, rir_len=1024, min_s=0.0, max_s=0.02, seed=5)
+    assert 0 < w.total and int(w.frame_offsets()[-1]) == 0
+    got = _run(aug, w)
+    ref = _oracle(w)
+    assert got["feats"].shape == ref["feats"].shape == (0, w.frontend.n_mel)
+    assert rir_err(got["rir"], ref["rir"]) <= RIR_TOL
+    assert wave_err(got["mixed"], ref["mixed"], w.offsets, silent_scale=w.speech) <= WAVE_TOL
+    np.testing.assert_allclose(got["gains"], ref["gains"], rtol=GAIN_TOL)
+    _run(aug, w, want_rir=False, want_mixed=False)
+    # no samples at all: responses are still produced, every gain is zero (zero energies)
+    empty = dataclasses.replace(w, offsets=np.zeros(w.n_utt + 1, np.int64), speech=np.zeros(0, np.float32),
+                                noise=np.zeros((w.n_noise, 0), np.float32))
+    got = _run(aug, empty)
+    assert got["feats"].shape[0] == 0 and got["mixed"].size == 0
+    assert rir_err(got["rir"], ref["rir"]) <= RIR_TOL
+    assert np.all(got["gains"] == 0.0)
+    gains = torch.full((w.n_utt, w.n_noise), float("nan"), device="cuda")
+    d = DeviceWorkload(empty)
+    aug.aug_convolve_mix_batch(empty.offsets, d.speech, d.noise, torch.from_numpy(ref["rir"].astype(np.float32)).cuda(),
+                               w.rir_len, d.snr_db, torch.zeros(0, device="cuda"), gains)
+    torch.cuda.synchronize()
+    assert np.all(gains.cpu().numpy() == 0.0)
