@@ -43,13 +43,14 @@ RECORDED_TRAFFIC = {
 
 
 def kernel_source_digest() -> str:
-    """Digest of the kernel sources with comments and white space removed."""
+    """Digest of the device code (kernels, their launchers and argument structures; not the host entry
+    points) with comments and white space removed."""
     import glob
     import hashlib
     import re
     h = hashlib.sha256()
     for f in sorted(glob.glob(os.path.join(ROOT, "paper_1912_11040_amd", "csrc", "*"))):
-        if f.endswith((".hip", ".h")):
+        if f.endswith(("_kernels.hip", ".h")):
             with open(f) as fh:
                 text = fh.read()
             text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
