@@ -30,7 +30,7 @@ import math
 import numpy as np
 
 __all__ = [
-    "frame_count", "rir_single", "rir_batch", "convolve_direct", "convolve_fft",
+    "frame_count", "rir_single", "rir_batch", "rir_mics_single", "rir_mics_batch", "convolve_direct", "convolve_fft",
     "convolve_at", "reverberate", "snr_gains", "convolve_mix_batch", "hamming",
     "dft_matrix", "stft_power", "bilinear_warp", "mel_edges_hz", "warped_mel_matrix",
     "dct2_matrix", "mel_epilogue", "vtlp_mel_batch", "pipeline_batch",
@@ -110,6 +110,66 @@ def rir_batch(geom, rir_len: int, fs: float, c: float):
     cnt = np.zeros((len(geom), rir_len), dtype=np.int32)
     for r in range(len(geom)):
         h[r], cnt[r] = rir_single(geom[r], rir_len, fs, c)
+    return h, cnt
+
+
+def rir_mics_single(geom_row, mics, rir_len: int, fs: float, c: float):
+    """Responses from one source to several microphones in the same room.
+
+    The recording device of Sec. 4 carries two microphones 6.8 cm apart; a
+    simulated counterpart needs one response per microphone for the same room
+    and source.  The image sources of a room do not depend on where the
+    microphone is, so they are listed once (per axis: coordinate and reflection
+    count) and every microphone sums its own response over that one list, tap
+    rule and amplitude as in `rir_single`.  geom_row's own microphone columns
+    are not used.  mics = [K, 3] (fp32 values).
+
+    Every image that can land below `rir_len` for any of the microphones must
+    be on the list: a microphone at most `room` away from the source along an
+    axis sees image n at a distance of at least (2|n| - 2) room, so the same
+    per-axis bound as for one microphone holds for each of them.
+
+    Returns (h fp64 [K, rir_len], tap_count int32 [K, rir_len]).
+    """
+    g = np.asarray(geom_row, dtype=np.float32).astype(np.float64)
+    mics = np.asarray(mics, dtype=np.float32).astype(np.float64).reshape(-1, 3)
+    room, src, beta = g[0:3], g[3:6], g[9]
+    k = np.float64(np.float32(fs)) / np.float64(np.float32(c))
+    radius = rir_len / k
+    images = []                                   # the shared list: per axis (coordinates, reflection counts)
+    for a in range(3):
+        n_max = int(math.ceil(radius / (2.0 * room[a]))) + 1
+        images.append(_axis_images(src[a], room[a], n_max))
+    (px, cx), (py, cy), (pz, cz) = images
+    refl_yz = cy[:, None] + cz[None, :]
+
+    h = np.zeros((len(mics), rir_len), dtype=np.float64)
+    tap_count = np.zeros((len(mics), rir_len), dtype=np.int64)
+    for m, mic in enumerate(mics):
+        dx2 = (px - mic[0]) * (px - mic[0])
+        dy2 = (py - mic[1]) * (py - mic[1])
+        dz2 = (pz - mic[2]) * (pz - mic[2])
+        for ix in range(len(px)):
+            d = np.sqrt((dx2[ix] + dy2[:, None]) + dz2[None, :])
+            idx = np.floor(d * k + 0.5).astype(np.int64)
+            keep = idx < rir_len
+            if not keep.any():
+                continue
+            amp = np.power(beta, (cx[ix] + refl_yz)[keep].astype(np.float64)) / (4.0 * np.pi * d[keep])
+            h[m] += np.bincount(idx[keep], weights=amp, minlength=rir_len)
+            tap_count[m] += np.bincount(idx[keep], minlength=rir_len)
+    return h, tap_count.astype(np.int32)
+
+
+def rir_mics_batch(geom, mics, rir_len: int, fs: float, c: float):
+    """geom [n_rir, 10], mics [n_rir, K, 3]; returns (h [n_rir, K, L] fp64, tap_count [n_rir, K, L] int32)."""
+    geom = np.asarray(geom, dtype=np.float32).reshape(-1, 10)
+    mics = np.asarray(mics, dtype=np.float32)
+    mics = mics.reshape(len(geom), -1, 3)
+    h = np.zeros((len(geom), mics.shape[1], rir_len), dtype=np.float64)
+    cnt = np.zeros((len(geom), mics.shape[1], rir_len), dtype=np.int32)
+    for r in range(len(geom)):
+        h[r], cnt[r] = rir_mics_single(geom[r], mics[r], rir_len, fs, c)
     return h, cnt
 
 
