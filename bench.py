@@ -159,6 +159,61 @@ def cpu_baseline(w, budget_s: float = 15.0, vtlp: str = "mel", fft: bool = False
                          "direct time-domain convolution + DFT-matrix front end") + f", {dt:.1f} s"}
 
 
+def bench_mics(args, w, aug) -> dict:
+    """aug_rir_mics_batch alone: every room of the workload with a line array of --mics microphones."""
+    import torch
+    from paper_1912_11040_amd import workloads as W
+    K, L = args.mics, w.rir_len
+    geom_h = np.asarray(w.geom, np.float32).reshape(-1, 10)
+    mics_h = W.microphone_arrays(geom_h, K, 0.068, seed=17)
+    geom, mics = torch.from_numpy(geom_h).cuda(), torch.from_numpy(mics_h).cuda()
+    n_rir = len(geom_h)
+    out_h = torch.empty((n_rir, K, L), dtype=torch.float32, device="cuda")
+    cnt = torch.empty((n_rir, K, L), dtype=torch.int32, device="cuda")
+    aug.aug_rir_mics_batch(geom, mics, L, w.fs, w.c, out_h, cnt)          # untimed: counts the images
+    n_images = float(cnt.sum(dtype=torch.int64).item())
+    del cnt
+    for _ in range(args.warmup):
+        aug.aug_rir_mics_batch(geom, mics, L, w.fs, w.c, out_h)
+    torch.cuda.synchronize()
+    aug.aug_profile_read()
+    aug.aug_profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        aug.aug_rir_mics_batch(geom, mics, L, w.fs, w.c, out_h)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = aug.aug_profile_read()
+    aug.aug_profile_enable(False)
+    ms_per_step = dt * 1e3 / args.steps
+    rir_ms = prof["rir"][0] / max(prof["rir"][1], 1)
+    flops = RIR_FLOP_PER_IMAGE * n_images
+    res = {
+        "metric": f"image-method responses/sec, {K} microphones per room, on 1 GPU",
+        "value": n_rir * K / (ms_per_step * 1e-3), "unit": "responses/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": f"rooms and sources of {describe(w)}; {K} microphones 6.8 cm apart in each; "
+                               f"{n_rir} x {K} responses of {L} taps", "entry_point": "aug_rir_mics_batch",
+                   "images_per_step": n_images},
+        "roofline": {"bound": "alu", "achieved": flops / (rir_ms * 1e-3) / 1e12, "peak": PEAK_FP64_TFLOPS,
+                     "unit": "TFLOP/s", "frac": flops / (rir_ms * 1e-3) / 1e12 / PEAK_FP64_TFLOPS, "traffic": None,
+                     "kernel": "rir_image_kernel", "avg_launch_ms": rir_ms},
+        "stage_ms": {k: round(ms / args.steps, 4) for k, (ms, n) in prof.items() if n > 0},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import aug_oracle as O
+        t0, done = time.perf_counter(), 0
+        while done < n_rir and time.perf_counter() - t0 < 15.0:
+            O.rir_mics_batch(geom_h[done:done + 1], mics_h[done:done + 1], L, w.fs, w.c)
+            done += 1
+        dt = time.perf_counter() - t0
+        res["cpu_baseline"] = {"value": done * K / dt, "unit": "responses/s", "cores": 1, "kind": "oracle",
+                               "sample": f"first {done} room(s) of the workload, {K} microphones each, {dt:.1f} s"}
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -170,6 +225,9 @@ def main() -> int:
                     help="mel: the warp is applied to the mel bank inside the front end (the headline path); "
                          "waveform: aug_vtlp_resynth_batch on the speech first, then the same path with "
                          "alpha = 1 (the paper's own order); waveform-only: aug_vtlp_resynth_batch alone")
+    ap.add_argument("--mics", type=int, default=0,
+                    help="time aug_rir_mics_batch alone: the workload's rooms with this many microphones in each "
+                         "(responses/s instead of the headline metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="also time the step replayed from a HIP graph (extra object in the JSON line; matters for "
@@ -202,6 +260,13 @@ def main() -> int:
     full = w.geom is not None
 
     aug = Augmenter(0)
+    if args.mics > 0:
+        if not full:
+            print("bench.py: --mics needs a workload with rooms", file=sys.stderr)
+            return 2
+        print(json.dumps(bench_mics(args, w, aug)))
+        aug.close()
+        return 0
     warped = torch.empty_like(speech) if args.vtlp != "mel" else None
     ones = torch.ones_like(alpha)
 

@@ -56,6 +56,8 @@ typedef struct aug_ctx aug_ctx;
 #define AUG_MAX_NOISE 8
 /* Largest number of mel channels. */
 #define AUG_MAX_MEL 128
+/* Largest number of microphones per room in aug_rir_mics_batch. */
+#define AUG_MAX_MIC 16
 #define AUG_MAX_UTT 65535        /* utterances per call */
 #define AUG_MAX_UTT_SAMPLES ((1 << 30) - 1)   /* samples per utterance */
 
@@ -105,6 +107,30 @@ int64_t aug_frame_count(int64_t n_samples, int win, int hop);
  */
 int aug_rir_batch(aug_ctx* ctx, int n_rir, const float* geom, int rir_len,
                   float fs, float c, float* rir_out, int32_t* tap_count_out);
+
+/*
+ * Responses from each source to several microphones in its room: the device
+ * that records the far-field test sets of Sec. 4 carries two microphones
+ * 6.8 cm apart, and simulating such a device needs one response per
+ * microphone for the same room, source and walls.
+ *
+ *   n_mic          microphones per room, 1..AUG_MAX_MIC.
+ *   geom           DEVICE float [n_rir][10] as for aug_rir_batch; its microphone
+ *                  columns (6..8) are not read.
+ *   mics           DEVICE float [n_rir][n_mic][3]: microphone x,y,z, inside the
+ *                  room and away from the source like the single one.
+ *   rir_out        DEVICE float [n_rir][n_mic][rir_len], overwritten: slice
+ *                  [r][m] is what aug_rir_batch gives for row r with microphone
+ *                  mics[r][m], bit for bit.
+ *   tap_count_out  DEVICE int32 [n_rir][n_mic][rir_len] or NULL.
+ *
+ * The image sources of a room are the same for every microphone, but the
+ * kernels visit them in shells of distance around the microphone, so each
+ * microphone is summed as a response of its own: the cost is n_mic times that
+ * of aug_rir_batch.  n_rir == 0 is a no-op.
+ */
+int aug_rir_mics_batch(aug_ctx* ctx, int n_rir, int n_mic, const float* geom, const float* mics,
+                       int rir_len, float fs, float c, float* rir_out, int32_t* tap_count_out);
 
 /*
  * Reverberation and additive noise (acoustic simulator, Sec. 2.3): every

@@ -22,6 +22,7 @@ AUG_ERR_NOMEM = -3
 AUG_ERR_HIP = -4
 
 EXPORTS = ("aug_create", "aug_destroy", "aug_last_error", "aug_frame_count", "aug_feature_dim", "aug_rir_batch",
+           "aug_rir_mics_batch",
            "aug_convolve_mix_batch", "aug_vtlp_mel_batch", "aug_vtlp_resynth_batch", "aug_pipeline_batch",
            "aug_profile_enable", "aug_profile_read")
 
@@ -84,6 +85,8 @@ def load_library() -> ctypes.CDLL:
     lib.aug_feature_dim.restype = ci
     lib.aug_rir_batch.argtypes = [vp, ci, vp, ci, cf, cf, vp, vp]
     lib.aug_rir_batch.restype = ci
+    lib.aug_rir_mics_batch.argtypes = [vp, ci, ci, vp, vp, ci, cf, cf, vp, vp]
+    lib.aug_rir_mics_batch.restype = ci
     lib.aug_convolve_mix_batch.argtypes = [vp, ci, p_i64, vp, ci, vp, vp, ci, vp, vp, vp]
     lib.aug_convolve_mix_batch.restype = ci
     lib.aug_vtlp_mel_batch.argtypes = [vp, ci, p_i64, vp, vp, p_cfg, p_i64, vp]
@@ -178,6 +181,17 @@ class Augmenter:
         self._check(self._lib.aug_rir_batch(
             self._h, n_rir, _ptr(geom, torch.float32), int(rir_len), float(fs), float(c),
             _ptr(rir_out, torch.float32), _ptr(tap_count_out, torch.int32)))
+
+    def aug_rir_mics_batch(self, geom, mics, rir_len: int, fs: float, c: float, rir_out, tap_count_out=None,
+                           n_mic: Optional[int] = None):
+        """geom [n_rir][10], mics [n_rir][n_mic][3]; n_mic is read from mics' shape unless given."""
+        import torch
+        n_rir = int(geom.numel() // 10) if geom is not None else 0
+        if n_mic is None:
+            n_mic = int(mics.shape[-2]) if mics is not None and mics.dim() >= 2 else 0
+        self._check(self._lib.aug_rir_mics_batch(
+            self._h, n_rir, int(n_mic), _ptr(geom, torch.float32), _ptr(mics, torch.float32), int(rir_len),
+            float(fs), float(c), _ptr(rir_out, torch.float32), _ptr(tap_count_out, torch.int32)))
 
     def aug_convolve_mix_batch(self, offsets, speech, noise, rir, rir_len: int, snr_db, mixed_out,
                                gains_out=None, n_noise: Optional[int] = None):

@@ -419,7 +419,7 @@ int aug_destroy(aug_ctx* ctx) {
         rc = AUG_ERR_HIP;
     }
     DeviceBuffer* bufs[] = {&ctx->d_offsets, &ctx->d_frame_offsets, &ctx->d_conv_items, &ctx->d_frame_items,
-                            &ctx->rir_items, &ctx->rir_ctrl, &ctx->rir_pow, &ctx->rir, &ctx->rir_spec, &ctx->reverb, &ctx->energy, &ctx->gains, &ctx->first_tap, &ctx->vtlp_tab, &ctx->dct, &ctx->mel_tab,
+                            &ctx->rir_items, &ctx->rir_ctrl, &ctx->rir_pow, &ctx->mic_rows, &ctx->rir, &ctx->rir_spec, &ctx->reverb, &ctx->energy, &ctx->gains, &ctx->first_tap, &ctx->vtlp_tab, &ctx->dct, &ctx->mel_tab,
                             &ctx->window};
     for (DeviceBuffer* b : bufs) b->release();
     for (DeviceBuffer& b : ctx->twiddle) b.release();
@@ -474,6 +474,26 @@ int aug_rir_batch(aug_ctx* ctx, int n_rir, const float* geom, int rir_len, float
     if ((int64_t)n_rir * aug::rir_items_per_response(rir_len) > 0x7fffffffLL)
         return fail(ctx, AUG_ERR_UNSUPPORTED, "too many responses in one call");
     return run_rir(ctx, n_rir, geom, rir_len, fs, c, rir_out, tap_count_out);
+}
+
+int aug_rir_mics_batch(aug_ctx* ctx, int n_rir, int n_mic, const float* geom, const float* mics, int rir_len,
+                       float fs, float c, float* rir_out, int32_t* tap_count_out) {
+    AUG_TRY(enter(ctx));
+    if (n_rir < 0) return fail(ctx, AUG_ERR_INVALID_ARG, "n_rir is negative");
+    if (n_mic < 1 || n_mic > AUG_MAX_MIC) return fail(ctx, AUG_ERR_INVALID_ARG, "n_mic must be in 1..%d", AUG_MAX_MIC);
+    AUG_TRY(check_rir_args(ctx, rir_len, fs, c));
+    if (n_rir == 0) return AUG_OK;
+    if (!geom || !mics || !rir_out) return fail(ctx, AUG_ERR_INVALID_ARG, "geom, mics or rir_out is null");
+    const int64_t n_rows = (int64_t)n_rir * n_mic;
+    if (n_rows * aug::rir_items_per_response(rir_len) > 0x7fffffffLL)
+        return fail(ctx, AUG_ERR_UNSUPPORTED, "too many responses in one call");
+    // rewriting the rows is ordered after an earlier call's kernels by the stream; growing the buffer frees
+    // the old one, which waits for them
+    AUG_HIP(ctx->mic_rows.reserve(sizeof(float) * 10 * (size_t)n_rows), "microphone rows");
+    AUG_TRY(mark(ctx, -1));
+    AUG_HIP(aug::launch_rir_mic_rows(ctx->stream, n_rir, n_mic, geom, mics, ctx->mic_rows.as<float>()), "microphone rows kernel");
+    AUG_TRY(mark(ctx, AUG_STAGE_OTHER));
+    return run_rir(ctx, (int)n_rows, ctx->mic_rows.as<float>(), rir_len, fs, c, rir_out, tap_count_out);
 }
 
 int aug_convolve_mix_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, const float* speech, int n_noise,

@@ -51,6 +51,7 @@ struct aug_ctx {
     aug::DeviceBuffer rir_items;         // Item [n_rir * items_per_response]
     aug::DeviceBuffer rir_ctrl;          // int [rir_ctrl_ints()]: item count, next item, class counters
     aug::DeviceBuffer rir_pow;           // float [n_rir][pow entries]: beta^k
+    aug::DeviceBuffer mic_rows;          // float [n_rir * n_mic][10]: one geometry row per microphone
 
     // intermediate results
     aug::DeviceBuffer rir;               // float [n_rir][rir_len]            (pipeline only)
@@ -91,6 +92,9 @@ hipError_t launch_rir_plan(hipStream_t s, int n_groups, int n_rir, const float* 
 hipError_t launch_rir(hipStream_t s, int n_groups, int n_rir, const float* geom, int rir_len, double fs_over_c,
                       const void* items, int* ctrl, const float* pow_table, float* rir_out, int32_t* cnt_out,
                       bool restart);
+
+// rows float [n_rir * n_mic][10]: geometry row r / n_mic with microphone mics[r] (float [n_rir][n_mic][3]).
+hipError_t launch_rir_mic_rows(hipStream_t s, int n_rir, int n_mic, const float* geom, const float* mics, float* rows);
 
 // Largest complex FFT size the convolution kernels are built for, and the size chosen for a response length.
 int conv_fft_size(int rir_len);

@@ -675,6 +675,22 @@ hipError_t launch_fill2_u32(hipStream_t s, void* p, uint32_t v, int64_t n, void*
     return hipGetLastError();
 }
 
+// One geometry row per (response, microphone): the row of the response with its microphone columns replaced.
+__global__ void rir_mic_rows_kernel(int n_rows, int n_mic, const float* __restrict__ geom, const float* __restrict__ mics,
+                                    float* __restrict__ rows) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;       // one thread per output value
+    if (i >= n_rows * 10) return;
+    const int row = i / 10, col = i - row * 10;
+    rows[i] = (col >= 6 && col < 9) ? mics[(size_t)row * 3 + (col - 6)] : geom[(size_t)(row / n_mic) * 10 + col];
+}
+
+hipError_t launch_rir_mic_rows(hipStream_t s, int n_rir, int n_mic, const float* geom, const float* mics, float* rows) {
+    const int n_rows = n_rir * n_mic;
+    if (n_rows <= 0) return hipSuccess;
+    rir_mic_rows_kernel<<<dim3((unsigned)((n_rows * 10 + 255) / 256)), dim3(256), 0, s>>>(n_rows, n_mic, geom, mics, rows);
+    return hipGetLastError();
+}
+
 int rir_items_per_response(int rir_len) { return kMaxShells + rir_len / kMaxTaps + 2; }
 size_t rir_item_bytes() { return sizeof(Item); }
 int rir_pow_entries() { return kPow; }

@@ -194,6 +194,22 @@ def draw_geometry(rng: np.random.Generator, n_src: int, dims, beta: float,
     return rows
 
 
+def microphone_arrays(geom, n_mic: int = 2, spacing: float = 0.068, seed: int = 0) -> np.ndarray:
+    """A small horizontal line array in place of each row's microphone: [n_rows, n_mic, 3] float32.
+
+    The n_mic microphones of a row are `spacing` metres apart along a randomly oriented horizontal line
+    centred on that row's own microphone position (two microphones 6.8 cm apart by default, the device
+    of Sec. 4).  Rows keep their `margin` from the walls as long as the array is shorter than it.
+    """
+    geom = np.asarray(geom, dtype=np.float32).reshape(-1, 10)
+    rng = np.random.default_rng(seed)
+    phi = rng.uniform(0.0, 2.0 * np.pi, len(geom))
+    along = np.stack([np.cos(phi), np.sin(phi), np.zeros_like(phi)], axis=1)            # [n, 3]
+    steps = (np.arange(n_mic) - 0.5 * (n_mic - 1)) * spacing                              # [n_mic]
+    mics = geom[:, None, 6:9].astype(np.float64) + steps[None, :, None] * along[:, None, :]
+    return mics.astype(np.float32)
+
+
 def _random_room(rng: np.random.Generator):
     dims = np.array([rng.uniform(3.0, 10.0), rng.uniform(3.0, 8.0), rng.uniform(2.5, 4.0)])
     beta = rng.uniform(0.2, 0.9)

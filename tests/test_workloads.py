@@ -60,3 +60,15 @@ def test_features_only_has_no_room():
     w = W.features_only(n_utt=3, seconds=0.5)
     assert w.noise is None and w.geom is None and w.n_noise == 0
     assert w.frame_offsets().tolist() == [0, 48, 96, 144]
+
+
+def test_microphone_arrays():
+    w = W.tiny(n_utt=4)
+    geom = w.geom.reshape(-1, 10)
+    m = W.microphone_arrays(geom, 3, 0.05, seed=2)
+    assert m.shape == (len(geom), 3, 3) and m.dtype == np.float32
+    np.testing.assert_array_equal(m, W.microphone_arrays(geom, 3, 0.05, seed=2))
+    np.testing.assert_allclose(m[:, 1], geom[:, 6:9], atol=1e-6)                 # centred on the row's microphone
+    np.testing.assert_allclose(np.linalg.norm(m[:, 2] - m[:, 0], axis=1), 0.10, atol=1e-5)
+    assert np.all(m[:, :, 2] == geom[:, None, 8])                                # horizontal
+    assert np.all(m > 0.4) and np.all(m < geom[:, None, 0:3] - 0.4)              # still inside the margin
