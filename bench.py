@@ -36,9 +36,9 @@ RIR_FLOP_PER_IMAGE = 12.0     # 2 add, sqrt, mul, add, floor, table product, div
 # runs summarised in profiles/hbm_traffic_<workload>.md, scaled there by a 1 GiB copy.  They describe the
 # kernel sources with this digest only; for any other sources `traffic` is reported as null.
 RECORDED_TRAFFIC = {
-    "digest": "9472e2a08a73eb02",
-    "varlen": {"rir": 138990276, "rir_spectrum": 202532248, "convolve": 1271470510, "mel": 627145750},
-    "throughput": {"rir": 736060198, "rir_spectrum": 1220584732, "convolve": 5738003450, "mel": 2221260075},
+    "digest": "4762a08df0848850",
+    "varlen": {"rir": 139247720, "rir_spectrum": 202534623, "convolve": 1272214593, "mel": 627036052},
+    "throughput": {"rir": 740230960, "rir_spectrum": 1220458604, "convolve": 5728436880, "mel": 2221194030},
 }
 
 
