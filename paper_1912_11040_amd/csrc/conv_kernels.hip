@@ -145,6 +145,9 @@ __device__ inline void multiply_pair(float2 A, float2 B, float2 w, float2 Hk, fl
 
 constexpr int kXcds = 8;
 
+// two consecutive samples; only their 4-byte alignment is promised (global accesses of two dwords need no more)
+struct __attribute__((aligned(4))) SamplePair { float x, y; };
+
 // MULTI: the response has several partitions.
 template <int N, int T, bool MULTI>
 __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* __restrict__ tw) {
@@ -187,13 +190,24 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
         asm volatile("" : "+v"(tid_p));
         const int k2 = tid_p % (M / 2), half = tid_p / (M / 2);
         const int w0 = (wb - 1) * N + 2 * tid_p;           // first sample of this thread in the window (may be < 0)
+        if (wb >= 1 && (wb + 1) * (int64_t)N <= len) {
+            // the whole window lies inside the utterance (the same for every thread of the group): sixteen
+            // two-sample loads with nothing to test, issued back to back
+            const float* xw = x + w0;
 #pragma unroll
-        for (int n1 = 0; n1 < 16; ++n1) {
-            const int g = w0 + 2 * M * n1;
-            // unsigned compares fold the g >= 0 test in
-            const float x0 = (unsigned)g < (unsigned)len ? x[g] : 0.f;
-            const float x1 = (unsigned)(g + 1) < (unsigned)len ? x[g + 1] : 0.f;
-            v[n1] = make_float2(x0, x1);
+            for (int n1 = 0; n1 < 16; ++n1) {
+                const SamplePair s2 = *reinterpret_cast<const SamplePair*>(xw + 2 * M * n1);
+                v[n1] = make_float2(s2.x, s2.y);
+            }
+        } else {
+#pragma unroll
+            for (int n1 = 0; n1 < 16; ++n1) {
+                const int g = w0 + 2 * M * n1;
+                // unsigned compares fold the g >= 0 test in
+                const float x0 = (unsigned)g < (unsigned)len ? x[g] : 0.f;
+                const float x1 = (unsigned)(g + 1) < (unsigned)len ? x[g + 1] : 0.f;
+                v[n1] = make_float2(x0, x1);
+            }
         }
         if (p == 0) {                                // the block's own input samples are the window's second half
 #pragma unroll
@@ -234,12 +248,25 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
     // there, which the power law of the front end would turn into a visible feature value.
     const int out0 = b * N + 2 * tid;
     float e = 0.f;
+    if ((b + 1) * (int64_t)N <= len) {               // a full block: eight two-sample stores, nothing to test
+        float* yb = y + out0;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int g = out0 + 2 * M * i;
-        const float s0 = g >= first ? out[i].x : 0.f, s1 = g + 1 >= first ? out[i].y : 0.f;
-        if (g < len) { y[g] = s0; e += s0 * s0; }
-        if (g + 1 < len) { y[g + 1] = s1; e += s1 * s1; }
+        for (int i = 0; i < 8; ++i) {
+            const int g = out0 + 2 * M * i;
+            SamplePair s2;
+            s2.x = g >= first ? out[i].x : 0.f;
+            s2.y = g + 1 >= first ? out[i].y : 0.f;
+            *reinterpret_cast<SamplePair*>(yb + 2 * M * i) = s2;
+            e += s2.x * s2.x + s2.y * s2.y;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int g = out0 + 2 * M * i;
+            const float s0 = g >= first ? out[i].x : 0.f, s1 = g + 1 >= first ? out[i].y : 0.f;
+            if (g < len) { y[g] = s0; e += s0 * s0; }
+            if (g + 1 < len) { y[g + 1] = s1; e += s1 * s1; }
+        }
     }
     double es = (double)e, es_in = (double)e_in;
     for (int off = 32; off > 0; off >>= 1) {

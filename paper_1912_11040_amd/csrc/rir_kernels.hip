@@ -253,9 +253,11 @@ struct __align__(16) AxisImage {
 
 struct WalkCtx {
     double k_fs_c;
-    double guard;        // estimates closer than this to a rounding boundary are redone exactly
+    double shift;        // 0.5 + guard - (n0 - 1): added to d fs/c, it gives slot = tap - n0 + 1 by truncation
+    double guard2;       // estimates whose fraction (after the shift) is below this are redone exactly
     double beta;
-    int n0, n_taps;
+    int n0m1;            // n0 - 1
+    unsigned int n_slots;   // taps of the item + 1: slot 0 takes what belongs below the item and is never read
 };
 
 // the reference recipe, kept out of line so that the estimate's loop stays short
@@ -274,44 +276,57 @@ __device__ inline int reflection_cut(float log2_beta, float d_min) {
     return k > 1.0e6f ? (1 << 20) : (int)k + 2;
 }
 
-// Tap index of an image at squared distance d2, and y ~ 1/sqrt(d2) for its amplitude.
-__device__ inline int tap_index(const WalkCtx& w, double d2, float& y) {
+// Slot (tap - n0 + 1) of an image at squared distance d2, and y ~ 1/sqrt(d2) for its amplitude.
+// The estimate of d fs/c is good to ~2e-9 taps; shifted up by the guard, its fraction falls below
+// 2 guard exactly when the true value may lie within the guard of a rounding boundary, and only then is
+// the reference recipe evaluated.  Images below the item (slot <= 0 after truncation towards zero, or
+// negative) land in slot 0 or fail the range check; both are ignored.
+__device__ inline int tap_slot(const WalkCtx& w, double d2, float& y) {
     const float d2f = (float)d2;
     y = __frsqrt_rn(d2f);
     const double s0 = (double)(d2f * y);                   // sqrt(d2) to ~2e-7
     const double res = fma(-s0, s0, d2);                   // exact residual
     const double s1 = fma(res, (double)(0.5f * y), s0);    // one Newton step: ~1e-13 relative
-    const double t = fma(s1, w.k_fs_c, 0.5);
-    const double frac = __builtin_amdgcn_fract(t);
-    int idx = (int)t;
-    if (fabs(frac - 0.5) > 0.5 - w.guard) idx = exact_tap(d2, w.k_fs_c);
-    return idx;
+    const double t = fma(s1, w.k_fs_c, w.shift);
+    int slot = (int)t;
+    if (__builtin_amdgcn_fract(t) < w.guard2) slot = exact_tap(d2, w.k_fs_c) - w.n0m1;
+    return slot;
 }
 
 template <bool COUNT>
-__device__ inline void deposit(const WalkCtx& w, int idx, float x, unsigned long long* hist, unsigned int* hist32) {
-    const unsigned int rel = (unsigned int)(idx - w.n0);
-    if (rel >= (unsigned int)w.n_taps) return;
+__device__ inline void deposit(const WalkCtx& w, int slot, float x, unsigned long long* hist, unsigned int* hist32) {
+    if ((unsigned int)slot >= w.n_slots) return;
     if (COUNT) {
-        atomicAdd(&hist32[rel], 1u);
+        atomicAdd(&hist32[slot], 1u);
     } else {
         // x = amplitude * 2^24; amplitude * 2^56 as a 64-bit integer from two exact fp32 scalings
         const float fr = __builtin_amdgcn_fractf(x);
         const unsigned int hi = (unsigned int)x;
         const unsigned int lo = (unsigned int)(fr * 4294967296.0f);
-        atomicAdd(&hist[rel], ((unsigned long long)hi << 32) | lo);
+        atomicAdd(&hist[slot], ((unsigned long long)hi << 32) | lo);
     }
 }
 
 template <bool COUNT>
 __device__ inline void walk_piece_table(const WalkCtx& w, double a, float cxy, const AxisImage* z, int len,
                                         unsigned long long* hist, unsigned int* hist32) {
-    for (int i = 0; i < len; ++i) {
-        const AxisImage e = z[i];
+    // walked from the far end so that one register is both the address and the loop condition
+    // (the sums are integers: the order does not matter)
+    // (the LDS address itself is the loop variable, opaque to the compiler so that it is not split into
+    // a counter plus an offset)
+    typedef const AxisImage __attribute__((address_space(3))) * LdsImages;
+    const unsigned int first = (unsigned int)(uintptr_t)(LdsImages)z;
+    for (unsigned int cur = first + (unsigned int)len * (unsigned int)sizeof(AxisImage); cur != first;) {
+        cur -= (unsigned int)sizeof(AxisImage);
+        asm("" : "+v"(cur));
+        const LdsImages p = (LdsImages)(uintptr_t)cur;
+        AxisImage e;
+        e.key = p->key;
+        e.aux = p->aux;
         const double d2 = __dadd_rn(a, e.key);
         float y;
-        const int idx = tap_index(w, d2, y);
-        deposit<COUNT>(w, idx, (__int_as_float(e.aux) * y) * cxy, hist, hist32);
+        const int slot = tap_slot(w, d2, y);
+        deposit<COUNT>(w, slot, (__int_as_float(e.aux) * y) * cxy, hist, hist32);
     }
 }
 
@@ -328,10 +343,10 @@ __device__ __attribute__((noinline)) void walk_column_direct(const WalkCtx w, co
             const double dz = axis_delta(az, q, n);
             const double d2 = __dadd_rn(a, __dmul_rn(dz, dz));
             float y;
-            const int idx = tap_index(w, d2, y);
+            const int slot = tap_slot(w, d2, y);
             float bz = 0.f;
             if (!COUNT) bz = beta_pow_slow(w.beta, iabs(n - q) + iabs(n));
-            deposit<COUNT>(w, idx, (bz * y) * cxy, hist, hist32);
+            deposit<COUNT>(w, slot, (bz * y) * cxy, hist, hist32);
         }
 }
 
@@ -436,7 +451,7 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
     const float* __restrict__ geom, int rir_len, double k_fs_c, const Item* __restrict__ items,
     int* __restrict__ ctrl, const float* __restrict__ pow_table, float* __restrict__ rir_out,
     int32_t* __restrict__ cnt_out) {
-    __shared__ unsigned long long hist[COUNT ? kMaxTaps / 2 : kMaxTaps];
+    __shared__ unsigned long long hist[(COUNT ? kMaxTaps / 2 : kMaxTaps) + 1];     // slot 0 is never read
     __shared__ float bpow[COUNT ? 1 : kPow];
     __shared__ AxisImage ztab[2 * kAxisCap];       // z images sorted by dz*dz
     __shared__ AxisImage ytab[2 * kAxisCap];       // y images sorted by dy*dy
@@ -459,9 +474,9 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
         const float* g = geom + (size_t)item.rir * 10;
 
         if (COUNT) {
-            for (int i = tid; i < n_taps; i += kThreads) hist32[i] = 0u;
+            for (int i = tid; i <= n_taps; i += kThreads) hist32[i] = 0u;
         } else {
-            for (int i = tid; i < n_taps; i += kThreads) hist[i] = 0ull;
+            for (int i = tid; i <= n_taps; i += kThreads) hist[i] = 0ull;
             for (int i = tid; i < kPow; i += kThreads) bpow[i] = pow_table[(size_t)item.rir * kPow + i];
         }
         __syncthreads();
@@ -490,9 +505,11 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
             Column* wc = cols[wave];
             WalkCtx wctx;
             wctx.k_fs_c = k_fs_c;
-            wctx.guard = 1e-12 * (double)(n1 + 1) + 1e-13;
-            wctx.n0 = n0;
-            wctx.n_taps = n_taps;
+            const double guard = 1e-12 * (double)(n1 + 1) + 1e-13;
+            wctx.shift = (0.5 + guard) - (double)(n0 - 1);
+            wctx.guard2 = 2.0 * guard;
+            wctx.n0m1 = n0 - 1;
+            wctx.n_slots = (unsigned int)n_taps + 1u;
             wctx.beta = beta;
             const float y0_max = fmaxf(fabsf((float)(ay.src - ay.mic)), fabsf((float)(ay.src + ay.mic)));
             const float z0_max = fmaxf(fabsf((float)(az.src - az.mic)), fabsf((float)(az.src + az.mic)));
@@ -631,11 +648,11 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
 
         if (COUNT) {
             int32_t* out = cnt_out + (size_t)item.rir * rir_len + n0;
-            for (int i = tid; i < n_taps; i += kThreads) out[i] = (int32_t)hist32[i];
+            for (int i = tid; i < n_taps; i += kThreads) out[i] = (int32_t)hist32[i + 1];
         } else {
             float* out = rir_out + (size_t)item.rir * rir_len + n0;
             for (int i = tid; i < n_taps; i += kThreads) {
-                const unsigned long long v = hist[i];
+                const unsigned long long v = hist[i + 1];
                 const double d = (double)(unsigned int)(v >> 32) * 4294967296.0 + (double)(unsigned int)v;
                 out[i] = (float)(d * 1.3877787807814457e-17);       // 2^-56
             }
