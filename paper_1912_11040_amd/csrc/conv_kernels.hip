@@ -190,22 +190,32 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
         asm volatile("" : "+v"(tid_p));
         const int k2 = tid_p % (M / 2), half = tid_p / (M / 2);
         const int w0 = (wb - 1) * N + 2 * tid_p;           // first sample of this thread in the window (may be < 0)
-        if (wb >= 1 && (wb + 1) * (int64_t)N <= len) {
-            // the whole window lies inside the utterance (the same for every thread of the group): sixteen
-            // two-sample loads with nothing to test, issued back to back
-            const float* xw = x + w0;
+        // The window is block wb - 1 followed by block wb.  The first is a whole block of the utterance or
+        // (wb = 0) lies before its start; the second is whole except at the utterance's end.  Whole blocks
+        // are read with two-sample loads and nothing to test, the same for every thread of the group.
+        const float* xw = x + w0;
+        if (wb >= 1) {
 #pragma unroll
-            for (int n1 = 0; n1 < 16; ++n1) {
+            for (int n1 = 0; n1 < 8; ++n1) {
                 const SamplePair s2 = *reinterpret_cast<const SamplePair*>(xw + 2 * M * n1);
                 v[n1] = make_float2(s2.x, s2.y);
             }
         } else {
 #pragma unroll
-            for (int n1 = 0; n1 < 16; ++n1) {
-                const int g = w0 + 2 * M * n1;
-                // unsigned compares fold the g >= 0 test in
-                const float x0 = (unsigned)g < (unsigned)len ? x[g] : 0.f;
-                const float x1 = (unsigned)(g + 1) < (unsigned)len ? x[g + 1] : 0.f;
+            for (int n1 = 0; n1 < 8; ++n1) v[n1] = make_float2(0.f, 0.f);
+        }
+        if ((wb + 1) * (int64_t)N <= len) {
+#pragma unroll
+            for (int n1 = 8; n1 < 16; ++n1) {
+                const SamplePair s2 = *reinterpret_cast<const SamplePair*>(xw + 2 * M * n1);
+                v[n1] = make_float2(s2.x, s2.y);
+            }
+        } else {
+#pragma unroll
+            for (int n1 = 8; n1 < 16; ++n1) {
+                const int g = w0 + 2 * M * n1;                     // >= 0 in this half
+                const float x0 = g < len ? x[g] : 0.f;
+                const float x1 = g + 1 < len ? x[g + 1] : 0.f;
                 v[n1] = make_float2(x0, x1);
             }
         }
