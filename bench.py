@@ -36,9 +36,9 @@ RIR_FLOP_PER_IMAGE = 12.0     # 2 add, sqrt, mul, add, floor, table product, div
 # runs summarised in profiles/hbm_traffic_<workload>.md, scaled there by a 1 GiB copy.  They describe the
 # kernel sources with this digest only; for any other sources `traffic` is reported as null.
 RECORDED_TRAFFIC = {
-    "digest": "4762a08df0848850",
-    "varlen": {"rir": 139247720, "rir_spectrum": 202534623, "convolve": 1272214593, "mel": 627036052},
-    "throughput": {"rir": 740230960, "rir_spectrum": 1220458604, "convolve": 5728436880, "mel": 2221194030},
+    "digest": "0cfbf2ec4f706c26",
+    "varlen": {"rir": 124206024, "rir_spectrum": 202541643, "convolve": 1330361433, "mel": 627087549},
+    "throughput": {"rir": 672419566, "rir_spectrum": 1220132549, "convolve": 5675457889, "mel": 2221217745},
 }
 
 
