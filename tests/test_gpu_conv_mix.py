@@ -119,6 +119,23 @@ def test_three_noise_sources_16000_taps(aug):
     _check(aug, offsets, speech, noise, rir, snr)
 
 
+def test_whole_blocks_and_odd_starts_at_the_largest_transform(aug):
+    # 16384-sample blocks: utterances that are exact multiples of the block (every window and output block
+    # takes the untested two-sample path), one sample more, one sample in all, and odd start offsets, where
+    # those 8-byte accesses are only 4-byte aligned
+    rng = np.random.default_rng(13)
+    lens = [16385, 32768, 1, 16384, 49155]
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    assert offsets[1] % 2 == 1 and offsets[3] % 2 == 0 and offsets[4] % 2 == 0
+    total = int(offsets[-1])
+    speech = rng.standard_normal(total).astype(np.float32)
+    noise = rng.standard_normal((1, total)).astype(np.float32)
+    rir = _decaying_rirs(rng, len(lens), 2, 9000)
+    snr = rng.uniform(0, 30, (len(lens), 1)).astype(np.float32)
+    print("case: L=9000, whole 16384-sample blocks, odd starts", flush=True)
+    _check(aug, offsets, speech, noise, rir, snr)
+
+
 def test_most_noise_sources_the_interface_takes(aug):
     rng = np.random.default_rng(12)
     lens = [1500, 0, 2600, 700]
