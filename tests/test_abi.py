@@ -69,8 +69,17 @@ def test_feature_dim_helper(lib):
 
 def test_null_context_is_rejected(lib):
     assert lib.aug_rir_batch(None, 1, None, 16, 16000.0, 343.0, None, None) == binding.AUG_ERR_INVALID_ARG
+    assert lib.aug_rir_mics_batch(None, 1, 2, None, None, 16, 16000.0, 343.0, None, None) == binding.AUG_ERR_INVALID_ARG
+    assert lib.aug_vtlp_resynth_batch(None, 0, None, None, None, None, None) == binding.AUG_ERR_INVALID_ARG
     assert lib.aug_destroy(None) == binding.AUG_OK
     assert lib.aug_last_error(None) == b"context is null"
+
+
+def test_limits_in_the_header_match_the_binding():
+    text = open(os.path.join(ROOT, "include", "aug.h")).read()
+    limit = lambda name: int(re.search(r"#define\s+" + name + r"\s+(\d+)", text).group(1))
+    assert limit("AUG_MAX_RIR_LEN") == 32768 and limit("AUG_MAX_NOISE") == 8
+    assert limit("AUG_MAX_MEL") == 128 and limit("AUG_MAX_MIC") == 16 and limit("AUG_MAX_UTT") == 65535
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
