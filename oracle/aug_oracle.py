@@ -20,8 +20,11 @@ numpy's FFT as a library step for sizes where the direct sums would take
 hours; tests tie them to the direct forms on small shapes.
 
 Every function below is pinned by CPU tests against closed forms or
-independent formulas (none is "parity unpinned"); the end-to-end pipeline has
-no printed value in the paper and is pinned piecewise only.
+independent formulas (none is "parity unpinned").  The paper prints no
+end-to-end value; the composition `pipeline_batch` is pinned by the closed
+form that rooms without reflections give (every response a single impulse
+1/(4 pi r): the mixture is a sum of shifted, scaled inputs whose delays,
+amplitudes, energies and gains can be worked out by hand).
 """
 from __future__ import annotations
 
