@@ -232,7 +232,7 @@ typedef struct aug_vtlp_cfg {
 
 /*
  * VTLP on the waveform by resynthesis, the step the paper places before the
- * acoustic simulator (Sec. 2.3, Eq. (1); window length from Sec. 3).
+ * acoustic simulator (Sec. 2.3, Eq. (1); window length from Sec. 4, Table 2).
  *
  *   offsets   HOST int64 [n_utt+1] as above.
  *   wave      DEVICE float [total].

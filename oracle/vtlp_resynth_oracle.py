@@ -5,7 +5,7 @@ the acoustic simulator: the signal is analysed in short frames, each frame's
 spectrum is moved along the frequency axis by the bilinear rule of Eq. (1) with
 one warp factor per utterance, and the frames are put back together by
 overlap-add.  The paper fixes Eq. (1), omega_k = 2 pi k / K, the per-utterance
-factor and (Sec. 3) the best window length, 50 ms; the rest of the algorithm is
+factor and (Sec. 4, Table 2) the best window length, 50 ms; the rest of the algorithm is
 in a cited paper only, so the steps below are readings, each stated where it is
 taken:
 
@@ -27,7 +27,9 @@ taken:
        frame's position; no synthesis window, no gain correction; the output has
        the input's length.  alpha = 1 therefore returns the input.
 
-Everything is fp64 NumPy; numpy's FFT is used as a library step.  Pins are in
+Everything is fp64 NumPy.  `method="dft"` writes the K-point transform pair of
+V-2 / V-4 out as the sums that define it; the default `method="fft"` calls
+numpy's FFT as a library step (a test ties the two together).  Pins are in
 tests/test_oracle_vtlp_resynth.py (inverse warp against Eq. (1) itself, identity
 at alpha = 1, where a pure tone lands, linearity, hop-shift covariance); no
 function here is "parity unpinned".  Only tests, the smoke check and the
@@ -39,7 +41,7 @@ from __future__ import annotations
 import numpy as np
 
 __all__ = ["hann_periodic", "resynth_frame_count", "inverse_warp", "source_bins",
-           "warp_spectrum", "vtlp_resynth", "vtlp_resynth_batch"]
+           "warp_spectrum", "dft_half", "idft_real", "vtlp_resynth", "vtlp_resynth_batch"]
 
 
 def hann_periodic(win: int):
@@ -75,7 +77,25 @@ def warp_spectrum(X, alpha, nfft: int):
     return (1.0 - f) * X[j] + f * X[j + 1]
 
 
-def vtlp_resynth(x, alpha, win: int = 800, nfft: int = 2048):
+def dft_half(g):
+    """X[k] = sum_n g[n] exp(-2 pi i k n / K), k = 0..K/2, as the sum itself (V-2)."""
+    g = np.asarray(g, dtype=np.float64)
+    nfft = g.shape[0]
+    k = np.arange(nfft // 2 + 1, dtype=np.float64)[:, None]
+    n = np.arange(nfft, dtype=np.float64)[None, :]
+    return np.exp(-2j * np.pi * k * n / nfft) @ g
+
+
+def idft_real(Y, nfft: int):
+    """y[n] = Re (1/K) sum_{k<K} Z[k] exp(+2 pi i k n / K), Z the Hermitian extension of Y[0..K/2] (V-4)."""
+    Y = np.asarray(Y, dtype=np.complex128)
+    Z = np.concatenate([Y, np.conj(Y[-2:0:-1])])
+    k = np.arange(nfft, dtype=np.float64)[None, :]
+    n = np.arange(nfft, dtype=np.float64)[:, None]
+    return np.real(np.exp(2j * np.pi * k * n / nfft) @ Z) / nfft
+
+
+def vtlp_resynth(x, alpha, win: int = 800, nfft: int = 2048, method: str = "fft"):
     """One utterance through analysis, warp and overlap-add (V-1 .. V-4)."""
     x = np.asarray(x, dtype=np.float64)
     n = x.shape[0]
@@ -92,8 +112,10 @@ def vtlp_resynth(x, alpha, win: int = 800, nfft: int = 2048):
         g = np.zeros(nfft, dtype=np.float64)
         g[:half] = frame[half:]                  # offsets 0 .. W/2 - 1
         g[nfft - half:] = frame[:half]           # offsets -W/2 .. -1
-        Y = warp_spectrum(np.fft.rfft(g), alpha, nfft)
-        y = np.fft.irfft(Y, nfft)
+        if method == "dft":
+            y = idft_real(warp_spectrum(dft_half(g), alpha, nfft), nfft)
+        else:
+            y = np.fft.irfft(warp_spectrum(np.fft.rfft(g), alpha, nfft), nfft)
         pos = centre + tau
         ok = (pos >= 0) & (pos < n)
         out[pos[ok]] += y[tau[ok] % nfft]

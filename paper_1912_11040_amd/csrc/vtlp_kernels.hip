@@ -4,7 +4,7 @@
 // acoustic simulator then takes as its input.
 //
 // What the paper leaves to a cited work is fixed as follows.  Frames of 800 samples (50 ms, the best
-// window length of Sec. 3) under the periodic Hann window, every 400 samples, frame t centred on sample
+// window length of Sec. 4, Table 2) under the periodic Hann window, every 400 samples, frame t centred on sample
 // 400 t, so that each sample lies in two frames whose weights add up to one.  The frame is laid out
 // around time zero of a 2048-point transform.  Output bin k' reads the input spectrum, by linear
 // interpolation between the two nearest bins, at the frequency that Eq. (1) maps onto k':

@@ -111,3 +111,18 @@ def test_batch_is_per_utterance():
         np.testing.assert_array_equal(y[off[u]:off[u + 1]], V.vtlp_resynth(x[off[u]:off[u + 1]], alpha[u]))
     # noise keeps roughly its level
     assert 0.7 <= np.sqrt(np.mean(y[off[3]:] ** 2)) / np.sqrt(np.mean(x[off[3]:] ** 2)) <= 1.1
+
+
+def test_direct_dft_form_equals_the_fft_form():
+    """The transform pair written out as sums (2048 points) gives what the library FFT gives."""
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal(1300)
+    for alpha in (0.8, 1.2):
+        a = V.vtlp_resynth(x, alpha, method="dft")
+        b = V.vtlp_resynth(x, alpha, method="fft")
+        np.testing.assert_allclose(a, b, atol=1e-11)
+    # the sums themselves: a unit impulse at n0 has the spectrum exp(-2 pi i k n0 / K), and comes back
+    g = np.zeros(2048); g[5] = 1.0
+    X = V.dft_half(g)
+    np.testing.assert_allclose(X, np.exp(-2j * np.pi * np.arange(1025) * 5 / 2048), atol=1e-12)
+    np.testing.assert_allclose(V.idft_real(X, 2048), g, atol=1e-12)
