@@ -126,12 +126,92 @@ def _ptr(t, dtype=None):
     return ctypes.c_void_p(t.data_ptr())
 
 
+def _numel(t) -> int:
+    return 0 if t is None else int(t.numel())
+
+
+def _need(name: str, t, count: int, exact: bool = False):
+    """Raise ValueError unless tensor `t` holds at least (exactly) `count` elements; None counts as empty."""
+    have = _numel(t)
+    if (have != count) if exact else (have < count):
+        raise ValueError(f"{name} holds {have} elements, the call needs {'exactly' if exact else 'at least'} {count}")
+
+
+# Element counts that the C ABI takes on trust (it sees bare addresses): checked here, on the host, before
+# anything is launched.  An undersized output would otherwise be written past its end by a kernel.
+
+def check_offsets_pair(off: np.ndarray, foff: Optional[np.ndarray] = None):
+    if off.ndim != 1 or len(off) < 1:
+        raise ValueError("offsets must be a one-dimensional array of n_utt + 1 entries")
+    if foff is not None and len(foff) != len(off):
+        raise ValueError(f"frame_offsets has {len(foff)} entries, offsets has {len(off)}")
+
+
+def check_rir_sizes(geom, rir_len: int, rir_out, tap_count_out, mics=None, n_mic: int = 1):
+    if _numel(geom) % 10:
+        raise ValueError("geom must hold 10 values per response")
+    n_rir = _numel(geom) // 10
+    if mics is not None:
+        _need("mics", mics, n_rir * n_mic * 3, exact=True)
+    _need("rir_out", rir_out, n_rir * n_mic * int(rir_len))
+    if tap_count_out is not None:
+        _need("tap_count_out", tap_count_out, n_rir * n_mic * int(rir_len))
+
+
+def check_mix_sizes(off: np.ndarray, speech, n_noise: int, noise, snr_db, gains_out=None):
+    n_utt, total = len(off) - 1, int(off[-1])
+    _need("speech", speech, total)
+    _need("noise", noise, n_noise * total)
+    _need("snr_db", snr_db, n_utt * n_noise)
+    if gains_out is not None:
+        _need("gains_out", gains_out, n_utt * n_noise)
+
+
+def check_convolve_mix_sizes(off: np.ndarray, speech, n_noise: int, noise, rir, rir_len: int, snr_db, mixed_out,
+                             gains_out=None):
+    check_offsets_pair(off)
+    check_mix_sizes(off, speech, n_noise, noise, snr_db, gains_out)
+    _need("rir", rir, (len(off) - 1) * (1 + n_noise) * int(rir_len))
+    _need("mixed_out", mixed_out, int(off[-1]))
+
+
+def check_mel_sizes(off: np.ndarray, foff: np.ndarray, wave, alpha, feats_out, feature_dim: int):
+    check_offsets_pair(off, foff)
+    _need("wave", wave, int(off[-1]))
+    _need("alpha", alpha, len(off) - 1)
+    _need("feats_out", feats_out, int(foff[-1]) * int(feature_dim))
+
+
+def check_pipeline_sizes(off: np.ndarray, foff: np.ndarray, speech, n_noise: int, noise, geom, rir_len: int,
+                         snr_db, alpha, feature_dim: int, feats_out, rir_out=None, mixed_out=None, gains_out=None):
+    check_offsets_pair(off, foff)
+    n_utt = len(off) - 1
+    check_mix_sizes(off, speech, n_noise, noise, snr_db, gains_out)
+    _need("geom", geom, n_utt * (1 + n_noise) * 10, exact=True)
+    _need("alpha", alpha, n_utt)
+    _need("feats_out", feats_out, int(foff[-1]) * int(feature_dim))
+    if rir_out is not None:
+        _need("rir_out", rir_out, n_utt * (1 + n_noise) * int(rir_len))
+    if mixed_out is not None:
+        _need("mixed_out", mixed_out, int(off[-1]))
+
+
+def check_resynth_sizes(off: np.ndarray, wave, alpha, wave_out):
+    check_offsets_pair(off)
+    _need("wave", wave, int(off[-1]))
+    _need("alpha", alpha, len(off) - 1)
+    _need("wave_out", wave_out, int(off[-1]))
+
+
 class Augmenter:
     """One library context bound to a device and a stream (torch's current stream by default)."""
 
-    def __init__(self, device: int = 0, stream=None):
+    def __init__(self, device: int = 0, stream=None, check_sizes: bool = True):
+        """check_sizes=False skips the host-side element-count checks of the tensors (the library still
+        validates everything it can see: nulls, sizes, offsets)."""
         import torch
         self._lib = load_library()
+        self._check_sizes = bool(check_sizes)
         if stream is None:
             stream = torch.cuda.current_stream(device)
         self.stream = stream
@@ -177,6 +257,8 @@ class Augmenter:
 
     def aug_rir_batch(self, geom, rir_len: int, fs: float, c: float, rir_out, tap_count_out=None):
         import torch
+        if self._check_sizes:
+            check_rir_sizes(geom, rir_len, rir_out, tap_count_out)
         n_rir = int(geom.numel() // 10) if geom is not None else 0
         self._check(self._lib.aug_rir_batch(
             self._h, n_rir, _ptr(geom, torch.float32), int(rir_len), float(fs), float(c),
@@ -189,6 +271,8 @@ class Augmenter:
         n_rir = int(geom.numel() // 10) if geom is not None else 0
         if n_mic is None:
             n_mic = int(mics.shape[-2]) if mics is not None and mics.dim() >= 2 else 0
+        if self._check_sizes:
+            check_rir_sizes(geom, rir_len, rir_out, tap_count_out, mics, int(n_mic))
         self._check(self._lib.aug_rir_mics_batch(
             self._h, n_rir, int(n_mic), _ptr(geom, torch.float32), _ptr(mics, torch.float32), int(rir_len),
             float(fs), float(c), _ptr(rir_out, torch.float32), _ptr(tap_count_out, torch.int32)))
@@ -199,6 +283,8 @@ class Augmenter:
         off = _host_i64(offsets)
         if n_noise is None:
             n_noise = 0 if noise is None else int(noise.shape[0])
+        if self._check_sizes:
+            check_convolve_mix_sizes(off, speech, int(n_noise), noise, rir, rir_len, snr_db, mixed_out, gains_out)
         self._check(self._lib.aug_convolve_mix_batch(
             self._h, len(off) - 1, off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
             _ptr(speech, torch.float32), int(n_noise), _ptr(noise, torch.float32),
@@ -210,6 +296,8 @@ class Augmenter:
         off = _host_i64(offsets)
         foff = _host_i64(frame_offsets)
         c = cfg if isinstance(cfg, FrontendCfg) else FrontendCfg.of(cfg)
+        if self._check_sizes:
+            check_mel_sizes(off, foff, wave, alpha, feats_out, self._lib.aug_feature_dim(ctypes.byref(c)))
         self._check(self._lib.aug_vtlp_mel_batch(
             self._h, len(off) - 1, off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
             _ptr(wave, torch.float32), _ptr(alpha, torch.float32), ctypes.byref(c),
@@ -220,6 +308,8 @@ class Augmenter:
         import torch
         off = _host_i64(offsets)
         c = VtlpCfg(int(win), int(hop), int(nfft))
+        if self._check_sizes:
+            check_resynth_sizes(off, wave, alpha, wave_out)
         self._check(self._lib.aug_vtlp_resynth_batch(
             self._h, len(off) - 1, off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
             _ptr(wave, torch.float32), _ptr(alpha, torch.float32), ctypes.byref(c),
@@ -234,6 +324,10 @@ class Augmenter:
         fc = cfg if isinstance(cfg, FrontendCfg) else FrontendCfg.of(cfg)
         if n_noise is None:
             n_noise = 0 if noise is None else int(noise.shape[0])
+        if self._check_sizes:
+            check_pipeline_sizes(off, foff, speech, int(n_noise), noise, geom, rir_len, snr_db, alpha,
+                                 self._lib.aug_feature_dim(ctypes.byref(fc)), feats_out, rir_out, mixed_out,
+                                 gains_out)
         self._check(self._lib.aug_pipeline_batch(
             self._h, len(off) - 1, off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
             _ptr(speech, torch.float32), int(n_noise), _ptr(noise, torch.float32),

@@ -13,7 +13,8 @@ pytestmark = pytest.mark.gpu
 
 @pytest.fixture(scope="module")
 def aug():
-    a = binding.Augmenter(0)
+    # the binding's own element-count checks are off here: these tests are about what the library itself refuses
+    a = binding.Augmenter(0, check_sizes=False)
     yield a
     a.close()
 
@@ -80,3 +81,15 @@ def test_bad_device_is_rejected():
     h = ctypes.c_void_p()
     assert lib.aug_create(ctypes.byref(h), 99, None) == binding.AUG_ERR_INVALID_ARG
     assert not h.value
+
+
+def test_binding_refuses_short_tensors_before_the_library_sees_them():
+    import torch
+    g = dev(W.tiny(n_utt=1).geom)
+    with binding.Augmenter(0) as a:
+        with pytest.raises(ValueError, match="rir_out"):
+            a.aug_rir_batch(g, 64, 16000.0, 343.0, torch.zeros(2 * 64 - 1, device="cuda"))
+        x = torch.zeros(1000, device="cuda")
+        with pytest.raises(ValueError, match="frame_offsets"):
+            a.aug_vtlp_mel_batch([0, 600, 1000], x, torch.ones(2, device="cuda"), W.FrontendConfig(), [0, 2],
+                                 torch.zeros(8, 40, device="cuda"))
