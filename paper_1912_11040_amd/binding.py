@@ -151,11 +151,12 @@ def check_rir_sizes(geom, rir_len: int, rir_out, tap_count_out, mics=None, n_mic
     if _numel(geom) % 10:
         raise ValueError("geom must hold 10 values per response")
     n_rir = _numel(geom) // 10
+    n_mic, rir_len = max(int(n_mic), 0), max(int(rir_len), 0)      # the library refuses the negative ones itself
     if mics is not None:
-        _need("mics", mics, n_rir * n_mic * 3, exact=True)
-    _need("rir_out", rir_out, n_rir * n_mic * int(rir_len))
+        _need("mics", mics, n_rir * n_mic * 3)
+    _need("rir_out", rir_out, n_rir * n_mic * rir_len)
     if tap_count_out is not None:
-        _need("tap_count_out", tap_count_out, n_rir * n_mic * int(rir_len))
+        _need("tap_count_out", tap_count_out, n_rir * n_mic * rir_len)
 
 
 def check_mix_sizes(off: np.ndarray, speech, n_noise: int, noise, snr_db, gains_out=None):

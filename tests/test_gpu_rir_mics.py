@@ -85,8 +85,10 @@ def binding_max_mic():
     return int(re.search(r"#define\s+AUG_MAX_MIC\s+(\d+)", open(os.path.join(root, "include", "aug.h")).read()).group(1))
 
 
-def test_argument_errors(aug):
+def test_argument_errors():
     import torch
+    # the binding's own element-count checks are off: this test is about what the library itself refuses
+    aug = binding.Augmenter(0, check_sizes=False)
     g = torch.zeros(1, 10, device="cuda")
     m = torch.zeros(1, 2, 3, device="cuda")
     out = torch.zeros(1, 2, 16, device="cuda")
@@ -107,3 +109,4 @@ def test_argument_errors(aug):
     aug.aug_rir_mics_batch(g, m, 16, FS, C, out)
     torch.cuda.synchronize()
     assert np.all(out.cpu().numpy() == 0.0)
+    aug.close()
