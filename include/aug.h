@@ -16,16 +16,29 @@
  *     keeps them.  Pointers marked HOST are ordinary host memory, read before
  *     the call returns.
  *   - Work is enqueued on the context's HIP stream and the call returns
- *     without waiting for it; the caller synchronises that stream before
- *     reading outputs.  Calls on one context must not overlap in time from
- *     several host threads.
+ *     without waiting for it, also when the batch's offsets differ from the
+ *     previous call's (they reach the device through pinned staging and
+ *     asynchronous copies, and the work-item tables are rebuilt there by small
+ *     kernels); the caller synchronises that stream before reading outputs.
+ *     HOST arrays are free for reuse as soon as the call returns.  Calls on one
+ *     context must not overlap in time from several host threads.
  *   - The context owns a private device workspace (impulse-response spectra,
  *     reverberated signals, energies, warp tables); it grows on demand and is
- *     released by aug_destroy.
+ *     released by aug_destroy.  Growing frees the old allocation, which waits
+ *     for the work that uses it: only calls larger than any before them wait.
+ *   - HIP graphs: a call whose sizes and offsets equal those of the previous
+ *     call on the context consists of kernel launches only and may be captured
+ *     from the context's stream into a graph.  Capture it only after one
+ *     identical, uncaptured call.  The graph holds addresses of the workspace:
+ *     destroy it before any call with larger sizes or other offsets (which may
+ *     move or rewrite the workspace) and before aug_destroy.  A call that would
+ *     have to allocate, copy offsets or rebuild tables while its stream is
+ *     being captured returns AUG_ERR_UNSUPPORTED instead.
  *   - Every function returns AUG_OK (0) or a negative aug_status; nothing is
  *     thrown across the boundary.  aug_last_error gives the message of the
- *     last failure on that context.  Arguments are checked on the host before
- *     anything is launched; a failed call launches nothing.
+ *     last failure on that context.  Arguments are checked on the host, and the
+ *     workspace is sized, before the first kernel of a call: a call that fails
+ *     a check or runs out of memory has launched nothing.
  *   - A pointer to an array that has no elements in this call (a batch with no
  *     utterances or no samples, an output with no rows) may be NULL; any other
  *     NULL that the argument lists below do not allow is AUG_ERR_INVALID_ARG.
@@ -152,11 +165,10 @@ int aug_rir_mics_batch(aug_ctx* ctx, int n_rir, int n_mic, const float* geom, co
  *               length kept, the tail past the end is dropped),
  *               E_j = sum_n y_j[n]^2,  g_j = sqrt(E_0 / (E_j 10^(snr_j/10)))
  *               (0 if E_0 or E_j is 0),  mixed = y_0 + sum_j g_j y_j.
- *               An energy counts as 0 when it is below 1e-10 of (energy of
- *               x_j) * (energy of h_j): where the exact y_j is zero (the
- *               utterance ends before the response's first tap) the transforms
- *               leave rounding noise, not a signal.  Samples before the
- *               first non-zero tap of h_j are written as exact zeros.
+ *               Samples before the first non-zero tap of h_j are exact
+ *               zeros (the transforms alone would leave rounding noise
+ *               there), so a source whose direct path arrives after the
+ *               utterance has ended has energy 0 and gain 0.
  *   gains_out   DEVICE float [n_utt][n_noise] or NULL: the g_j.
  */
 int aug_convolve_mix_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets,

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libaug.so")
-SOURCES = ["aug_api.hip", "rir_kernels.hip", "conv_kernels.hip", "mel_kernels.hip", "vtlp_kernels.hip"]
+SOURCES = ["aug_api.hip", "pack_kernels.hip", "rir_kernels.hip", "conv_kernels.hip", "mel_kernels.hip", "vtlp_kernels.hip"]
 
 # Packed-FP32 instructions are switched off for every kernel; the image-sum file is
 # also built without FMA contraction because its tap index must follow a fixed fp64

@@ -128,60 +128,126 @@ int check_frame_offsets(aug_ctx* ctx, int n_utt, const int64_t* offsets, const i
     return AUG_OK;
 }
 
-// Device copies of the offsets and the (utterance, block) / (utterance, frame group) tables.
-// Rebuilt only when the host arrays differ from the cached ones.
+// Grow one of the context's device buffers.  Growing frees the old allocation (which waits for the work
+// that uses it) and allocates: neither may happen while the stream is being captured into a graph.
+int grow(aug_ctx* ctx, DeviceBuffer& b, size_t bytes, const char* what) {
+    if (bytes <= b.bytes) return AUG_OK;
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(ctx->stream, &st) != hipSuccess) (void)hipGetLastError();
+    if (st != hipStreamCaptureStatusNone)
+        return fail(ctx, AUG_ERR_UNSUPPORTED, "%s would have to grow while the stream is being captured: "
+                    "run the same call once before capturing it", what);
+    hipError_t e = b.reserve(bytes);
+    if (e != hipSuccess) return fail_hip(ctx, e, what);
+    return AUG_OK;
+}
+
+// Pinned staging slots of at least `entries` int64 each, with their events.
+int ring_reserve(aug_ctx* ctx, size_t entries) {
+    aug::HostRing& r = ctx->ring;
+    if (entries <= r.cap) return AUG_OK;
+    for (int i = 0; i < aug::HostRing::kSlots; ++i) {
+        if (r.done[i]) AUG_HIP(hipEventSynchronize(r.done[i]), "staging event wait");
+        if (r.slot[i]) {
+            AUG_HIP(hipHostFree(r.slot[i]), "staging free");
+            r.slot[i] = nullptr;
+        }
+    }
+    r.cap = 0;
+    const size_t want = entries + entries / 4 + 64;
+    for (int i = 0; i < aug::HostRing::kSlots; ++i) {
+        AUG_HIP(hipHostMalloc(reinterpret_cast<void**>(&r.slot[i]), want * sizeof(int64_t), hipHostMallocDefault),
+                "pinned staging buffer");
+        if (!r.done[i]) AUG_HIP(hipEventCreateWithFlags(&r.done[i], hipEventDisableTiming), "staging event");
+    }
+    r.cap = want;
+    return AUG_OK;
+}
+
+// Copy up to two host arrays of n int64 each to the device through the next staging slot, without waiting
+// for the stream: the slot is reused only after this copy has run (its event).  A null array is skipped.
+int upload_offsets(aug_ctx* ctx, size_t n, const int64_t* a, int64_t* d_a, const int64_t* b, int64_t* d_b) {
+    aug::HostRing& r = ctx->ring;
+    const int i = r.next;
+    AUG_HIP(hipEventSynchronize(r.done[i]), "staging event wait");     // an unrecorded event counts as complete
+    if (a) {
+        memcpy(r.slot[i], a, n * sizeof(int64_t));
+        AUG_HIP(hipMemcpyAsync(d_a, r.slot[i], n * sizeof(int64_t), hipMemcpyHostToDevice, ctx->stream), "offsets copy");
+    }
+    if (b) {
+        memcpy(r.slot[i] + n, b, n * sizeof(int64_t));
+        AUG_HIP(hipMemcpyAsync(d_b, r.slot[i] + n, n * sizeof(int64_t), hipMemcpyHostToDevice, ctx->stream),
+                "frame offsets copy");
+    }
+    AUG_HIP(hipEventRecord(r.done[i], ctx->stream), "staging event record");
+    r.next = (i + 1) % aug::HostRing::kSlots;
+    return AUG_OK;
+}
+
+// Device copies of the offsets and the (utterance, block) / (utterance, frame group) tables.  When the host
+// arrays equal the previous call's nothing is done (a steady-state call is kernel launches only).  Otherwise
+// the arrays go to the device through pinned staging with asynchronous copies and the tables are rebuilt
+// there by two small kernels, all in stream order behind the earlier calls' kernels: the call does not
+// wait for the stream.  The host only counts the items (one pass over the utterances) to size the grids.
 int sync_packing(aug_ctx* ctx, int n_utt, const int64_t* offsets, const int64_t* frame_offsets,
                  int conv_block, int frames_per_group) {
     aug::Packing& pk = ctx->packing;
     const size_t n = (size_t)n_utt + 1;
     const bool same_off = pk.offsets.size() == n && !memcmp(pk.offsets.data(), offsets, n * sizeof(int64_t));
     const bool need_conv = conv_block > 0 && !(same_off && pk.conv_block == conv_block);
-    const bool same_fr = !frame_offsets || (same_off && pk.frame_offsets.size() == n &&
+    const bool need_fr = frame_offsets && !(same_off && pk.frame_offsets.size() == n &&
                           !memcmp(pk.frame_offsets.data(), frame_offsets, n * sizeof(int64_t)) &&
                           pk.frames_per_group == frames_per_group);
-    if (same_off && !need_conv && same_fr) return AUG_OK;
+    if (same_off && !need_conv && !need_fr) return AUG_OK;
 
-    // earlier work may still read the old tables
-    AUG_HIP(hipStreamSynchronize(ctx->stream), "stream synchronize");
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(ctx->stream, &st) != hipSuccess) (void)hipGetLastError();
+    if (st != hipStreamCaptureStatusNone)
+        return fail(ctx, AUG_ERR_UNSUPPORTED, "the offsets differ from the previous call's: the tables cannot be "
+                    "rebuilt while the stream is being captured (run the same call once before capturing it)");
+
+    int64_t n_conv = 0, n_groups = 0;
+    if (need_conv)
+        for (int u = 0; u < n_utt; ++u) n_conv += (offsets[u + 1] - offsets[u] + conv_block - 1) / conv_block;
+    if (need_fr)
+        for (int u = 0; u < n_utt; ++u)
+            n_groups += (frame_offsets[u + 1] - frame_offsets[u] + frames_per_group - 1) / frames_per_group;
+    if (n_conv > 0x7fffffffLL || n_groups > 0x7fffffffLL)
+        return fail(ctx, AUG_ERR_UNSUPPORTED, "too many blocks or frame groups in one call");
+
+    AUG_TRY(grow(ctx, ctx->d_offsets, n * sizeof(int64_t), "offsets buffer"));
+    if (need_conv) {
+        AUG_TRY(grow(ctx, ctx->d_conv_first, n * sizeof(int), "block prefix table"));
+        AUG_TRY(grow(ctx, ctx->d_conv_items, (size_t)std::max<int64_t>(n_conv, 1) * sizeof(int2), "block table"));
+    }
+    if (need_fr) {
+        AUG_TRY(grow(ctx, ctx->d_frame_offsets, n * sizeof(int64_t), "frame offsets buffer"));
+        AUG_TRY(grow(ctx, ctx->d_frame_first, n * sizeof(int), "frame group prefix table"));
+        AUG_TRY(grow(ctx, ctx->d_frame_items, (size_t)std::max<int64_t>(n_groups, 1) * sizeof(int2), "frame group table"));
+    }
+    AUG_TRY(ring_reserve(ctx, 2 * n));
+    if (!same_off || need_fr)
+        AUG_TRY(upload_offsets(ctx, n, same_off ? nullptr : offsets, ctx->d_offsets.as<int64_t>(),
+                               need_fr ? frame_offsets : nullptr, ctx->d_frame_offsets.as<int64_t>()));
+    AUG_HIP(aug::launch_pack(ctx->stream, n_utt, ctx->d_offsets.as<int64_t>(), ctx->d_frame_offsets.as<int64_t>(),
+                             conv_block, frames_per_group,
+                             need_conv ? ctx->d_conv_first.as<int>() : nullptr, ctx->d_conv_items.as<int2>(), n_conv,
+                             need_fr ? ctx->d_frame_first.as<int>() : nullptr, ctx->d_frame_items.as<int2>(), n_groups),
+            "packing kernels");
+
     if (!same_off) {
         pk.offsets.assign(offsets, offsets + n);
-        pk.conv_block = 0;
-        pk.frame_offsets.clear();
-        AUG_HIP(ctx->d_offsets.reserve(n * sizeof(int64_t)), "offsets buffer");
-        AUG_HIP(hipMemcpy(ctx->d_offsets.ptr, offsets, n * sizeof(int64_t), hipMemcpyHostToDevice), "offsets copy");
+        if (!need_conv) pk.conv_block = 0;
+        if (!need_fr) pk.frame_offsets.clear();
     }
-    if (conv_block > 0 && pk.conv_block != conv_block) {
-        std::vector<int2> items;
-        for (int u = 0; u < n_utt; ++u) {
-            const int64_t len = offsets[u + 1] - offsets[u];
-            const int64_t nb = (len + conv_block - 1) / conv_block;
-            for (int64_t b = 0; b < nb; ++b) items.push_back(make_int2(u, (int)b));
-        }
+    if (need_conv) {
         pk.conv_block = conv_block;
-        pk.n_conv_blocks = (int64_t)items.size();
-        if (!items.empty()) {
-            AUG_HIP(ctx->d_conv_items.reserve(items.size() * sizeof(int2)), "block table");
-            AUG_HIP(hipMemcpy(ctx->d_conv_items.ptr, items.data(), items.size() * sizeof(int2), hipMemcpyHostToDevice),
-                    "block table copy");
-        }
+        pk.n_conv_blocks = n_conv;
     }
-    if (frame_offsets && !same_fr) {
+    if (need_fr) {
         pk.frame_offsets.assign(frame_offsets, frame_offsets + n);
         pk.frames_per_group = frames_per_group;
-        std::vector<int2> items;
-        for (int u = 0; u < n_utt; ++u) {
-            const int64_t nf = frame_offsets[u + 1] - frame_offsets[u];
-            for (int64_t f = 0; f < nf; f += frames_per_group) items.push_back(make_int2(u, (int)f));
-        }
-        pk.n_frame_groups = (int64_t)items.size();
-        AUG_HIP(ctx->d_frame_offsets.reserve(n * sizeof(int64_t)), "frame offsets buffer");
-        AUG_HIP(hipMemcpy(ctx->d_frame_offsets.ptr, frame_offsets, n * sizeof(int64_t), hipMemcpyHostToDevice),
-                "frame offsets copy");
-        if (!items.empty()) {
-            AUG_HIP(ctx->d_frame_items.reserve(items.size() * sizeof(int2)), "frame group table");
-            AUG_HIP(hipMemcpy(ctx->d_frame_items.ptr, items.data(), items.size() * sizeof(int2), hipMemcpyHostToDevice),
-                    "frame group table copy");
-        }
+        pk.n_frame_groups = n_groups;
     }
     return AUG_OK;
 }
@@ -191,7 +257,7 @@ int ensure_twiddle(aug_ctx* ctx, int n, const float2** out) {
     while ((1 << lg) < n) ++lg;
     DeviceBuffer& b = ctx->twiddle[lg];
     if (!b.ptr) {
-        AUG_HIP(b.reserve(sizeof(float2) * (size_t)aug::twiddle_entries(n)), "twiddle table");
+        AUG_TRY(grow(ctx, b, sizeof(float2) * (size_t)aug::twiddle_entries(n), "twiddle table"));
         AUG_HIP(aug::launch_twiddle(ctx->stream, n, b.as<float2>()), "twiddle kernel");
     }
     *out = b.as<float2>();
@@ -212,15 +278,50 @@ int mark(aug_ctx* ctx, int stage) {
     return AUG_OK;
 }
 
+// Source j of the reverberated signals starts at j * reverb_stride(total): an even stride keeps the
+// 8-byte loads of the front end aligned for every source.
+int64_t reverb_stride(int64_t total) { return (total + 1) & ~(int64_t)1; }
+
+// ---- workspace of each stage: sized before the first kernel of a call, so that a call that runs out of
+// ---- memory has launched nothing ----
+
+int prepare_rir(aug_ctx* ctx, int n_rir, int rir_len) {
+    AUG_TRY(grow(ctx, ctx->rir_items, 2 * aug::rir_item_bytes() * (size_t)n_rir * aug::rir_items_per_response(rir_len),
+                 "response item table"));
+    AUG_TRY(grow(ctx, ctx->rir_ctrl, aug::rir_ctrl_ints() * sizeof(int), "response item counter"));
+    AUG_TRY(grow(ctx, ctx->rir_pow, sizeof(float) * (size_t)n_rir * aug::rir_pow_entries(), "reflection table"));
+    return AUG_OK;
+}
+
+int prepare_convolve_mix(aug_ctx* ctx, int n_utt, int n_noise, int rir_len) {
+    const int64_t total = ctx->packing.offsets[n_utt];
+    if (n_utt == 0 || total == 0) return AUG_OK;
+    const int n_src = 1 + n_noise;
+    const int fft_n = aug::conv_fft_size(rir_len);
+    const int n_part = (rir_len + fft_n - 1) / fft_n;
+    AUG_TRY(grow(ctx, ctx->rir_spec, sizeof(float2) * (size_t)n_utt * n_src * n_part * (fft_n + 1), "spectrum workspace"));
+    AUG_TRY(grow(ctx, ctx->reverb, sizeof(float) * (size_t)n_src * reverb_stride(total), "reverberation workspace"));
+    AUG_TRY(grow(ctx, ctx->gains, sizeof(float) * (size_t)std::max(1, n_utt * n_noise), "gain workspace"));
+    AUG_TRY(grow(ctx, ctx->energy, sizeof(double) * (size_t)n_utt * n_src, "energy workspace"));
+    AUG_TRY(grow(ctx, ctx->first_tap, sizeof(int) * (size_t)n_utt * n_src, "first-tap workspace"));
+    return AUG_OK;
+}
+
+int prepare_mel(aug_ctx* ctx, int n_utt, const aug_frontend_cfg* cfg) {
+    if (n_utt == 0 || ctx->packing.n_frame_groups == 0) return AUG_OK;
+    AUG_TRY(grow(ctx, ctx->window, sizeof(float) * (size_t)cfg->win, "window table"));
+    if (cfg->feature == AUG_FEAT_MFCC)
+        AUG_TRY(grow(ctx, ctx->dct, sizeof(float) * (size_t)cfg->n_ceps * cfg->n_mel, "cosine table"));
+    AUG_TRY(grow(ctx, ctx->mel_tab, sizeof(float2) * (size_t)n_utt * aug::mel_table_stride(cfg->nfft), "mel table"));
+    return AUG_OK;
+}
+
 // ---- stage drivers: arguments already validated, packing already synchronised ----
 
 int run_rir(aug_ctx* ctx, int n_rir, const float* geom, int rir_len, float fs, float c, float* rir_out,
             int32_t* tap_count_out) {
     const double k = (double)fs / (double)c;
-    AUG_HIP(ctx->rir_items.reserve(2 * aug::rir_item_bytes() * (size_t)n_rir * aug::rir_items_per_response(rir_len)),
-            "response item table");
-    AUG_HIP(ctx->rir_ctrl.reserve(aug::rir_ctrl_ints() * sizeof(int)), "response item counter");
-    AUG_HIP(ctx->rir_pow.reserve(sizeof(float) * (size_t)n_rir * aug::rir_pow_entries()), "reflection table");
+    AUG_TRY(prepare_rir(ctx, n_rir, rir_len));
     const int n_groups = 2 * ctx->n_cu;
     AUG_TRY(mark(ctx, -1));
     AUG_HIP(aug::launch_rir_plan(ctx->stream, n_groups, n_rir, geom, rir_len, k, ctx->rir_items.ptr,
@@ -237,10 +338,6 @@ int run_rir(aug_ctx* ctx, int n_rir, const float* geom, int rir_len, float fs, f
     }
     return AUG_OK;
 }
-
-// Source j of the reverberated signals starts at j * reverb_stride(total): an even stride keeps the
-// 8-byte loads of the front end aligned for every source.
-int64_t reverb_stride(int64_t total) { return (total + 1) & ~(int64_t)1; }
 
 // Reverberates every source, measures the energies and derives the gains.  With mixed_out the mixture
 // is written there; without it the caller mixes on the fly from the context's reverberated signals.
@@ -262,21 +359,15 @@ int run_convolve_mix(aug_ctx* ctx, int n_utt, int n_noise, const float* speech, 
     int64_t max_len = 0;
     for (int u = 0; u < n_utt; ++u) max_len = std::max(max_len, pk.offsets[u + 1] - pk.offsets[u]);
 
-    AUG_HIP(ctx->rir_spec.reserve(sizeof(float2) * (size_t)n_utt * n_src * n_part * (fft_n + 1)), "spectrum workspace");
+    AUG_TRY(prepare_convolve_mix(ctx, n_utt, n_noise, rir_len));
     const int64_t stride = reverb_stride(total);
-    AUG_HIP(ctx->reverb.reserve(sizeof(float) * (size_t)n_src * stride), "reverberation workspace");
-    AUG_HIP(ctx->gains.reserve(sizeof(float) * (size_t)std::max(1, n_utt * n_noise)), "gain workspace");
-    AUG_HIP(ctx->energy.reserve(sizeof(double) * 3 * (size_t)n_utt * n_src), "energy workspace");
     double* const energy = ctx->energy.as<double>();
-    double* const energy_in = energy + (size_t)n_utt * n_src;
-    double* const h2 = energy_in + (size_t)n_utt * n_src;
 
     AUG_TRY(mark(ctx, -1));
-    AUG_HIP(ctx->first_tap.reserve(sizeof(int) * (size_t)n_utt * n_src), "first-tap workspace");
-    AUG_HIP(aug::launch_fill2_u32(ctx->stream, energy, 0u, (int64_t)n_utt * n_src * 6, ctx->first_tap.ptr, 0x7fffffffu,
+    AUG_HIP(aug::launch_fill2_u32(ctx->stream, energy, 0u, (int64_t)n_utt * n_src * 2, ctx->first_tap.ptr, 0x7fffffffu,
                                   (int64_t)n_utt * n_src), "energy and first-tap reset");
     AUG_TRY(mark(ctx, AUG_STAGE_OTHER));
-    AUG_HIP(aug::launch_rir_spectrum(ctx->stream, n_utt * n_src, rir, rir_len, fft_n, tw, ctx->rir_spec.as<float2>(), h2,
+    AUG_HIP(aug::launch_rir_spectrum(ctx->stream, n_utt * n_src, rir, rir_len, fft_n, tw, ctx->rir_spec.as<float2>(),
                                      ctx->first_tap.as<int>()),
             "spectrum kernel");
     AUG_TRY(mark(ctx, AUG_STAGE_RIR_SPECTRUM));
@@ -293,12 +384,10 @@ int run_convolve_mix(aug_ctx* ctx, int n_utt, int n_noise, const float* speech, 
     ca.reverb = ctx->reverb.as<float>();
     ca.reverb_stride = stride;
     ca.energy = energy;
-    ca.energy_in = energy_in;
     ca.first_tap = ctx->first_tap.as<int>();
     AUG_HIP(aug::launch_convolve(ctx->stream, fft_n, tw, ca), "convolution kernel");
     AUG_TRY(mark(ctx, AUG_STAGE_CONVOLVE));
-    AUG_HIP(aug::launch_gains(ctx->stream, n_utt, n_src, energy, energy_in, h2, snr_db, ctx->gains.as<float>(),
-                              gains_out), "gain kernel");
+    AUG_HIP(aug::launch_gains(ctx->stream, n_utt, n_src, energy, snr_db, ctx->gains.as<float>(), gains_out), "gain kernel");
     if (mixed_out)
         AUG_HIP(aug::launch_mix(ctx->stream, n_utt, ctx->d_offsets.as<int64_t>(), stride, n_src, ctx->reverb.as<float>(),
                                 ctx->gains.as<float>(), mixed_out, max_len), "mix kernel");
@@ -313,24 +402,21 @@ int run_mel(aug_ctx* ctx, int n_utt, const float* wave, const float* alpha, cons
     const aug::Packing& pk = ctx->packing;
     if (n_utt == 0 || pk.n_frame_groups == 0) return AUG_OK;
     const float2* tw = nullptr;
+    AUG_TRY(prepare_mel(ctx, n_utt, cfg));
     AUG_TRY(ensure_twiddle(ctx, cfg->nfft / 2, &tw));
     if (ctx->window_n != cfg->win) {
-        AUG_HIP(ctx->window.reserve(sizeof(float) * (size_t)cfg->win), "window table");
         AUG_HIP(aug::launch_window(ctx->stream, cfg->win, ctx->window.as<float>()), "window kernel");
         ctx->window_n = cfg->win;
     }
     const float* dct = nullptr;
     if (cfg->feature == AUG_FEAT_MFCC) {
         if (ctx->dct_ceps != cfg->n_ceps || ctx->dct_mel != cfg->n_mel) {
-            AUG_HIP(hipStreamSynchronize(ctx->stream), "stream synchronize");      // earlier work may read the old table
-            AUG_HIP(ctx->dct.reserve(sizeof(float) * (size_t)cfg->n_ceps * cfg->n_mel), "cosine table");
             AUG_HIP(aug::launch_dct_table(ctx->stream, cfg->n_ceps, cfg->n_mel, ctx->dct.as<float>()), "cosine table kernel");
             ctx->dct_ceps = cfg->n_ceps;
             ctx->dct_mel = cfg->n_mel;
         }
         dct = ctx->dct.as<float>();
     }
-    AUG_HIP(ctx->mel_tab.reserve(sizeof(float2) * (size_t)n_utt * aug::mel_table_stride(cfg->nfft)), "mel table");
     AUG_TRY(mark(ctx, -1));
     AUG_HIP(aug::launch_mel_table(ctx->stream, n_utt, alpha, *cfg, ctx->mel_tab.as<float2>()), "mel table kernel");
     aug::MelArgs ma;
@@ -419,11 +505,16 @@ int aug_destroy(aug_ctx* ctx) {
         rc = AUG_ERR_HIP;
     }
     DeviceBuffer* bufs[] = {&ctx->d_offsets, &ctx->d_frame_offsets, &ctx->d_conv_items, &ctx->d_frame_items,
+                            &ctx->d_conv_first, &ctx->d_frame_first,
                             &ctx->rir_items, &ctx->rir_ctrl, &ctx->rir_pow, &ctx->mic_rows, &ctx->rir, &ctx->rir_spec, &ctx->reverb, &ctx->energy, &ctx->gains, &ctx->first_tap, &ctx->vtlp_tab, &ctx->dct, &ctx->mel_tab,
                             &ctx->window};
     for (DeviceBuffer* b : bufs) b->release();
     for (DeviceBuffer& b : ctx->twiddle) b.release();
     for (auto& m : ctx->marks) (void)hipEventDestroy(m.first);
+    for (int i = 0; i < aug::HostRing::kSlots; ++i) {
+        if (ctx->ring.done[i]) (void)hipEventDestroy(ctx->ring.done[i]);
+        if (ctx->ring.slot[i]) (void)hipHostFree(ctx->ring.slot[i]);
+    }
     delete ctx;
     return rc;
 }
@@ -489,7 +580,7 @@ int aug_rir_mics_batch(aug_ctx* ctx, int n_rir, int n_mic, const float* geom, co
         return fail(ctx, AUG_ERR_UNSUPPORTED, "too many responses in one call");
     // rewriting the rows is ordered after an earlier call's kernels by the stream; growing the buffer frees
     // the old one, which waits for them
-    AUG_HIP(ctx->mic_rows.reserve(sizeof(float) * 10 * (size_t)n_rows), "microphone rows");
+    AUG_TRY(grow(ctx, ctx->mic_rows, sizeof(float) * 10 * (size_t)n_rows, "microphone rows"));
     AUG_TRY(mark(ctx, -1));
     AUG_HIP(aug::launch_rir_mic_rows(ctx->stream, n_rir, n_mic, geom, mics, ctx->mic_rows.as<float>()), "microphone rows kernel");
     AUG_TRY(mark(ctx, AUG_STAGE_OTHER));
@@ -548,7 +639,7 @@ int aug_vtlp_resynth_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, cons
     for (int u = 0; u < n_utt; ++u) max_len = std::max(max_len, offsets[u + 1] - offsets[u]);
     const float2* tw = nullptr;
     AUG_TRY(ensure_twiddle(ctx, aug::vtlp_fft_size(), &tw));
-    AUG_HIP(ctx->vtlp_tab.reserve(sizeof(float2) * (size_t)n_utt * aug::vtlp_table_entries()), "warp table");
+    AUG_TRY(grow(ctx, ctx->vtlp_tab, sizeof(float2) * (size_t)n_utt * aug::vtlp_table_entries(), "warp table"));
     AUG_TRY(mark(ctx, -1));
     AUG_HIP(aug::launch_vtlp_table(ctx->stream, n_utt, alpha, ctx->vtlp_tab.as<float2>()), "warp table kernel");
     AUG_HIP(aug::launch_fill_u32(ctx->stream, wave_out, 0u, total), "output clear");
@@ -581,9 +672,12 @@ int aug_pipeline_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, const fl
     const int64_t total = offsets[n_utt];
     float* rir = rir_out;
     if (!rir) {
-        AUG_HIP(ctx->rir.reserve(sizeof(float) * (size_t)n_utt * n_src * rir_len), "response workspace");
+        AUG_TRY(grow(ctx, ctx->rir, sizeof(float) * (size_t)n_utt * n_src * rir_len, "response workspace"));
         rir = ctx->rir.as<float>();
     }
+    AUG_TRY(prepare_rir(ctx, n_utt * n_src, rir_len));
+    AUG_TRY(prepare_convolve_mix(ctx, n_utt, n_noise, rir_len));
+    AUG_TRY(prepare_mel(ctx, n_utt, cfg));
     AUG_TRY(run_rir(ctx, n_utt * n_src, geom, rir_len, fs, c, rir, nullptr));
     AUG_TRY(run_convolve_mix(ctx, n_utt, n_noise, speech, noise, rir, rir_len, snr_db, mixed_out, gains_out));
     if (mixed_out || total == 0) return run_mel(ctx, n_utt, mixed_out, alpha, cfg, feats_out);

@@ -32,6 +32,17 @@ struct Packing {
     int64_t n_frame_groups = 0;
 };
 
+// Pinned host staging for the offset arrays: a call copies its arrays into the next slot and enqueues an
+// asynchronous copy from there, so the caller's arrays are free when the call returns and nothing waits for
+// the stream.  A slot is reused only after the copy that read it has completed (its event).
+struct HostRing {
+    static constexpr int kSlots = 4;
+    int64_t* slot[kSlots] = {nullptr, nullptr, nullptr, nullptr};
+    hipEvent_t done[kSlots] = {nullptr, nullptr, nullptr, nullptr};
+    size_t cap = 0;                      // int64 entries per slot
+    int next = 0;
+};
+
 }  // namespace aug
 
 struct aug_ctx {
@@ -45,6 +56,10 @@ struct aug_ctx {
     aug::DeviceBuffer d_frame_offsets;   // int64 [n_utt+1]
     aug::DeviceBuffer d_conv_items;      // int2 [n_conv_blocks]: (utterance, block)
     aug::DeviceBuffer d_frame_items;     // int2 [n_frame_groups]: (utterance, first frame)
+    aug::DeviceBuffer d_conv_first;      // int [n_utt+1]: blocks of the utterances before u
+    aug::DeviceBuffer d_frame_first;     // int [n_utt+1]: frame groups of the utterances before u
+    aug::HostRing ring;
+    unsigned char* scratch = nullptr;    // this device's copy of the library's static scratch array
 
     // image-method work list
     int n_cu = 0;                        // compute units of the device
@@ -57,7 +72,7 @@ struct aug_ctx {
     aug::DeviceBuffer rir;               // float [n_rir][rir_len]            (pipeline only)
     aug::DeviceBuffer rir_spec;          // float2 [n_rir][n_part][P+1]
     aug::DeviceBuffer reverb;            // float [1+n_noise][total rounded up to even]
-    aug::DeviceBuffer energy;            // double [3][n_utt][1+n_noise]: reverberated signals, inputs, responses
+    aug::DeviceBuffer energy;            // double [n_utt][1+n_noise]: energies of the reverberated signals
     aug::DeviceBuffer gains;             // float [n_utt][n_noise]
     aug::DeviceBuffer first_tap;         // int [n_utt][1+n_noise]
     aug::DeviceBuffer mel_tab;           // float2 [n_utt][nfft/2+1]: (channel, weight) per bin
@@ -100,10 +115,9 @@ hipError_t launch_rir_mic_rows(hipStream_t s, int n_rir, int n_mic, const float*
 int conv_fft_size(int rir_len);
 
 // Spectra of the zero-padded partitions of each response: spec float2 [n_rir][n_part][P+1], P = fft_n;
-// the sum of every response's squared taps is added to h2[n_rir] (zero on entry) and the index of its first
-// non-zero tap is taken into first_tap[n_rir] (INT_MAX on entry).
+// the index of every response's first non-zero tap is taken into first_tap[n_rir] (INT_MAX on entry).
 hipError_t launch_rir_spectrum(hipStream_t s, int n_rir, const float* rir, int rir_len, int fft_n,
-                               const float2* twiddle, float2* spec, double* h2, int* first_tap);
+                               const float2* twiddle, float2* spec, int* first_tap);
 
 // Overlap-save convolution of every (utterance, source) with its response; adds the block's energy
 // to energy[u][j] (double, must be zero on entry).  src_base[j] points at source j's packed signal.
@@ -120,15 +134,14 @@ struct ConvArgs {
     float* reverb;               // [n_src][reverb_stride]
     int64_t reverb_stride;
     double* energy;              // [n_utt][n_src] of the reverberated signals
-    double* energy_in;           // [n_utt][n_src] of the inputs
     const int* first_tap;        // [n_utt][n_src] first non-zero tap of each response
 };
 hipError_t launch_convolve(hipStream_t s, int fft_n, const float2* twiddle, const ConvArgs& a);
 
 // gains [n_utt][n_src - 1] from the energies and the target SNRs (also copied to gains_out when given)
-// energy, energy_in, h2: [n_utt][n_src] energies of the reverberated signals, of the inputs and of the responses
-hipError_t launch_gains(hipStream_t s, int n_utt, int n_src, const double* energy, const double* energy_in,
-                        const double* h2, const float* snr_db, float* gains, float* gains_out);
+// energy: [n_utt][n_src] energies of the reverberated signals
+hipError_t launch_gains(hipStream_t s, int n_utt, int n_src, const double* energy, const float* snr_db, float* gains,
+                        float* gains_out);
 // mixed = reverb[0] + sum_j gains[j - 1] reverb[j]; source j of the reverberated signals starts at j * stride
 hipError_t launch_mix(hipStream_t s, int n_utt, const int64_t* d_offsets, int64_t stride, int n_src,
                       const float* reverb, const float* gains, float* mixed_out, int64_t max_len);
@@ -181,6 +194,13 @@ bool vtlp_supported(int win, int hop, int nfft);
 hipError_t launch_vtlp_table(hipStream_t s, int n_utt, const float* alpha, float2* tab);
 hipError_t launch_vtlp_resynth(hipStream_t s, int n_utt, const int64_t* d_offsets, int64_t max_len,
                                const float* wave, const float2* tab, const float2* twiddle, float* out);
+
+// Exclusive prefix sums of the per-utterance item counts (blocks of conv_block samples; groups of
+// frames_per_group output rows) and the item tables (utterance, block) / (utterance, first row), all from the
+// device copies of the offsets.  A null `*_first` skips that table.  The item counts are the host's.
+hipError_t launch_pack(hipStream_t s, int n_utt, const int64_t* d_offsets, const int64_t* d_frame_offsets,
+                       int conv_block, int frames_per_group, int* conv_first, int2* conv_items, int64_t n_conv_items,
+                       int* frame_first, int2* frame_items, int64_t n_frame_items);
 
 // fill n 32-bit words with a value (used instead of memset so that calls stay graph-capturable)
 hipError_t launch_fill_u32(hipStream_t s, void* p, uint32_t v, int64_t n);

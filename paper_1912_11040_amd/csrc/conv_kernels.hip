@@ -71,9 +71,8 @@ template <int N> __device__ inline float2 pair_twiddle(const float2* __restrict_
 template <int N, int T>
 __global__ __launch_bounds__(T) void rir_spectrum_kernel(
     const float* __restrict__ rir, int rir_len, int n_part, const float2* __restrict__ tw,
-    float2* __restrict__ spec, double* __restrict__ h2, int* __restrict__ first_tap) {
+    float2* __restrict__ spec, int* __restrict__ first_tap) {
     extern __shared__ float2 buf[];
-    __shared__ double red[T / 64];
     constexpr int M = N / 16;
     const int tid = threadIdx.x;
     const int r = blockIdx.x / n_part, p = blockIdx.x % n_part;
@@ -96,20 +95,9 @@ __global__ __launch_bounds__(T) void rir_spectrum_kernel(
     // the response is zero before its first non-zero tap, and so is everything convolved with it
     for (int off = 32; off > 0; off >>= 1) first = min(first, __shfl_down(first, off, 64));
     if ((tid & 63) == 0 && first != 0x7fffffff) atomicMin(&first_tap[r], first);
-    // the partition's share of the response's energy, sum of squared taps (h2 must be zero on entry)
-    double e = 0.0;
-#pragma unroll
-    for (int n1 = 0; n1 < 8; ++n1) e += (double)(v[n1].x * v[n1].x + v[n1].y * v[n1].y);
-    for (int off = 32; off > 0; off >>= 1) e += __shfl_down(e, off, 64);
-    if ((tid & 63) == 0) red[tid >> 6] = e;
     fft_columns_forward<N>(v, tw, tid);
     fft_columns_store<N, T>(v, buf, tid);
     __syncthreads();
-    if (tid == 0) {
-        double tot = 0.0;
-        for (int i = 0; i < T / 64; ++i) tot += red[i];
-        atomicAdd(&h2[r], tot);
-    }
     fft_rows<N, false>(buf, tw, tid);
     __syncthreads();
     float2* out = spec + ((size_t)r * n_part + p) * (N + 1);
@@ -152,7 +140,7 @@ struct __attribute__((aligned(4))) SamplePair { float x, y; };
 template <int N, int T, bool MULTI>
 __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* __restrict__ tw) {
     extern __shared__ float2 buf[];
-    __shared__ double red[T / 64], red_in[T / 64];
+    __shared__ double red[T / 64];
     constexpr int M = N / 16;
     static_assert(T == M, "one thread per column of the split transform");
     const int tid = threadIdx.x;
@@ -179,7 +167,6 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
     for (int i = 0; i < 8; ++i) out[i] = make_float2(0.f, 0.f);
 
     float2 v[16];
-    float e_in = 0.f;
     const int n_part = MULTI ? a.n_part : 1;
     for (int p = 0; p < n_part; ++p) {
         const int wb = b - p;                        // input window [(wb-1)N, (wb+1)N)
@@ -218,10 +205,6 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
                 const float x1 = g + 1 < len ? x[g + 1] : 0.f;
                 v[n1] = make_float2(x0, x1);
             }
-        }
-        if (p == 0) {                                // the block's own input samples are the window's second half
-#pragma unroll
-            for (int n1 = 8; n1 < 16; ++n1) e_in += v[n1].x * v[n1].x + v[n1].y * v[n1].y;
         }
         fft_columns_forward<N>(v, tw, tid_p);
         if (MULTI && p > 0) __syncthreads();         // the previous partition's column loads are done
@@ -278,45 +261,28 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
             if (g + 1 < len) { y[g + 1] = s1; e += s1 * s1; }
         }
     }
-    double es = (double)e, es_in = (double)e_in;
-    for (int off = 32; off > 0; off >>= 1) {
-        es += __shfl_down(es, off, 64);
-        es_in += __shfl_down(es_in, off, 64);
-    }
-    if ((tid & 63) == 0) {
-        red[tid >> 6] = es;
-        red_in[tid >> 6] = es_in;
-    }
+    double es = (double)e;
+    for (int off = 32; off > 0; off >>= 1) es += __shfl_down(es, off, 64);
+    if ((tid & 63) == 0) red[tid >> 6] = es;
     __syncthreads();
     if (tid == 0) {
-        double tot = 0.0, tot_in = 0.0;
-        for (int i = 0; i < T / 64; ++i) {
-            tot += red[i];
-            tot_in += red_in[i];
-        }
+        double tot = 0.0;
+        for (int i = 0; i < T / 64; ++i) tot += red[i];
         atomicAdd(&a.energy[(size_t)u * a.n_src + j], tot);
-        atomicAdd(&a.energy_in[(size_t)u * a.n_src + j], tot_in);
     }
 }
 
-// A reverberated signal that is exactly zero (the utterance ends before the direct path arrives) comes out of
-// the transforms as rounding noise of relative size ~1e-7.  Its measured energy is therefore taken as zero when
-// it is below 1e-10 of (energy of the input) x (energy of the response): far below anything a signal that did
-// arrive can have, far above the noise.
-constexpr double kSilentFraction = 1e-10;
-
 // One thread per (utterance, noise source): the gain that puts the reverberated noise at its target
-// SNR against the reverberated speech; a silent signal on either side gives gain 0.
-__global__ void gain_kernel(int n_utt, int n_src, const double* __restrict__ energy, const double* __restrict__ energy_in,
-                            const double* __restrict__ h2, const float* __restrict__ snr_db,
+// SNR against the reverberated speech; zero energy on either side gives gain 0.  (A source whose direct
+// path arrives after the utterance has ended has exactly zero energy: the convolution writes exact zeros
+// before the response's first non-zero tap.)
+__global__ void gain_kernel(int n_utt, int n_src, const double* __restrict__ energy, const float* __restrict__ snr_db,
                             float* __restrict__ gains, float* __restrict__ gains_out) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     const int n_noise = n_src - 1;
     if (i >= n_utt * n_noise) return;
     const int u = i / n_noise, j = 1 + i % n_noise;
-    const size_t s0 = (size_t)u * n_src, sj = s0 + j;
-    const double e0 = energy[s0] > kSilentFraction * energy_in[s0] * h2[s0] ? energy[s0] : 0.0;
-    const double ej = energy[sj] > kSilentFraction * energy_in[sj] * h2[sj] ? energy[sj] : 0.0;
+    const double e0 = energy[(size_t)u * n_src], ej = energy[(size_t)u * n_src + j];
     const double snr = (double)snr_db[i];
     const float gain = (e0 > 0.0 && ej > 0.0) ? (float)sqrt(e0 / (ej * pow(10.0, snr / 10.0))) : 0.f;
     gains[i] = gain;
@@ -345,7 +311,7 @@ __global__ __launch_bounds__(256) void mix_kernel(
 
 template <int N>
 hipError_t spectrum_n(hipStream_t s, int n_rir, const float* rir, int rir_len, const float2* tw,
-                      float2* spec, double* h2, int* first_tap) {
+                      float2* spec, int* first_tap) {
     constexpr int T = conv_threads(N);
     const int n_part = (rir_len + N - 1) / N;
     const size_t lds = sizeof(float2) * lds_padded_size(N);
@@ -353,7 +319,7 @@ hipError_t spectrum_n(hipStream_t s, int n_rir, const float* rir, int rir_len, c
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    k<<<dim3((unsigned)(n_rir * n_part)), dim3(T), lds, s>>>(rir, rir_len, n_part, tw, spec, h2, first_tap);
+    k<<<dim3((unsigned)(n_rir * n_part)), dim3(T), lds, s>>>(rir, rir_len, n_part, tw, spec, first_tap);
     return hipGetLastError();
 }
 
@@ -397,9 +363,9 @@ hipError_t launch_twiddle(hipStream_t s, int n, float2* tw) {
     }
 
 hipError_t launch_rir_spectrum(hipStream_t s, int n_rir, const float* rir, int rir_len, int fft_n,
-                               const float2* twiddle, float2* spec, double* h2, int* first_tap) {
+                               const float2* twiddle, float2* spec, int* first_tap) {
     if (n_rir <= 0) return hipSuccess;
-#define CALL(NN) spectrum_n<NN>(s, n_rir, rir, rir_len, twiddle, spec, h2, first_tap)
+#define CALL(NN) spectrum_n<NN>(s, n_rir, rir, rir_len, twiddle, spec, first_tap)
     AUG_FFT_DISPATCH(fft_n, CALL)
 #undef CALL
 }
@@ -411,12 +377,12 @@ hipError_t launch_convolve(hipStream_t s, int fft_n, const float2* twiddle, cons
 #undef CALL
 }
 
-hipError_t launch_gains(hipStream_t s, int n_utt, int n_src, const double* energy, const double* energy_in,
-                        const double* h2, const float* snr_db, float* gains, float* gains_out) {
+hipError_t launch_gains(hipStream_t s, int n_utt, int n_src, const double* energy, const float* snr_db, float* gains,
+                        float* gains_out) {
     const int n = n_utt * (n_src - 1);
     if (n <= 0) return hipSuccess;
-    gain_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(n_utt, n_src, energy, energy_in, h2, snr_db,
-                                                                         gains, gains_out);
+    gain_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(n_utt, n_src, energy, snr_db, gains,
+                                                                         gains_out);
     return hipGetLastError();
 }
 

@@ -3,6 +3,7 @@ import numpy as np
 import pytest
 
 from oracle import aug_oracle as O
+from paper_1912_11040_amd import binding
 from paper_1912_11040_amd import workloads as W
 from tests.parity import FEAT_TOL, GAIN_TOL, RIR_TOL, WAVE_TOL, DeviceWorkload, feat_err, rir_err, wave_err
 
@@ -251,8 +252,16 @@ def test_steady_state_call_can_be_captured_in_a_graph():
                                w.frontend, d.frame_offsets, eager)          # sizes the workspace, uploads the tables
         stream.synchronize()
         out = d.empty_feats()
+        w2 = w.slice([0, 1])
+        d2 = DeviceWorkload(w2)
+        out2 = d2.empty_feats()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=stream):
+            # a batch with other offsets would need copies and new tables: refused while the stream is captured
+            with pytest.raises(binding.AugError) as refused:
+                ctx.aug_pipeline_batch(w2.offsets, d2.speech, d2.noise, d2.geom, w2.rir_len, w2.fs, w2.c, d2.snr_db,
+                                       d2.alpha, w2.frontend, d2.frame_offsets, out2)
+            assert refused.value.code == binding.AUG_ERR_UNSUPPORTED
             ctx.aug_pipeline_batch(w.offsets, d.speech, d.noise, d.geom, w.rir_len, w.fs, w.c, d.snr_db, d.alpha,
                                    w.frontend, d.frame_offsets, out)
     want = eager.cpu().numpy()
@@ -312,3 +321,34 @@ def test_batch_with_no_frames_and_batch_with_no_samples(aug):
                                w.rir_len, d.snr_db, torch.zeros(0, device="cuda"), gains)
     torch.cuda.synchronize()
     assert np.all(gains.cpu().numpy() == 0.0)
+
+
+def test_batches_with_new_lengths_every_call(aug):
+    # The example queue hands over a batch with new lengths at every step (Sec. 2.2): batches that differ in
+    # utterance count, lengths and response length alternate on one context with no synchronisation between
+    # the calls (nine calls, so the four staging slots for the offsets are reused twice); every call's
+    # features and gains against the oracle.
+    import torch
+    ws = [W.varlen(n_utt=3, rir_len=1200, min_s=0.05, max_s=0.9, seed=21),
+          W.varlen(n_utt=6, rir_len=700, min_s=0.02, max_s=0.5, seed=22),
+          W.varlen(n_utt=4, rir_len=1200, min_s=0.3, max_s=1.4, seed=23)]
+    refs = [_oracle(w) for w in ws]
+    devs = [DeviceWorkload(w) for w in ws]
+    outs = []
+    for k in range(9):
+        w, d = ws[k % 3], devs[k % 3]
+        feats = d.empty_feats()
+        gains = torch.full((w.n_utt, w.n_noise), float("nan"), dtype=torch.float32, device="cuda")
+        mixed = torch.full((w.total,), float("nan"), dtype=torch.float32, device="cuda") if k % 2 else None
+        aug.aug_pipeline_batch(w.offsets, d.speech, d.noise, d.geom, w.rir_len, w.fs, w.c, d.snr_db, d.alpha,
+                               w.frontend, d.frame_offsets, feats, None, mixed, gains)
+        outs.append((feats, gains, mixed))
+    torch.cuda.synchronize()
+    for k, (feats, gains, mixed) in enumerate(outs):
+        w, ref = ws[k % 3], refs[k % 3]
+        fe = feat_err(feats.cpu().numpy(), ref["feats"])
+        print(f"  call {k}: batch {k % 3}, feat err {fe:.2e}", flush=True)
+        assert fe <= FEAT_TOL
+        np.testing.assert_allclose(gains.cpu().numpy(), ref["gains"], rtol=GAIN_TOL)
+        if mixed is not None:
+            assert wave_err(mixed.cpu().numpy(), ref["mixed"], w.offsets, silent_scale=w.speech) <= WAVE_TOL
