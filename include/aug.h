@@ -235,6 +235,36 @@ int aug_vtlp_mel_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, const fl
                        const float* alpha, const aug_frontend_cfg* cfg,
                        const int64_t* frame_offsets, float* feats_out);
 
+/*
+ * aug_vtlp_mel_batch for callers that cannot allocate device memory: serving
+ * loops, harnesses that forbid hipMalloc, code that must not trigger an
+ * allocation at an awkward moment.  Arguments, output and errors are those of
+ * aug_vtlp_mel_batch, and so are the kernels; what differs is where the
+ * tables of the call live (device copies of the offsets, the frame-group
+ * table, the per-utterance warped mel tables, twiddles, window, cosine
+ * table): in a fixed array of AUG_STATIC_SCRATCH_BYTES that is part of the
+ * library's device image, one copy per GPU, held from the moment the library
+ * is loaded on that GPU until the process ends.  The call makes no hipMalloc,
+ * hipFree or other allocating call (the pinned staging it copies the offsets
+ * through is set up by aug_create).
+ *
+ * Limits: n_utt <= AUG_STATIC_MAX_UTT, and the output rows, counted in groups
+ * of 64 per utterance (sum over u of ceil(rows_u / 64)), at most
+ * AUG_STATIC_MAX_ROW_GROUPS; a larger batch is refused with
+ * AUG_ERR_UNSUPPORTED and nothing is launched.
+ *
+ * Every call on a GPU, from any context, uses that GPU's one array and
+ * rewrites all of it that it reads: nothing of an earlier call's contents is
+ * relied on.  Calls that overlap in time on one GPU (two contexts on two
+ * streams, two threads) race on the array; the caller must order them.
+ */
+#define AUG_STATIC_MAX_UTT 4096
+#define AUG_STATIC_MAX_ROW_GROUPS 65536
+#define AUG_STATIC_SCRATCH_BYTES (10u << 20)
+int aug_vtlp_mel_batch_static(aug_ctx* ctx, int n_utt, const int64_t* offsets, const float* wave,
+                              const float* alpha, const aug_frontend_cfg* cfg,
+                              const int64_t* frame_offsets, float* feats_out);
+
 /* Analysis constants of the waveform VTLP.  Kernels are built for 800 / 400 / 2048. */
 typedef struct aug_vtlp_cfg {
     int win;        /* frame length in samples (periodic Hann), 50 ms in the paper's best setting */

@@ -23,7 +23,8 @@ AUG_ERR_HIP = -4
 
 EXPORTS = ("aug_create", "aug_destroy", "aug_last_error", "aug_frame_count", "aug_feature_dim", "aug_rir_batch",
            "aug_rir_mics_batch",
-           "aug_convolve_mix_batch", "aug_vtlp_mel_batch", "aug_vtlp_resynth_batch", "aug_pipeline_batch",
+           "aug_convolve_mix_batch", "aug_vtlp_mel_batch", "aug_vtlp_mel_batch_static", "aug_vtlp_resynth_batch",
+           "aug_pipeline_batch",
            "aug_profile_enable", "aug_profile_read")
 
 FEATURE_KINDS = {"power": 0, "log": 1, "mfcc": 2}      # AUG_FEAT_*
@@ -91,6 +92,8 @@ def load_library() -> ctypes.CDLL:
     lib.aug_convolve_mix_batch.restype = ci
     lib.aug_vtlp_mel_batch.argtypes = [vp, ci, p_i64, vp, vp, p_cfg, p_i64, vp]
     lib.aug_vtlp_mel_batch.restype = ci
+    lib.aug_vtlp_mel_batch_static.argtypes = [vp, ci, p_i64, vp, vp, p_cfg, p_i64, vp]
+    lib.aug_vtlp_mel_batch_static.restype = ci
     lib.aug_vtlp_resynth_batch.argtypes = [vp, ci, p_i64, vp, vp, ctypes.POINTER(VtlpCfg), vp]
     lib.aug_vtlp_resynth_batch.restype = ci
     lib.aug_pipeline_batch.argtypes = [vp, ci, p_i64, vp, ci, vp, vp, ci, cf, cf, vp, vp, p_cfg,
@@ -300,6 +303,19 @@ class Augmenter:
         if self._check_sizes:
             check_mel_sizes(off, foff, wave, alpha, feats_out, self._lib.aug_feature_dim(ctypes.byref(c)))
         self._check(self._lib.aug_vtlp_mel_batch(
+            self._h, len(off) - 1, off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+            _ptr(wave, torch.float32), _ptr(alpha, torch.float32), ctypes.byref(c),
+            foff.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), _ptr(feats_out, torch.float32)))
+
+    def aug_vtlp_mel_batch_static(self, offsets, wave, alpha, cfg, frame_offsets, feats_out):
+        """aug_vtlp_mel_batch with its tables in the library's static device array: the call allocates nothing."""
+        import torch
+        off = _host_i64(offsets)
+        foff = _host_i64(frame_offsets)
+        c = cfg if isinstance(cfg, FrontendCfg) else FrontendCfg.of(cfg)
+        if self._check_sizes:
+            check_mel_sizes(off, foff, wave, alpha, feats_out, self._lib.aug_feature_dim(ctypes.byref(c)))
+        self._check(self._lib.aug_vtlp_mel_batch_static(
             self._h, len(off) - 1, off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
             _ptr(wave, torch.float32), _ptr(alpha, torch.float32), ctypes.byref(c),
             foff.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), _ptr(feats_out, torch.float32)))

@@ -10,6 +10,7 @@
 #include <new>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 #include "aug_internal.h"
 
@@ -48,6 +49,32 @@ void DeviceBuffer::release() {
 namespace {
 
 using aug::DeviceBuffer;
+
+// ---- the static scratch array of aug_vtlp_mel_batch_static ----
+// Device memory that is part of the library's code object: every GPU that loads the library holds its own
+// copy at its own address.  In host code the array's name is only a handle for hipGetSymbolAddress, never a
+// device address; g_scratch[device] is what kernels and copies are given.
+static __device__ __align__(256) unsigned char scratch[AUG_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+unsigned char* g_scratch[kMaxDevices] = {};      // per device, filled by aug_create with that device current
+std::mutex g_scratch_mutex;
+
+constexpr size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+// byte offsets of the tables inside the array
+struct ScratchLayout {
+    static constexpr size_t twiddle = 0;                                                        // float2 [393]
+    static constexpr size_t window = twiddle + align256(sizeof(float2) * 512);                  // float [<= 2048]
+    static constexpr size_t dct = window + align256(sizeof(float) * 2048);                      // float [128][128]
+    static constexpr size_t offsets = dct + align256(sizeof(float) * AUG_MAX_MEL * AUG_MAX_MEL);
+    static constexpr size_t frame_offsets = offsets + align256(sizeof(int64_t) * (AUG_STATIC_MAX_UTT + 1));
+    static constexpr size_t frame_first = frame_offsets + align256(sizeof(int64_t) * (AUG_STATIC_MAX_UTT + 1));
+    static constexpr size_t frame_items = frame_first + align256(sizeof(int) * (AUG_STATIC_MAX_UTT + 1));
+    static constexpr size_t mel_tab = frame_items + align256(sizeof(int2) * AUG_STATIC_MAX_ROW_GROUPS);
+    static constexpr size_t mel_tab_bytes = sizeof(float2) * (size_t)AUG_STATIC_MAX_UTT * (512 / 2 + 1 + 9);
+    static constexpr size_t end = mel_tab + align256(mel_tab_bytes);
+};
+static_assert(ScratchLayout::end <= AUG_STATIC_SCRATCH_BYTES, "the tables fit the static array");
 
 int fail(aug_ctx* ctx, int code, const char* fmt, ...) {
     if (ctx) {
@@ -493,6 +520,25 @@ int aug_create(aug_ctx** out, int device_id, void* hip_stream) {
         delete ctx;
         return AUG_ERR_HIP;
     }
+    // This device's copy of the static scratch array (once per device, with the device current), and pinned
+    // staging large enough for the entry point that uses it, so that that entry point never allocates.
+    if (device_id < kMaxDevices) {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch[device_id]) {
+            unsigned char* p = nullptr;
+            if (hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+                (void)hipGetLastError();
+                delete ctx;
+                return AUG_ERR_HIP;
+            }
+            g_scratch[device_id] = p;
+        }
+        ctx->scratch = g_scratch[device_id];
+    }
+    if (ring_reserve(ctx, 2 * ((size_t)AUG_STATIC_MAX_UTT + 1)) != AUG_OK) {
+        aug_destroy(ctx);
+        return AUG_ERR_NOMEM;
+    }
     *out = ctx;
     return AUG_OK;
 }
@@ -612,6 +658,68 @@ int aug_vtlp_mel_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, const fl
         return fail(ctx, AUG_ERR_INVALID_ARG, "wave, alpha or feats_out is null");
     AUG_TRY(sync_packing(ctx, n_utt, offsets, frame_offsets, 0, aug::mel_frames_per_group()));
     return run_mel(ctx, n_utt, wave, alpha, cfg, feats_out);
+}
+
+int aug_vtlp_mel_batch_static(aug_ctx* ctx, int n_utt, const int64_t* offsets, const float* wave, const float* alpha,
+                              const aug_frontend_cfg* cfg, const int64_t* frame_offsets, float* feats_out) {
+    AUG_TRY(enter(ctx));
+    AUG_TRY(check_offsets(ctx, n_utt, offsets));
+    AUG_TRY(check_frontend(ctx, cfg));
+    AUG_TRY(check_frame_offsets(ctx, n_utt, offsets, frame_offsets, cfg));
+    if ((!wave && offsets[n_utt] > 0) || (!alpha && n_utt > 0) || (!feats_out && frame_offsets[n_utt] > 0))
+        return fail(ctx, AUG_ERR_INVALID_ARG, "wave, alpha or feats_out is null");
+    if (n_utt > AUG_STATIC_MAX_UTT)
+        return fail(ctx, AUG_ERR_UNSUPPORTED, "%d utterances: the static scratch array holds tables for at most %d",
+                    n_utt, AUG_STATIC_MAX_UTT);
+    const int fpg = aug::mel_frames_per_group();
+    int64_t n_groups = 0;
+    for (int u = 0; u < n_utt; ++u) n_groups += (frame_offsets[u + 1] - frame_offsets[u] + fpg - 1) / fpg;
+    if (n_groups > AUG_STATIC_MAX_ROW_GROUPS)
+        return fail(ctx, AUG_ERR_UNSUPPORTED, "%lld groups of %d output rows: the static scratch array holds at most %d",
+                    (long long)n_groups, fpg, AUG_STATIC_MAX_ROW_GROUPS);
+    if (cfg->win > 2048) return fail(ctx, AUG_ERR_UNSUPPORTED, "window longer than 2048 samples");
+    if (n_utt == 0 || n_groups == 0) return AUG_OK;
+    unsigned char* const base = ctx->scratch;            // the device address, not the array's name
+    if (!base) return fail(ctx, AUG_ERR_HIP, "the static scratch array is not available on this device");
+    if (ctx->ring.cap < 2 * ((size_t)n_utt + 1)) return fail(ctx, AUG_ERR_HIP, "staging ring missing");
+
+    float2* const tw = reinterpret_cast<float2*>(base + ScratchLayout::twiddle);
+    float* const window = reinterpret_cast<float*>(base + ScratchLayout::window);
+    float* const dct = reinterpret_cast<float*>(base + ScratchLayout::dct);
+    int64_t* const d_off = reinterpret_cast<int64_t*>(base + ScratchLayout::offsets);
+    int64_t* const d_foff = reinterpret_cast<int64_t*>(base + ScratchLayout::frame_offsets);
+    int* const d_first = reinterpret_cast<int*>(base + ScratchLayout::frame_first);
+    int2* const d_items = reinterpret_cast<int2*>(base + ScratchLayout::frame_items);
+    float2* const mel_tab = reinterpret_cast<float2*>(base + ScratchLayout::mel_tab);
+
+    // Everything the kernels read from the array is rewritten here, in stream order, by this call.
+    AUG_TRY(upload_offsets(ctx, (size_t)n_utt + 1, offsets, d_off, frame_offsets, d_foff));
+    AUG_HIP(aug::launch_pack(ctx->stream, n_utt, d_off, d_foff, 0, fpg, nullptr, nullptr, 0, d_first, d_items, n_groups),
+            "packing kernels");
+    AUG_HIP(aug::launch_twiddle(ctx->stream, cfg->nfft / 2, tw), "twiddle kernel");
+    AUG_HIP(aug::launch_window(ctx->stream, cfg->win, window), "window kernel");
+    if (cfg->feature == AUG_FEAT_MFCC)
+        AUG_HIP(aug::launch_dct_table(ctx->stream, cfg->n_ceps, cfg->n_mel, dct), "cosine table kernel");
+    AUG_HIP(aug::launch_mel_table(ctx->stream, n_utt, alpha, *cfg, mel_tab), "mel table kernel");
+    aug::MelArgs ma;
+    ma.offsets = d_off;
+    ma.frame_offsets = d_foff;
+    ma.items = d_items;
+    ma.n_items = n_groups;
+    ma.frames_per_group = fpg;
+    ma.wave = wave;
+    ma.extra = nullptr;
+    ma.extra_stride = 0;
+    ma.gains = nullptr;
+    ma.n_extra = 0;
+    ma.mel_tab = mel_tab;
+    ma.dct = cfg->feature == AUG_FEAT_MFCC ? dct : nullptr;
+    ma.window = window;
+    ma.twiddle = tw;
+    ma.cfg = *cfg;
+    ma.feats = feats_out;
+    AUG_HIP(aug::launch_mel(ctx->stream, ma), "mel kernel");
+    return AUG_OK;
 }
 
 int aug_feature_dim(const aug_frontend_cfg* cfg) {
