@@ -70,3 +70,47 @@ class DeviceWorkload:
     def empty_feats(self):
         return self.torch.full((self.n_frames, self.w.frontend.n_mel), float("nan"),
                                dtype=self.torch.float32, device="cuda")
+
+
+# ---- the oracle on many utterances at once (host processes; nothing here touches the GPU) ----
+
+def _oracle_utterance(job):
+    from oracle import aug_oracle as O
+    s, conv, stft = job
+    return O.pipeline_batch(s.offsets, s.speech, s.noise, s.geom, s.rir_len, s.fs, s.c, s.snr_db, s.alpha,
+                            s.frontend, conv_method=conv, stft_method=stft)
+
+
+def _oracle_rir_rows(job):
+    from oracle import aug_oracle as O
+    geom, rir_len, fs, c = job
+    return O.rir_batch(geom, rir_len, fs, c)
+
+
+def _pool(workers):
+    # fresh interpreters ("spawn"): the parent has the GPU open, and a forked copy of it must not exist
+    import multiprocessing as mp
+    from concurrent.futures import ProcessPoolExecutor
+    return ProcessPoolExecutor(max_workers=workers, mp_context=mp.get_context("spawn"))
+
+
+def oracle_utterances(w, utts, conv="fft", stft="dft", workers=8):
+    """pipeline_batch of the oracle for each listed utterance of workload w (one-utterance slices), in parallel."""
+    jobs = [(w.slice([u]), conv, stft) for u in utts]
+    with _pool(min(workers, max(1, len(jobs)))) as ex:
+        return list(ex.map(_oracle_utterance, jobs))
+
+
+def oracle_rirs(geom, rir_len, fs, c, workers=8):
+    """rir_batch of the oracle over the rows of geom, in parallel; returns (h, tap_count)."""
+    geom = np.asarray(geom, np.float32).reshape(-1, 10)
+    jobs = [(geom[r:r + 1], rir_len, fs, c) for r in range(len(geom))]
+    with _pool(min(workers, max(1, len(jobs)))) as ex:
+        parts = list(ex.map(_oracle_rir_rows, jobs))
+    return np.concatenate([p[0] for p in parts]), np.concatenate([p[1] for p in parts])
+
+
+def spread(n, count, extra=()):
+    """`count` indices spread evenly over range(n), always with the first and the last, plus `extra`."""
+    picks = set(int(round(i * (n - 1) / max(count - 1, 1))) for i in range(count)) | set(int(e) for e in extra)
+    return sorted(picks)

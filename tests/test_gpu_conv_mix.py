@@ -194,3 +194,57 @@ def test_measured_snr_equals_target(aug):
     y = O.reverberate(offsets, speech, noise, rir.astype(np.float64))
     got = 10 * np.log10(np.sum(y[0] ** 2) / np.sum((gains[0, 0] * y[1]) ** 2))
     assert got == pytest.approx(7.5, abs=1e-3)
+
+
+def test_utterances_that_end_as_a_source_arrives(aug):
+    # Where the waveform bar stops being attainable, as fixed cases.  The transforms' rounding noise is about
+    # 1e-7 of (input RMS x response norm), whatever part of the reverberated signal the utterance still holds.
+    # An utterance that ends m samples after a source's direct path arrives holds a sliver of energy
+    # E = ratio x E_in x E_h, so the noise is about 1e-7 / sqrt(ratio) of its RMS.  Stated bar, asserted here:
+    #   * the utterance ends at or before the speech's first tap: gain 0 and exact zeros on both sides;
+    #   * otherwise  max|z - z_ref| <= max(1e-4, 1e-6 / sqrt(ratio)) x RMS(z_ref)  and gains to
+    #     max(1e-4, 1e-6 / sqrt(ratio)) relative, ratio = E_0 / (E_in,0 E_h,0) of the reverberated speech.
+    # With speech-like onsets (ratio 1e-5 .. 1e-3 in the last few samples) that is the ordinary 1e-4 bar or
+    # just above it; an onset of near-zero samples (ratio ~ 1e-11, the case a random sweep once met) is far
+    # outside it and only the formula holds.
+    L = 600
+    row_s = [6, 5, 3, 1, 4, 1, 1, 1, 1, 0.6]          # speech 3 m from the microphone: first tap 140
+    row_n = [6, 5, 3, 2, 1, 1, 1, 1, 1, 0.6]          # noise 1 m away: first tap 47
+    extra = [1, 2, 3, 5, 10, 50, 400]
+    lens = [140 + e for e in extra] + [47 + e for e in extra] + [47, 46, 140, 139, 142]
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    total = int(offsets[-1])
+    geom = np.array([[row_s, row_n]] * len(lens), np.float32)
+    h, _ = O.rir_batch(geom.reshape(-1, 10), L, 16000.0, 343.0)
+    rir = h.reshape(len(lens), 2, L).astype(np.float32)
+    snr = np.full((len(lens), 1), 10.0, np.float32)
+    for seed in (1, 2, 3):
+        rng = np.random.default_rng(seed)
+        speech = np.concatenate([W.speech_like(rng, int(n)) for n in lens]).astype(np.float32)
+        noise = rng.standard_normal((1, total)).astype(np.float32)
+        speech[offsets[-2]:offsets[-2] + 2] *= 1e-5          # last utterance: a near-silent onset, two samples arrive
+        mixed, gains = _run(aug, offsets, speech, noise, rir, snr)
+        ref, g_ref = O.convolve_mix_batch(offsets, speech, noise, rir.astype(np.float64), snr)
+        y = O.reverberate(offsets, speech, None, rir[:, :1].astype(np.float64))
+        worst_ordinary = 0.0
+        for u, n in enumerate(lens):
+            a, b = int(offsets[u]), int(offsets[u + 1])
+            got, want = mixed[a:b].astype(np.float64), ref[a:b]
+            if n <= 140:              # the speech never arrives: no SNR to set, gain 0, and the mixture is silence
+                assert g_ref[u, 0] == 0.0 and gains[u, 0] == 0.0
+                assert not want.any() and not got.any()
+                continue
+            e0 = float(np.sum(y[0, a:b] ** 2))
+            e_in = float(np.sum(speech[a:b].astype(np.float64) ** 2))
+            ratio = e0 / (e_in * float(np.sum(rir[u, 0].astype(np.float64) ** 2)))
+            bar = max(WAVE_TOL, 1e-6 / np.sqrt(ratio))
+            err = np.max(np.abs(got - want)) / np.sqrt(np.mean(want ** 2))
+            assert err <= bar, (seed, n, ratio, err)
+            assert abs(gains[u, 0] - g_ref[u, 0]) <= max(GAIN_TOL, 1e-6 / np.sqrt(ratio)) * g_ref[u, 0]
+            if u < len(lens) - 1:
+                assert ratio > 3e-6                           # speech-like onsets stay near the ordinary bar
+                worst_ordinary = max(worst_ordinary, err)
+            else:
+                assert ratio < 1e-9
+        print(f"  seed {seed}: worst error / RMS among speech-like slivers {worst_ordinary:.2e}", flush=True)
+        assert worst_ordinary <= 2e-4

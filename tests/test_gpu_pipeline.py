@@ -89,6 +89,16 @@ def test_batch_config_full_size(aug):
     got = _run(aug, w)
     lean = _run(aug, w, want_rir=False, want_mixed=False)
     foff = w.frame_offsets()
+    # all 128 responses of the configuration: amplitudes from the pipeline, tap counts from aug_rir_batch
+    import torch
+    from tests.parity import dev, oracle_rirs
+    h_ref, cnt_ref = oracle_rirs(w.geom, w.rir_len, w.fs, w.c)
+    cnt = torch.full((len(h_ref), w.rir_len), -7, dtype=torch.int32, device="cuda")
+    h = torch.empty((len(h_ref), w.rir_len), dtype=torch.float32, device="cuda")
+    aug.aug_rir_batch(dev(w.geom.reshape(-1, 10)), w.rir_len, w.fs, w.c, h, cnt)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(cnt.cpu().numpy(), cnt_ref)
+    assert rir_err(got["rir"].reshape(-1, w.rir_len), h_ref) <= RIR_TOL
     for u in range(0, w.n_utt, 8):
         s = w.slice([u])
         ref = _oracle(s)
@@ -106,54 +116,65 @@ def test_varlen_config_small(aug):
     _compare_unmaterialised(aug, w, ref)
 
 
-def test_varlen_full_size_sampled(aug):
-    # The benchmark's configuration and launch shape; the oracle checks sampled utterances:
-    # their responses in full (tap counts come from the rir test), the mixture through the
-    # fp64 FFT form tied to direct sums at sampled positions, and all their frames.
-    w = W.varlen()
-    print(f"case: varlen full size, {w.n_utt} utterances, {w.total} samples, L={w.rir_len}", flush=True)
+def _full_size_sampled(aug, w, picks):
+    """The whole workload in one call, as the benchmark launches it; the listed utterances against the oracle:
+    their responses (amplitudes of the pipeline's image sums, and tap counts from aug_rir_batch on the same
+    rows), gains, the whole mixture (fp64 FFT form, itself tied to direct sums at sampled positions) and all
+    their frames, for both forms of the call."""
+    import torch
+    from tests.parity import dev, oracle_utterances
     got = _run(aug, w, want_rir=True, want_mixed=True)
     assert not np.isnan(got["feats"]).any() and not np.isnan(got["mixed"]).any()
     lean = _run(aug, w, want_rir=False, want_mixed=False)       # the call the benchmark times
     assert not np.isnan(lean["feats"]).any()
+    np.testing.assert_array_equal(lean["gains"], got["gains"])
     foff = w.frame_offsets()
     lens = w.lengths()
+    refs = oracle_utterances(w, picks, conv="fft")
+    # tap counts of the picked utterances' responses, on the workload's own rooms
+    rows = np.ascontiguousarray(w.geom[picks]).reshape(-1, 10)
+    h = torch.full((len(rows), w.rir_len), float("nan"), dtype=torch.float32, device="cuda")
+    cnt = torch.full((len(rows), w.rir_len), -7, dtype=torch.int32, device="cuda")
+    aug.aug_rir_batch(dev(rows), w.rir_len, w.fs, w.c, h, cnt)
+    torch.cuda.synchronize()
+    cnt = cnt.cpu().numpy().reshape(len(picks), -1, w.rir_len)
+    h = h.cpu().numpy().reshape(len(picks), -1, w.rir_len)
     rng = np.random.default_rng(0)
-    picks = [int(np.argmin(lens)), int(np.argmax(lens)), int(rng.integers(0, w.n_utt))]
-    for u in picks:
+    for i, (u, ref) in enumerate(zip(picks, refs)):
         print(f"  utterance {u}: {lens[u]} samples", flush=True)
         s = w.slice([u])
-        ref = _oracle(s, conv="fft")
+        np.testing.assert_array_equal(cnt[i], ref["tap_count"][0])           # integer work: bit exact
+        assert rir_err(h[i], ref["rir"][0]) <= RIR_TOL
+        np.testing.assert_array_equal(h[i], got["rir"][u])                    # one image sum, whoever asks for it
         sub = dict(rir=got["rir"][u:u + 1], mixed=got["mixed"][w.offsets[u]:w.offsets[u + 1]],
                    gains=got["gains"][u:u + 1], feats=got["feats"][foff[u]:foff[u + 1]])
         _compare(sub, ref, s)
         assert feat_err(lean["feats"][foff[u]:foff[u + 1]], ref["feats"]) <= FEAT_TOL
-        pos = rng.integers(0, lens[u], 32)
-        for j in range(1 + w.n_noise):
-            x = s.speech if j == 0 else s.noise[j - 1]
-            direct = O.convolve_at(x, ref["rir"][0, j], pos)
-            np.testing.assert_allclose(O.convolve_fft(x, ref["rir"][0, j])[pos], direct, atol=1e-9)
+        if i % 4 == 0:                                                         # the FFT form of the oracle itself
+            pos = rng.integers(0, lens[u], 32)
+            for j in range(1 + w.n_noise):
+                x = s.speech if j == 0 else s.noise[j - 1]
+                direct = O.convolve_at(x, ref["rir"][0, j], pos)
+                np.testing.assert_allclose(O.convolve_fft(x, ref["rir"][0, j])[pos], direct, atol=1e-9)
+
+
+def test_varlen_full_size_sampled(aug):
+    # the benchmark's configuration and launch shape; 18 of its 256 utterances (first, last, shortest,
+    # longest and a spread in between): 72 responses of 16000 taps
+    from tests.parity import spread
+    w = W.varlen()
+    print(f"case: varlen full size, {w.n_utt} utterances, {w.total} samples, L={w.rir_len}", flush=True)
+    lens = w.lengths()
+    _full_size_sampled(aug, w, spread(w.n_utt, 16, extra=[np.argmin(lens), np.argmax(lens)]))
 
 
 def test_throughput_full_size_sampled(aug):
-    # The largest configuration (32768-tap responses in two partitions), as the benchmark launches it
-    # with --workload throughput: one sampled utterance through the oracle, features of the call that
-    # does not materialise the mixture included.
+    # the largest configuration (32768-tap responses in two partitions), as the benchmark launches it with
+    # --workload throughput; 16 of its 1024 utterances: 48 responses of 32768 taps
+    from tests.parity import spread
     w = W.throughput()
     print(f"case: throughput full size, {w.n_utt} utterances, {w.total} samples, L={w.rir_len}", flush=True)
-    got = _run(aug, w, want_rir=True, want_mixed=True)
-    assert not np.isnan(got["feats"]).any() and not np.isnan(got["mixed"]).any()
-    lean = _run(aug, w, want_rir=False, want_mixed=False)
-    assert not np.isnan(lean["feats"]).any()
-    foff = w.frame_offsets()
-    u = int(np.random.default_rng(1).integers(0, w.n_utt))
-    print(f"  utterance {u}", flush=True)
-    s = w.slice([u])
-    ref = _oracle(s, conv="fft")
-    sub = dict(rir=got["rir"][u:u + 1], mixed=got["mixed"][w.offsets[u]:w.offsets[u + 1]],
-               gains=got["gains"][u:u + 1], feats=got["feats"][foff[u]:foff[u + 1]])
-    _compare(sub, ref, s)
-    assert feat_err(lean["feats"][foff[u]:foff[u + 1]], ref["feats"]) <= FEAT_TOL
+    _full_size_sampled(aug, w, spread(w.n_utt, 16))
 
 
 @pytest.mark.parametrize("want_mixed", [False, True])

@@ -129,6 +129,20 @@ def test_very_flat_room_walks_images_directly(aug):
     _check(aug, g, 2000)
 
 
+@pytest.mark.parametrize("axis", [0, 1])
+def test_very_narrow_rooms_walk_images_directly(aug, axis):
+    # 12 cm wide along x (more than 320 x images per parity inside the response's radius: the rows of the
+    # column table do not fit) or along y (the sorted y table does not fit): both take the plain path
+    dims = [3.0, 3.2, 2.7]
+    src, mic = [1.0, 1.1, 1.0], [2.1, 2.0, 1.5]
+    dims[axis], src[axis], mic[axis] = 0.12, 0.04, 0.08
+    g = np.array([dims + src + mic + [0.5],
+                  [4.0, 3.0, 2.7, 1.0, 1.1, 1.0, 2.1, 2.0, 1.5, 0.6]], np.float32)
+    print(f"case: room 12 cm wide along axis {axis}, L=2000", flush=True)
+    _, cnt = _check(aug, g, 2000)
+    assert cnt[0].sum() > 200_000
+
+
 def test_symmetric_geometry_with_tied_distances(aug):
     # source and microphone at mid height: images above and below tie exactly in distance
     g = np.array([[4.0, 4.0, 3.0, 1.0, 2.0, 1.5, 3.0, 2.0, 1.5, 0.8],
