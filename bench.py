@@ -4,9 +4,11 @@
 A step is one aug_pipeline_batch call (impulse responses, reverberation, SNR mix,
 warped power-mel features) over one batch of seeded synthetic utterances that is
 already resident in HBM.  Prints one JSON line with the whole-call throughput in
-audio-seconds per second, the roofline of the dominant kernel (timed with HIP
-events on the library's stream inside the timed region) and the CPU oracle timed
-on a bounded sample of the same workload.
+audio-seconds per second on the variable-length workload, the roofline of its dominant
+kernel (timed with HIP events on the library's stream inside the timed region), the
+same figures for all five workloads (`per_config`), the step time when every call
+brings a batch with new lengths (`rotating`), and the CPU oracle timed on a bounded
+sample of the same workload on all host cores.
 """
 from __future__ import annotations
 
@@ -28,9 +30,13 @@ METRIC_BY_VTLP = {"mel": METRIC,
                   "waveform": "augmented audio-sec/sec (waveform VTLP+RIR+conv+mix+mel) on 1 GPU",
                   "waveform-only": "waveform-VTLP audio-sec/sec on 1 GPU"}
 PEAK_HBM_GBS = 8000.0
-PEAK_FP32_TFLOPS = 157.3
+PEAK_FP32_TFLOPS = 157.3      # vector fp32 with packed instructions; plain FMAs, all this build issues, reach 78.6
 PEAK_FP64_TFLOPS = 78.6
 RIR_FLOP_PER_IMAGE = 12.0     # 2 add, sqrt, mul, add, floor, table product, divide, scale, accumulate ...
+KERNEL_OF_STAGE = {"rir": "rir_image_kernel", "convolve": "convolve_kernel", "mel": "mel_kernel",
+                   "mix": "mix_kernel", "rir_spectrum": "rir_spectrum_kernel", "vtlp": "vtlp_resynth_kernel"}
+# timed steps per workload for the per-config figures (about a second of GPU time each)
+PER_CONFIG_STEPS = {"tiny": 300, "features": 100, "batch": 300, "varlen": 200, "throughput": 30}
 
 # HBM bytes per launch (read + written) of each stage's kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE
 # runs summarised in profiles/hbm_traffic_<workload>.md, scaled there by a 1 GiB copy.  They describe the
@@ -81,7 +87,8 @@ def conv_flop_per_sample(rir_len: int) -> float:
 
 
 def stage_work(w, n_images: float):
-    """Algorithmic work of each stage for one step: (bound, amount, unit of amount)."""
+    """Algorithmic work of each stage for one step: (bound, amount).  `n_images` is the number of image
+    sources the image-sum kernel is charged with (bench.py passes the number it actually walks)."""
     n_src = 1 + w.n_noise
     frames = int(w.frame_offsets()[-1])
     fe = w.frontend
@@ -109,54 +116,403 @@ def roofline_for(stage: str, work, ms: float):
         achieved, peak, unit, b = amount / sec / 1e12, PEAK_FP64_TFLOPS, "TFLOP/s", "alu"
     else:
         achieved, peak, unit, b = amount / sec / 1e12, PEAK_FP32_TFLOPS, "TFLOP/s", "alu"
-    return {"bound": b, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
-            "traffic": None}
+    frac = achieved / peak
+    if not frac <= 1.0:
+        raise RuntimeError(f"roofline fraction {frac:.3f} of stage {stage} exceeds 1: the work model charges "
+                           "the kernel with work it does not do")
+    return {"bound": b, "achieved": achieved, "peak": peak, "unit": unit, "frac": frac, "traffic": None}
 
 
-def cpu_baseline(w, budget_s: float = 15.0, vtlp: str = "mel", fft: bool = False):
-    """The oracle as it stands, one thread, on the first utterances of the workload: utterances are
-    fed to it one at a time until the time budget is used up.  fft=True times the oracle's own
-    FFT forms (fp64 numpy FFT convolution and STFT) instead of the direct sums."""
+# ---- CPU baseline: the oracle as it stands, one process per host core ----
+
+def _oracle_job(job):
+    """One utterance through the oracle in a worker process (one thread); returns (seconds, audio seconds)."""
+    s, vtlp, fft = job
     from oracle import aug_oracle as O
     try:
         from threadpoolctl import threadpool_limits
     except Exception:                                  # pragma: no cover
-        threadpool_limits = None
+        import contextlib
+        threadpool_limits = lambda limits: contextlib.nullcontext()
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        if vtlp != "mel":
+            from oracle import vtlp_resynth_oracle as V
+            import dataclasses
+            warped = V.vtlp_resynth_batch(s.offsets, s.speech, s.alpha)
+            s = dataclasses.replace(s, speech=warped.astype(np.float32), alpha=np.ones_like(s.alpha))
+        if vtlp == "waveform-only":
+            pass
+        elif s.geom is not None:
+            O.pipeline_batch(s.offsets, s.speech, s.noise, s.geom, s.rir_len, s.fs, s.c, s.snr_db,
+                             s.alpha, s.frontend, conv_method="fft" if fft else "direct",
+                             stft_method="fft" if fft else "dft")
+        else:
+            O.vtlp_mel_batch(s.offsets, s.speech, s.alpha, s.frontend, "fft" if fft else "dft")
+        return time.perf_counter() - t0, s.audio_seconds
 
-    def run():
-        elapsed, audio, count = 0.0, 0.0, 0
-        for u in range(w.n_utt):
-            s = w.slice([u])
-            t0 = time.perf_counter()
-            if vtlp != "mel":
-                from oracle import vtlp_resynth_oracle as V
-                import dataclasses
-                warped = V.vtlp_resynth_batch(s.offsets, s.speech, s.alpha)
-                s = dataclasses.replace(s, speech=warped.astype(np.float32), alpha=np.ones_like(s.alpha))
-            if vtlp == "waveform-only":
-                pass
-            elif s.geom is not None:
-                O.pipeline_batch(s.offsets, s.speech, s.noise, s.geom, s.rir_len, s.fs, s.c, s.snr_db,
-                                 s.alpha, s.frontend, conv_method="fft" if fft else "direct",
-                                 stft_method="fft" if fft else "dft")
-            else:
-                O.vtlp_mel_batch(s.offsets, s.speech, s.alpha, s.frontend, "fft" if fft else "dft")
-            elapsed += time.perf_counter() - t0
-            audio += s.audio_seconds
-            count += 1
-            if elapsed >= budget_s:
+
+def cpu_baseline(w, budget_s: float = 12.0, vtlp: str = "mel", fft: bool = False):
+    """The oracle, unchanged, on every host core this process may use: one worker process per core
+    (fresh interpreters, one thread each), utterances of the workload handed out one at a time from the
+    first on, for about `budget_s` seconds of wall time.  fft=True times the oracle's own FFT forms
+    (fp64 numpy FFT convolution and STFT) instead of its direct sums."""
+    import multiprocessing as mp
+    from concurrent.futures import FIRST_COMPLETED, ProcessPoolExecutor, wait
+    # the cores this process may use, capped by the machine's per-job CPU share where it states one
+    cores = len(os.sched_getaffinity(0))
+    share = os.environ.get("OMP_NUM_THREADS", "")
+    if share.isdigit() and int(share) > 0:
+        cores = min(cores, int(share))
+    done_audio, done_n, pending = 0.0, 0, set()
+    with ProcessPoolExecutor(max_workers=cores, mp_context=mp.get_context("spawn")) as ex:
+        list(ex.map(abs, range(cores)))                # workers up and imported before the clock starts
+        t0 = time.perf_counter()
+        nxt = 0
+        while True:
+            while len(pending) < cores and nxt < w.n_utt and time.perf_counter() - t0 < budget_s:
+                pending.add(ex.submit(_oracle_job, (w.slice([nxt]), vtlp, fft)))
+                nxt += 1
+            if not pending:
                 break
-        return elapsed, audio, count
-
-    if threadpool_limits is not None:
-        with threadpool_limits(limits=1):
-            dt, audio, count = run()
-    else:
-        dt, audio, count = run()
-    return {"value": audio / dt, "unit": "audio-s/s", "cores": 1, "kind": "oracle",
-            "sample": f"first {count} utterance(s) of the workload ({audio:.1f} audio-s), one at a time, "
+            finished, pending = wait(pending, return_when=FIRST_COMPLETED)
+            for f in finished:
+                done_audio += f.result()[1]
+                done_n += 1
+        dt = time.perf_counter() - t0
+    return {"value": done_audio / dt, "unit": "audio-s/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {done_n} utterance(s) of the workload ({done_audio:.1f} audio-s), one per worker "
+                      f"process at a time on {cores} cores, "
                       + ("fp64 FFT convolution + FFT front end" if fft else
-                         "direct time-domain convolution + DFT-matrix front end") + f", {dt:.1f} s"}
+                         "direct time-domain convolution + DFT-matrix front end") + f", {dt:.1f} s of wall time"}
+
+
+# ---- GPU side ----
+
+class DeviceBatch:
+    """A workload's arrays in HBM, its output buffer and the step that the benchmark times."""
+
+    def __init__(self, w, aug, vtlp="mel"):
+        import torch
+        dev = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+        self.w, self.aug, self.vtlp = w, aug, vtlp
+        self.offsets = np.ascontiguousarray(w.offsets, dtype=np.int64)
+        self.speech, self.noise, self.geom = dev(w.speech), dev(w.noise), dev(w.geom)
+        self.snr, self.alpha = dev(w.snr_db), dev(w.alpha)
+        self.foff = w.frame_offsets()
+        self.feats = torch.empty((int(self.foff[-1]), w.frontend.n_mel), dtype=torch.float32, device="cuda")
+        self.full = w.geom is not None
+        self.warped = torch.empty_like(self.speech) if vtlp != "mel" else None
+        self.ones = torch.ones_like(self.alpha)
+
+    def step(self, aug=None):
+        aug, w = aug or self.aug, self.w
+        if self.vtlp == "waveform-only":
+            aug.aug_vtlp_resynth_batch(self.offsets, self.speech, self.alpha, self.warped)
+            return
+        x, a = self.speech, self.alpha
+        if self.vtlp == "waveform":
+            aug.aug_vtlp_resynth_batch(self.offsets, self.speech, self.alpha, self.warped)
+            x, a = self.warped, self.ones
+        if self.full:
+            aug.aug_pipeline_batch(self.offsets, x, self.noise, self.geom, w.rir_len, w.fs, w.c, self.snr, a,
+                                   w.frontend, self.foff, self.feats)
+        else:
+            aug.aug_vtlp_mel_batch(self.offsets, x, a, w.frontend, self.foff, self.feats)
+
+    def trimmed(self, k: int):
+        """The same batch with every utterance 37 k samples shorter, repacked: other offsets, same rooms."""
+        import copy
+        import torch
+        w = self.w
+        cut = 37 * k
+        lens = np.maximum(w.lengths() - cut, 0)
+        off = np.zeros(w.n_utt + 1, dtype=np.int64)
+        np.cumsum(lens, out=off[1:])
+        idx = torch.from_numpy(np.concatenate([np.arange(w.offsets[u], w.offsets[u] + lens[u])
+                                               for u in range(w.n_utt)])).cuda()
+        b = copy.copy(self)
+        b.offsets = off
+        b.speech = self.speech[idx].contiguous()
+        b.noise = None if self.noise is None else self.noise[:, idx].contiguous()
+        fe = w.frontend
+        t = np.where(lens >= fe.win, 1 + (lens - fe.win) // fe.hop, 0)
+        b.foff = np.concatenate([[0], np.cumsum(t)]).astype(np.int64)
+        b.feats = torch.empty((int(b.foff[-1]), fe.n_mel), dtype=torch.float32, device="cuda")
+        b.warped = None if self.warped is None else torch.empty_like(b.speech)
+        return b
+
+
+def count_images(batch):
+    """(images of the definition with tap < L, images the amplitude kernel walks), both counted by the
+    library in untimed passes: tap_count_out summed, and the instrumented instantiation's counter."""
+    import torch
+    w, aug = batch.w, batch.aug
+    if not batch.full or batch.vtlp == "waveform-only":
+        return 0.0, 0.0
+    n_rir = w.n_utt * (1 + w.n_noise)
+    chunk = max(1, min(n_rir, (1 << 28) // w.rir_len))
+    g2 = batch.geom.reshape(-1, 10)
+    defined, visited = 0.0, 0.0
+    for a in range(0, n_rir, chunk):
+        b = min(n_rir, a + chunk)
+        h = torch.empty((b - a, w.rir_len), dtype=torch.float32, device="cuda")
+        cnt = torch.empty((b - a, w.rir_len), dtype=torch.int32, device="cuda")
+        rows = g2[a:b].contiguous()
+        aug.aug_rir_batch(rows, w.rir_len, w.fs, w.c, h, cnt)
+        defined += float(cnt.sum(dtype=torch.int64).item())
+        visited += float(aug.aug_rir_visited_images(rows, w.rir_len, w.fs, w.c, h))
+        del h, cnt
+    return defined, visited
+
+
+def timed_run(batch, steps: int, warmup: int, rotate=None):
+    """`warmup` untimed steps, then exactly `steps` timed ones between two synchronisations.  HIP events
+    around every stage hold the stream up by a few microseconds each (about 3 % of a varlen step when every
+    step carries them), so only every eighth timed step is instrumented (every step in short runs).
+    `rotate`: batches taken in turn instead of `batch` (every call then brings other offsets)."""
+    import torch
+    aug = batch.aug
+    seq = rotate or [batch]
+    for i in range(max(warmup, len(seq) if rotate else 0)):
+        seq[i % len(seq)].step()
+    torch.cuda.synchronize()
+    aug.aug_profile_read()
+    period = 8 if steps >= 40 else 1
+    timed_steps = len(range(0, steps, period))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        if i % period == 0:
+            aug.aug_profile_enable(True)
+            seq[i % len(seq)].step()
+            aug.aug_profile_enable(False)
+        else:
+            seq[i % len(seq)].step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = aug.aug_profile_read()
+    stages = {k: (ms / max(n, 1), n) for k, (ms, n) in prof.items() if n > 0}     # (ms per launch, launches)
+    return dt * 1e3 / steps, stages, timed_steps
+
+
+def summarise(batch, ms_per_step, stages, timed_steps, images, workload_name):
+    """Dominant stage, its roofline, and every stage's time and fraction."""
+    w = batch.w
+    defined, visited = images
+    work = stage_work(w, visited)
+    if batch.vtlp == "waveform-only":
+        work = {k: v for k, v in work.items() if k == "vtlp"}
+    per_step = {k: v[0] * v[1] / timed_steps for k, v in stages.items()}
+    dominant = max((k for k in stages if k in work), key=lambda k: per_step[k])
+    roof = roofline_for(dominant, work, per_step[dominant])
+    roof["kernel"] = KERNEL_OF_STAGE[dominant]
+    roof["avg_launch_ms"] = stages[dominant][0]
+    roof["traffic"] = recorded_traffic(workload_name, dominant)     # HBM bytes per launch, or null
+    if work[dominant][0] == "alu32":
+        roof["peak_note"] = "fp32 vector peak with packed FP32; this build issues plain FMAs only, which reach 78.6"
+    fracs = {k: round(roofline_for(k, work, per_step[k])["frac"], 4) for k in stages if k in work}
+    return dominant, roof, {k: round(v, 4) for k, v in per_step.items()}, fracs, work
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="varlen",
+                    choices=["tiny", "features", "batch", "varlen", "throughput"])
+    ap.add_argument("--vtlp", default="mel", choices=["mel", "waveform", "waveform-only"],
+                    help="mel: the warp is applied to the mel bank inside the front end (the headline path); "
+                         "waveform: aug_vtlp_resynth_batch on the speech first, then the same path with "
+                         "alpha = 1 (the paper's own order); waveform-only: aug_vtlp_resynth_batch alone")
+    ap.add_argument("--mics", type=int, default=0,
+                    help="time aug_rir_mics_batch alone: the workload's rooms with this many microphones in each "
+                         "(responses/s instead of the headline metric)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the step replayed from a HIP graph (extra object in the JSON line; matters for "
+                         "small batches, whose dozen launches cost as much as their kernels)")
+    ap.add_argument("--no-h2d", action="store_true",
+                    help="skip the extra, untimed-for-the-headline loop that copies the waveforms from host memory")
+    ap.add_argument("--rotate-batches", type=int, default=3,
+                    help="also time the step when K batches with different utterance lengths take turns, so that "
+                         "every call uploads new offsets and rebuilds its tables (0: skip)")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="skip the figures for the other four workloads")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one untimed 1 GiB device-to-device copy, the known-size kernel that "
+                         "FETCH_SIZE / WRITE_SIZE readings are scaled by")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this path runs on one GPU (utterances are independent; there is nothing to "
+              "exchange), so --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_1912_11040_amd import workloads as W
+    from paper_1912_11040_amd.binding import Augmenter
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+
+    w = W.WORKLOADS[args.workload]()
+    aug = Augmenter(0)
+    if args.mics > 0:
+        if w.geom is None:
+            print("bench.py: --mics needs a workload with rooms", file=sys.stderr)
+            return 2
+        print(json.dumps(bench_mics(args, w, aug)))
+        aug.close()
+        return 0
+
+    batch = DeviceBatch(w, aug, args.vtlp)
+    images = count_images(batch)
+
+    if args.copy_probe:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    ms_per_step, stages, timed_steps = timed_run(batch, args.steps, args.warmup)
+    dominant, roof, stage_ms, stage_frac, work = summarise(batch, ms_per_step, stages, timed_steps, images, args.workload)
+
+    rotating = None
+    if args.rotate_batches > 0 and args.vtlp == "mel":
+        # the largest batch first, so that the workspace is sized once
+        others = [batch] + [batch.trimmed(k) for k in range(1, args.rotate_batches)]
+        r_steps = max(len(others), min(args.steps, 60))
+        r_ms, _, _ = timed_run(batch, r_steps, args.warmup, rotate=others)
+        audio = sum(int(b.offsets[-1]) for b in others) / len(others) / w.fs
+        rotating = {"batches": len(others), "steps": r_steps, "ms_per_step": r_ms, "value": audio / (r_ms * 1e-3),
+                    "vs_steady_state": r_ms / ms_per_step * (w.audio_seconds / audio),
+                    "note": "the workload and copies of it with every utterance 37 k samples shorter take turns: "
+                            "every call has other offsets than the one before"}
+        del others
+
+    ms_with_h2d = None
+    if not args.no_h2d:
+        # The same step when the waveforms start in pinned host memory (never `value`: the boundary takes
+        # device pointers): host-to-device copies of speech and noise, then the call.
+        h_speech = torch.from_numpy(np.ascontiguousarray(w.speech)).pin_memory()
+        h_noise = None if w.noise is None else torch.from_numpy(np.ascontiguousarray(w.noise)).pin_memory()
+        reps = max(3, min(10, args.steps))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            batch.speech.copy_(h_speech, non_blocking=True)
+            if h_noise is not None:
+                batch.noise.copy_(h_noise, non_blocking=True)
+            batch.step()
+        torch.cuda.synchronize()
+        ms_with_h2d = (time.perf_counter() - t0) * 1e3 / reps
+        del h_speech, h_noise
+    graph_ms = None
+    if args.graph:
+        # the library's context runs on torch's current stream; capture needs a stream of its own
+        side = torch.cuda.Stream()
+        aug_g = Augmenter(0, side)
+        with torch.cuda.stream(side):
+            batch.step(aug_g)                            # sizes this context's workspace, uploads its tables
+            side.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                batch.step(aug_g)
+        for _ in range(args.warmup):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        del g
+        aug_g.close()
+
+    full = batch.full
+    foff = batch.foff
+    out = {
+        "metric": METRIC_BY_VTLP[args.vtlp],
+        "value": w.audio_seconds / (ms_per_step * 1e-3),
+        "unit": "audio-s/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": describe(w),
+                   "entry_point": {"mel": "", "waveform": "aug_vtlp_resynth_batch + ",
+                                   "waveform-only": "aug_vtlp_resynth_batch"}[args.vtlp] +
+                                  ("" if args.vtlp == "waveform-only" else
+                                   "aug_pipeline_batch" if full else "aug_vtlp_mel_batch"),
+                   "vtlp": args.vtlp, "images_defined": images[0], "images_visited": images[1]},
+        "roofline": roof,
+        "rotating": rotating,
+        "with_h2d": None if ms_with_h2d is None else
+                    {"ms_per_step": ms_with_h2d, "value": w.audio_seconds / (ms_with_h2d * 1e-3),
+                     "note": "waveforms copied from pinned host memory before every call; not the headline"},
+        "graph": None if graph_ms is None else
+                 {"ms_per_step": graph_ms, "value": w.audio_seconds / (graph_ms * 1e-3),
+                  "note": "the same step replayed from a HIP graph"},
+        "stage_ms": stage_ms,
+        "stage_timed_steps": timed_steps,
+        "stage_roofline_frac": stage_frac,
+    }
+    # The whole step against the chip: all stages' algorithmic flops over the step time against the fp32
+    # vector peak (the image sum's fp64 flops count once each, on the images it walks), and the bytes that
+    # must cross HBM at least once (inputs in, features out) against the HBM peak.
+    # front end: 2.5 K log2 K for the real transform + window + bin powers + sparse mel + power law, per frame
+    front_flop_per_frame = 2.5 * 512 * 9 + 400 + 771 + 1028 + 80
+    flops = sum(amount for k, (bound, amount) in work.items() if bound != "hbm" and k in stages)
+    if "mel" in stages:
+        flops += front_flop_per_frame * float(foff[-1])
+    n_src_in = 1 + (w.n_noise if full and args.vtlp != "waveform-only" else 0)
+    min_bytes = 4.0 * w.total * n_src_in + (4.0 * w.total if args.vtlp == "waveform-only"
+                                             else 4.0 * w.frontend.feature_dim * float(foff[-1]))
+    out["path_roofline"] = {
+        "flops_per_step": flops, "achieved_tflops": flops / (ms_per_step * 1e-3) / 1e12,
+        "frac_of_fp32_peak": flops / (ms_per_step * 1e-3) / 1e12 / PEAK_FP32_TFLOPS,
+        "min_hbm_bytes_per_step": min_bytes, "achieved_gbs": min_bytes / (ms_per_step * 1e-3) / 1e9,
+        "frac_of_hbm_peak": min_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
+    }
+
+    if not args.no_per_config and args.vtlp == "mel":
+        per = {args.workload: {"workload": describe(w), "steps": args.steps, "ms_per_step": ms_per_step,
+                               "value": out["value"], "dominant_kernel": roof["kernel"], "bound": roof["bound"],
+                               "frac": roof["frac"], "stage_ms": stage_ms}}
+        del batch
+        torch.cuda.empty_cache()
+        for name in ("tiny", "features", "batch", "varlen", "throughput"):
+            if name in per:
+                continue
+            wn = W.WORKLOADS[name]()
+            bn = DeviceBatch(wn, aug)
+            img = count_images(bn)
+            n_steps = PER_CONFIG_STEPS[name]
+            ms, st, ts = timed_run(bn, n_steps, 3)
+            _, rf, sms, _, _ = summarise(bn, ms, st, ts, img, name)
+            per[name] = {"workload": describe(wn), "steps": n_steps, "ms_per_step": ms,
+                         "value": wn.audio_seconds / (ms * 1e-3), "dominant_kernel": rf["kernel"],
+                         "bound": rf["bound"], "frac": rf["frac"], "stage_ms": sms}
+            del bn, wn
+            torch.cuda.empty_cache()
+        out["per_config"] = {k: per[k] for k in ("tiny", "features", "batch", "varlen", "throughput")}
+    aug.close()
+
+    if not args.no_cpu_baseline:
+        # the oracle's direct sums (the definition), then, as context, its own FFT forms, which is what a
+        # sensible CPU program would run; both on all host cores
+        out["cpu_baseline"] = cpu_baseline(w, vtlp=args.vtlp)
+        out["cpu_baseline_fft"] = cpu_baseline(w, budget_s=8.0, vtlp=args.vtlp, fft=True)
+    print(json.dumps(out))
+    return 0
 
 
 def bench_mics(args, w, aug) -> dict:
@@ -188,7 +544,16 @@ def bench_mics(args, w, aug) -> dict:
     aug.aug_profile_enable(False)
     ms_per_step = dt * 1e3 / args.steps
     rir_ms = prof["rir"][0] / max(prof["rir"][1], 1)
-    flops = RIR_FLOP_PER_IMAGE * n_images
+    # one-microphone time of the same rooms, for the ratio
+    one = torch.empty((n_rir, L), dtype=torch.float32, device="cuda")
+    for _ in range(args.warmup):
+        aug.aug_rir_batch(geom, L, w.fs, w.c, one)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        aug.aug_rir_batch(geom, L, w.fs, w.c, one)
+    torch.cuda.synchronize()
+    one_ms = (time.perf_counter() - t0) * 1e3 / args.steps
     res = {
         "metric": f"image-method responses/sec, {K} microphones per room, on 1 GPU",
         "value": n_rir * K / (ms_per_step * 1e-3), "unit": "responses/s", "n_gpus": 1, "steps": args.steps,
@@ -196,10 +561,9 @@ def bench_mics(args, w, aug) -> dict:
         "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"rooms and sources of {describe(w)}; {K} microphones 6.8 cm apart in each; "
                                f"{n_rir} x {K} responses of {L} taps", "entry_point": "aug_rir_mics_batch",
-                   "images_per_step": n_images},
-        "roofline": {"bound": "alu", "achieved": flops / (rir_ms * 1e-3) / 1e12, "peak": PEAK_FP64_TFLOPS,
-                     "unit": "TFLOP/s", "frac": flops / (rir_ms * 1e-3) / 1e12 / PEAK_FP64_TFLOPS, "traffic": None,
-                     "kernel": "rir_image_kernel", "avg_launch_ms": rir_ms},
+                   "images_defined": n_images},
+        "one_microphone_ms_per_step": one_ms, "ratio_to_one_microphone": ms_per_step / one_ms,
+        "rir_kernel_ms": rir_ms,
         "stage_ms": {k: round(ms / args.steps, 4) for k, (ms, n) in prof.items() if n > 0},
     }
     if not args.no_cpu_baseline:
@@ -212,233 +576,6 @@ def bench_mics(args, w, aug) -> dict:
         res["cpu_baseline"] = {"value": done * K / dt, "unit": "responses/s", "cores": 1, "kind": "oracle",
                                "sample": f"first {done} room(s) of the workload, {K} microphones each, {dt:.1f} s"}
     return res
-
-
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="varlen",
-                    choices=["tiny", "features", "batch", "varlen", "throughput"])
-    ap.add_argument("--vtlp", default="mel", choices=["mel", "waveform", "waveform-only"],
-                    help="mel: the warp is applied to the mel bank inside the front end (the headline path); "
-                         "waveform: aug_vtlp_resynth_batch on the speech first, then the same path with "
-                         "alpha = 1 (the paper's own order); waveform-only: aug_vtlp_resynth_batch alone")
-    ap.add_argument("--mics", type=int, default=0,
-                    help="time aug_rir_mics_batch alone: the workload's rooms with this many microphones in each "
-                         "(responses/s instead of the headline metric)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--graph", action="store_true",
-                    help="also time the step replayed from a HIP graph (extra object in the JSON line; matters for "
-                         "small batches, whose dozen launches cost as much as their kernels)")
-    ap.add_argument("--no-h2d", action="store_true",
-                    help="skip the extra, untimed-for-the-headline loop that copies the waveforms from host memory")
-    ap.add_argument("--copy-probe", action="store_true",
-                    help="also run one untimed 1 GiB device-to-device copy, the known-size kernel that "
-                         "FETCH_SIZE / WRITE_SIZE readings are scaled by")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this path runs on one GPU (utterances are independent; there is nothing to "
-              "exchange), so --gpus must be 1", file=sys.stderr)
-        return 2
-
-    import torch
-    from paper_1912_11040_amd import workloads as W
-    from paper_1912_11040_amd.binding import Augmenter
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 2
-
-    w = W.WORKLOADS[args.workload]()
-    dev = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
-    speech, noise, geom = dev(w.speech), dev(w.noise), dev(w.geom)
-    snr, alpha = dev(w.snr_db), dev(w.alpha)
-    foff = w.frame_offsets()
-    feats = torch.empty((int(foff[-1]), w.frontend.n_mel), dtype=torch.float32, device="cuda")
-    full = w.geom is not None
-
-    aug = Augmenter(0)
-    if args.mics > 0:
-        if not full:
-            print("bench.py: --mics needs a workload with rooms", file=sys.stderr)
-            return 2
-        print(json.dumps(bench_mics(args, w, aug)))
-        aug.close()
-        return 0
-    warped = torch.empty_like(speech) if args.vtlp != "mel" else None
-    ones = torch.ones_like(alpha)
-
-    def step():
-        if args.vtlp == "waveform-only":
-            aug.aug_vtlp_resynth_batch(w.offsets, speech, alpha, warped)
-            return
-        x, a = speech, alpha
-        if args.vtlp == "waveform":
-            aug.aug_vtlp_resynth_batch(w.offsets, speech, alpha, warped)
-            x, a = warped, ones
-        if full:
-            aug.aug_pipeline_batch(w.offsets, x, noise, geom, w.rir_len, w.fs, w.c, snr, a,
-                                   w.frontend, foff, feats)
-        else:
-            aug.aug_vtlp_mel_batch(w.offsets, x, a, w.frontend, foff, feats)
-
-    # images per step, for the image-sum kernel's algorithmic work (counted once, untimed)
-    n_images = 0.0
-    if full and args.vtlp != "waveform-only":
-        n_rir = w.n_utt * (1 + w.n_noise)
-        chunk = max(1, min(n_rir, (1 << 28) // w.rir_len))
-        g2 = geom.reshape(-1, 10)
-        for a in range(0, n_rir, chunk):
-            b = min(n_rir, a + chunk)
-            h = torch.empty((b - a, w.rir_len), dtype=torch.float32, device="cuda")
-            cnt = torch.empty((b - a, w.rir_len), dtype=torch.int32, device="cuda")
-            aug.aug_rir_batch(g2[a:b].contiguous(), w.rir_len, w.fs, w.c, h, cnt)
-            n_images += float(cnt.sum(dtype=torch.int64).item())
-            del h, cnt
-
-    if args.copy_probe:
-        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    aug.aug_profile_read()
-    # HIP events around every stage hold the stream up by a few microseconds each (about 3 % of a varlen
-    # step when every step carries them), so inside the timed region only every eighth step is
-    # instrumented; runs too short for that instrument every step.
-    period = 8 if args.steps >= 40 else 1
-    timed_steps = len(range(0, args.steps, period))
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        if i % period == 0:
-            aug.aug_profile_enable(True)
-            step()
-            aug.aug_profile_enable(False)
-        else:
-            step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    prof = aug.aug_profile_read()
-
-    ms_per_step = dt * 1e3 / args.steps
-
-    ms_with_h2d = None
-    if not args.no_h2d:
-        # The same step when the waveforms start in pinned host memory (never `value`: the boundary takes
-        # device pointers): host-to-device copies of speech and noise, then the call.
-        h_speech = torch.from_numpy(np.ascontiguousarray(w.speech)).pin_memory()
-        h_noise = None if w.noise is None else torch.from_numpy(np.ascontiguousarray(w.noise)).pin_memory()
-        reps = max(3, min(10, args.steps))
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(reps):
-            speech.copy_(h_speech, non_blocking=True)
-            if h_noise is not None:
-                noise.copy_(h_noise, non_blocking=True)
-            step()
-        torch.cuda.synchronize()
-        ms_with_h2d = (time.perf_counter() - t0) * 1e3 / reps
-        del h_speech, h_noise
-    graph_ms = None
-    if args.graph:
-        # the library's context runs on torch's current stream; capture needs a stream of its own
-        side = torch.cuda.Stream()
-        aug_g = Augmenter(0, side)
-        with torch.cuda.stream(side):
-            saved, aug = aug, aug_g
-            try:
-                step()                                   # sizes this context's workspace, uploads its tables
-                side.synchronize()
-                g = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(g, stream=side):
-                    step()
-            finally:
-                aug = saved
-        for _ in range(args.warmup):
-            g.replay()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            g.replay()
-        torch.cuda.synchronize()
-        graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-        del g
-        aug_g.close()
-    stages = {k: (ms / max(n, 1), n) for k, (ms, n) in prof.items() if n > 0}
-    work = stage_work(w, n_images)
-    if args.vtlp == "waveform-only":
-        work = {k: v for k, v in work.items() if k == "vtlp"}
-    dominant = max((k for k in stages if k in work), key=lambda k: stages[k][0] * stages[k][1])
-    per_step_launches = stages[dominant][1] / timed_steps
-    roof = roofline_for(dominant, work, stages[dominant][0] * per_step_launches)
-    roof["kernel"] = {"rir": "rir_image_kernel", "convolve": "convolve_kernel", "mel": "mel_kernel",
-                      "mix": "mix_kernel", "rir_spectrum": "rir_spectrum_kernel",
-                      "vtlp": "vtlp_resynth_kernel"}[dominant]
-    roof["avg_launch_ms"] = stages[dominant][0]
-    roof["traffic"] = recorded_traffic(args.workload, dominant)     # HBM bytes per launch, or null
-
-    out = {
-        "metric": METRIC_BY_VTLP[args.vtlp],
-        "value": w.audio_seconds / (ms_per_step * 1e-3),
-        "unit": "audio-s/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "f32",
-        "data": "synthetic",
-        "config": {"workload": describe(w),
-                   "entry_point": {"mel": "", "waveform": "aug_vtlp_resynth_batch + ",
-                                   "waveform-only": "aug_vtlp_resynth_batch"}[args.vtlp] +
-                                  ("" if args.vtlp == "waveform-only" else
-                                   "aug_pipeline_batch" if full else "aug_vtlp_mel_batch"),
-                   "vtlp": args.vtlp, "images_per_step": n_images},
-        "roofline": roof,
-        "with_h2d": None if ms_with_h2d is None else
-                    {"ms_per_step": ms_with_h2d, "value": w.audio_seconds / (ms_with_h2d * 1e-3),
-                     "note": "waveforms copied from pinned host memory before every call; not the headline"},
-        "graph": None if graph_ms is None else
-                 {"ms_per_step": graph_ms, "value": w.audio_seconds / (graph_ms * 1e-3),
-                  "note": "the same step replayed from a HIP graph"},
-        "stage_ms": {k: round(v[0] * v[1] / timed_steps, 4) for k, v in stages.items()},
-        "stage_timed_steps": timed_steps,
-        "stage_roofline_frac": {k: round(roofline_for(k, work, stages[k][0] * stages[k][1] / timed_steps)["frac"], 4)
-                                for k in stages if k in work},
-    }
-    # The whole step against the chip: all stages' algorithmic flops over the step time against the fp32
-    # vector peak (the image sum's fp64 flops count once each), and the bytes that must cross HBM at least
-    # once (inputs in, features out) against the HBM peak.
-    # front end: 2.5 K log2 K for the real transform + window + bin powers + sparse mel + power law, per frame
-    front_flop_per_frame = 2.5 * 512 * 9 + 400 + 771 + 1028 + 80
-    flops = sum(amount for k, (bound, amount) in work.items() if bound != "hbm" and k in stages)
-    if "mel" in stages:
-        flops += front_flop_per_frame * float(foff[-1])
-    n_src_in = 1 + (w.n_noise if full and args.vtlp != "waveform-only" else 0)
-    min_bytes = 4.0 * w.total * n_src_in + (4.0 * w.total if args.vtlp == "waveform-only"
-                                             else 4.0 * w.frontend.feature_dim * float(foff[-1]))
-    out["path_roofline"] = {
-        "flops_per_step": flops, "achieved_tflops": flops / (ms_per_step * 1e-3) / 1e12,
-        "frac_of_fp32_peak": flops / (ms_per_step * 1e-3) / 1e12 / PEAK_FP32_TFLOPS,
-        "min_hbm_bytes_per_step": min_bytes, "achieved_gbs": min_bytes / (ms_per_step * 1e-3) / 1e9,
-        "frac_of_hbm_peak": min_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
-    }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, vtlp=args.vtlp)
-        # context only: the same oracle with its FFT forms, which is what a sensible CPU program would run
-        out["cpu_baseline_fft"] = cpu_baseline(w, budget_s=8.0, vtlp=args.vtlp, fft=True)
-    aug.close()
-    print(json.dumps(out))
-    return 0
 
 
 if __name__ == "__main__":

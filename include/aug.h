@@ -329,6 +329,16 @@ enum {
     AUG_STAGE_VTLP,           /* waveform VTLP (aug_vtlp_resynth_batch) */
     AUG_N_STAGES
 };
+/*
+ * Measurement helper for the image sum: runs aug_rir_batch's amplitude pass in an instrumented
+ * instantiation, waits for it, and returns in *visited_out (HOST) how many image sources the kernel
+ * actually walked.  That is fewer than the images the definition sums over (those are what
+ * tap_count_out adds up to): images whose amplitude beta^k / (4 pi d) is too small to change the sum
+ * are skipped.  rir_out (DEVICE float [n_rir][rir_len]) receives the responses as usual.
+ */
+int aug_rir_visited_images(aug_ctx* ctx, int n_rir, const float* geom, int rir_len, float fs, float c,
+                           float* rir_out, uint64_t* visited_out);
+
 int aug_profile_enable(aug_ctx* ctx, int on);
 int aug_profile_read(aug_ctx* ctx, float* ms_out, int32_t* launches_out);
 

@@ -25,7 +25,7 @@ EXPORTS = ("aug_create", "aug_destroy", "aug_last_error", "aug_frame_count", "au
            "aug_rir_mics_batch",
            "aug_convolve_mix_batch", "aug_vtlp_mel_batch", "aug_vtlp_mel_batch_static", "aug_vtlp_resynth_batch",
            "aug_pipeline_batch",
-           "aug_profile_enable", "aug_profile_read")
+           "aug_profile_enable", "aug_profile_read", "aug_rir_visited_images")
 
 FEATURE_KINDS = {"power": 0, "log": 1, "mfcc": 2}      # AUG_FEAT_*
 
@@ -99,6 +99,8 @@ def load_library() -> ctypes.CDLL:
     lib.aug_pipeline_batch.argtypes = [vp, ci, p_i64, vp, ci, vp, vp, ci, cf, cf, vp, vp, p_cfg,
                                        p_i64, vp, vp, vp, vp]
     lib.aug_pipeline_batch.restype = ci
+    lib.aug_rir_visited_images.argtypes = [vp, ci, vp, ci, cf, cf, vp, ctypes.POINTER(ctypes.c_uint64)]
+    lib.aug_rir_visited_images.restype = ci
     lib.aug_profile_enable.argtypes = [vp, ci]
     lib.aug_profile_enable.restype = ci
     lib.aug_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int32)]
@@ -267,6 +269,18 @@ class Augmenter:
         self._check(self._lib.aug_rir_batch(
             self._h, n_rir, _ptr(geom, torch.float32), int(rir_len), float(fs), float(c),
             _ptr(rir_out, torch.float32), _ptr(tap_count_out, torch.int32)))
+
+    def aug_rir_visited_images(self, geom, rir_len: int, fs: float, c: float, rir_out) -> int:
+        """Images the amplitude kernel walks for these rooms (measurement helper; waits for the stream)."""
+        import torch
+        if self._check_sizes:
+            check_rir_sizes(geom, rir_len, rir_out, None)
+        n_rir = int(geom.numel() // 10) if geom is not None else 0
+        n = ctypes.c_uint64(0)
+        self._check(self._lib.aug_rir_visited_images(
+            self._h, n_rir, _ptr(geom, torch.float32), int(rir_len), float(fs), float(c),
+            _ptr(rir_out, torch.float32), ctypes.byref(n)))
+        return int(n.value)
 
     def aug_rir_mics_batch(self, geom, mics, rir_len: int, fs: float, c: float, rir_out, tap_count_out=None,
                            n_mic: Optional[int] = None):

@@ -552,7 +552,7 @@ int aug_destroy(aug_ctx* ctx) {
     }
     DeviceBuffer* bufs[] = {&ctx->d_offsets, &ctx->d_frame_offsets, &ctx->d_conv_items, &ctx->d_frame_items,
                             &ctx->d_conv_first, &ctx->d_frame_first,
-                            &ctx->rir_items, &ctx->rir_ctrl, &ctx->rir_pow, &ctx->mic_rows, &ctx->rir, &ctx->rir_spec, &ctx->reverb, &ctx->energy, &ctx->gains, &ctx->first_tap, &ctx->vtlp_tab, &ctx->dct, &ctx->mel_tab,
+                            &ctx->rir_items, &ctx->rir_ctrl, &ctx->rir_pow, &ctx->mic_rows, &ctx->visits, &ctx->rir, &ctx->rir_spec, &ctx->reverb, &ctx->energy, &ctx->gains, &ctx->first_tap, &ctx->vtlp_tab, &ctx->dct, &ctx->mel_tab,
                             &ctx->window};
     for (DeviceBuffer* b : bufs) b->release();
     for (DeviceBuffer& b : ctx->twiddle) b.release();
@@ -611,6 +611,34 @@ int aug_rir_batch(aug_ctx* ctx, int n_rir, const float* geom, int rir_len, float
     if ((int64_t)n_rir * aug::rir_items_per_response(rir_len) > 0x7fffffffLL)
         return fail(ctx, AUG_ERR_UNSUPPORTED, "too many responses in one call");
     return run_rir(ctx, n_rir, geom, rir_len, fs, c, rir_out, tap_count_out);
+}
+
+int aug_rir_visited_images(aug_ctx* ctx, int n_rir, const float* geom, int rir_len, float fs, float c,
+                           float* rir_out, uint64_t* visited_out) {
+    AUG_TRY(enter(ctx));
+    if (n_rir < 0) return fail(ctx, AUG_ERR_INVALID_ARG, "n_rir is negative");
+    AUG_TRY(check_rir_args(ctx, rir_len, fs, c));
+    if (!visited_out) return fail(ctx, AUG_ERR_INVALID_ARG, "visited_out is null");
+    *visited_out = 0;
+    if (n_rir == 0) return AUG_OK;
+    if (!geom || !rir_out) return fail(ctx, AUG_ERR_INVALID_ARG, "geom or rir_out is null");
+    if ((int64_t)n_rir * aug::rir_items_per_response(rir_len) > 0x7fffffffLL)
+        return fail(ctx, AUG_ERR_UNSUPPORTED, "too many responses in one call");
+    AUG_TRY(prepare_rir(ctx, n_rir, rir_len));
+    AUG_TRY(grow(ctx, ctx->visits, sizeof(unsigned long long), "visit counter"));
+    const double k = (double)fs / (double)c;
+    const int n_groups = 2 * ctx->n_cu;
+    AUG_HIP(aug::launch_fill_u32(ctx->stream, ctx->visits.ptr, 0u, 2), "visit counter clear");
+    AUG_HIP(aug::launch_rir_plan(ctx->stream, n_groups, n_rir, geom, rir_len, k, ctx->rir_items.ptr,
+                                 ctx->rir_ctrl.as<int>(), ctx->rir_pow.as<float>()), "rir plan kernel");
+    AUG_HIP(aug::launch_rir(ctx->stream, n_groups, n_rir, geom, rir_len, k, ctx->rir_items.ptr, ctx->rir_ctrl.as<int>(),
+                            ctx->rir_pow.as<float>(), rir_out, nullptr, false, ctx->visits.as<unsigned long long>()),
+            "rir kernel");
+    unsigned long long v = 0;
+    AUG_HIP(hipMemcpyAsync(&v, ctx->visits.ptr, sizeof v, hipMemcpyDeviceToHost, ctx->stream), "visit counter copy");
+    AUG_HIP(hipStreamSynchronize(ctx->stream), "stream synchronize");
+    *visited_out = v;
+    return AUG_OK;
 }
 
 int aug_rir_mics_batch(aug_ctx* ctx, int n_rir, int n_mic, const float* geom, const float* mics, int rir_len,

@@ -66,6 +66,7 @@ struct aug_ctx {
     aug::DeviceBuffer rir_items;         // Item [n_rir * items_per_response]
     aug::DeviceBuffer rir_ctrl;          // int [rir_ctrl_ints()]: item count, next item, class counters
     aug::DeviceBuffer rir_pow;           // float [n_rir][pow entries]: beta^k
+    aug::DeviceBuffer visits;            // one 64-bit counter (aug_rir_visited_images)
     aug::DeviceBuffer mic_rows;          // float [n_rir * n_mic][10]: one geometry row per microphone
 
     // intermediate results
@@ -98,6 +99,8 @@ namespace aug {
 // launch_rir then runs n_groups persistent work groups over the items (restart: once more over the
 // same plan), writing either
 // rir_out float [n_rir][rir_len] or, if rir_out is null, tap counts cnt_out int32 [n_rir][rir_len].
+// With `visits` (device, one 64-bit counter, zero on entry) the amplitude pass runs in a measuring
+// instantiation that adds the number of images it walked.
 int rir_items_per_response(int rir_len);
 size_t rir_item_bytes();
 int rir_ctrl_ints();
@@ -106,7 +109,7 @@ hipError_t launch_rir_plan(hipStream_t s, int n_groups, int n_rir, const float* 
                            void* items, int* ctrl, float* pow_table);
 hipError_t launch_rir(hipStream_t s, int n_groups, int n_rir, const float* geom, int rir_len, double fs_over_c,
                       const void* items, int* ctrl, const float* pow_table, float* rir_out, int32_t* cnt_out,
-                      bool restart);
+                      bool restart, unsigned long long* visits = nullptr);
 
 // rows float [n_rir * n_mic][10]: geometry row r / n_mic with microphone mics[r] (float [n_rir][n_mic][3]).
 hipError_t launch_rir_mic_rows(hipStream_t s, int n_rir, int n_mic, const float* geom, const float* mics, float* rows);

@@ -446,11 +446,12 @@ __device__ inline int count_below(const AxisCount& a, double bound) {
     return s > 0.0 ? count_within(a, s) : 0;
 }
 
-template <bool COUNT>
+// VISITS: a measuring instantiation that also adds the number of images it walked to *visits.
+template <bool COUNT, bool VISITS = false>
 __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
     const float* __restrict__ geom, int rir_len, double k_fs_c, const Item* __restrict__ items,
     int* __restrict__ ctrl, const float* __restrict__ pow_table, float* __restrict__ rir_out,
-    int32_t* __restrict__ cnt_out) {
+    int32_t* __restrict__ cnt_out, unsigned long long* __restrict__ visits = nullptr) {
     __shared__ unsigned long long hist[(COUNT ? kMaxTaps / 2 : kMaxTaps) + 1];     // slot 0 is never read
     __shared__ float bpow[COUNT ? 1 : kPow];
     __shared__ AxisImage ztab[2 * kAxisCap];       // z images sorted by dz*dz
@@ -463,6 +464,7 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n_items = ctrl[0];
+    unsigned long long walked = 0;
 
     for (;;) {
         if (tid == 0) s_item = atomicAdd(&ctrl[1], 1);
@@ -635,8 +637,10 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
                         const int first = (int)c.start + local * kPiece;
                         const int len = min(kPiece, (int)c.len - local * kPiece);
                         walk_piece_table<COUNT>(wctx, c.a, cxy, ztab + first, len, hist, hist32);
+                        if (VISITS) walked += (unsigned long long)len;
                     } else {
                         walk_column_direct<COUNT>(wctx, az, c.a, cxy, nmz, hist, hist32);
+                        if (VISITS) walked += (unsigned long long)niz;
                     }
                 }
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -658,6 +662,10 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
             }
         }
         __syncthreads();
+    }
+    if (VISITS) {
+        for (int off = 32; off > 0; off >>= 1) walked += __shfl_down(walked, off, 64);
+        if (lane == 0 && walked) atomicAdd(visits, walked);
     }
 }
 
@@ -742,7 +750,7 @@ hipError_t launch_rir_plan(hipStream_t s, int n_groups, int n_rir, const float* 
 
 hipError_t launch_rir(hipStream_t s, int n_groups, int n_rir, const float* geom, int rir_len, double fs_over_c,
                       const void* items, int* ctrl, const float* pow_table, float* rir_out, int32_t* cnt_out,
-                      bool restart) {
+                      bool restart, unsigned long long* visits) {
     if (n_rir <= 0) return hipSuccess;
     hipError_t e = hipSuccess;
     if (restart) {                                           // another pass over the same plan
@@ -750,7 +758,10 @@ hipError_t launch_rir(hipStream_t s, int n_groups, int n_rir, const float* geom,
         if (e != hipSuccess) return e;
     }
     const Item* it = static_cast<const Item*>(items);
-    if (rir_out)
+    if (rir_out && visits)
+        rir_image_kernel<false, true><<<dim3((unsigned)n_groups), dim3(kThreads), 0, s>>>(
+            geom, rir_len, fs_over_c, it, ctrl, pow_table, rir_out, nullptr, visits);
+    else if (rir_out)
         rir_image_kernel<false><<<dim3((unsigned)n_groups), dim3(kThreads), 0, s>>>(
             geom, rir_len, fs_over_c, it, ctrl, pow_table, rir_out, nullptr);
     else
