@@ -401,6 +401,7 @@ int run_convolve_mix(aug_ctx* ctx, int n_utt, int n_noise, const float* speech, 
     aug::ConvArgs ca;
     ca.offsets = ctx->d_offsets.as<int64_t>();
     ca.items = ctx->d_conv_items.as<int2>();
+    ca.first = ctx->d_conv_first.as<int>();
     ca.n_items = pk.n_conv_blocks;
     ca.n_src = n_src;
     ca.speech = speech;
@@ -412,7 +413,7 @@ int run_convolve_mix(aug_ctx* ctx, int n_utt, int n_noise, const float* speech, 
     ca.reverb_stride = stride;
     ca.energy = energy;
     ca.first_tap = ctx->first_tap.as<int>();
-    AUG_HIP(aug::launch_convolve(ctx->stream, fft_n, tw, ca), "convolution kernel");
+    AUG_HIP(aug::launch_convolve(ctx->stream, fft_n, tw, ca, ctx->n_cu), "convolution kernel");
     AUG_TRY(mark(ctx, AUG_STAGE_CONVOLVE));
     AUG_HIP(aug::launch_gains(ctx->stream, n_utt, n_src, energy, snr_db, ctx->gains.as<float>(), gains_out), "gain kernel");
     if (mixed_out)

@@ -127,7 +127,8 @@ hipError_t launch_rir_spectrum(hipStream_t s, int n_rir, const float* rir, int r
 struct ConvArgs {
     const int64_t* offsets;      // device
     const int2* items;           // device (utterance, block)
-    int64_t n_items;
+    const int* first;            // device [n_utt+1]: blocks of the utterances before u
+    int64_t n_items;             // blocks of one source, all utterances
     int n_src;
     const float* speech;
     const float* noise;          // [n_src-1][total]
@@ -139,7 +140,8 @@ struct ConvArgs {
     double* energy;              // [n_utt][n_src] of the reverberated signals
     const int* first_tap;        // [n_utt][n_src] first non-zero tap of each response
 };
-hipError_t launch_convolve(hipStream_t s, int fft_n, const float2* twiddle, const ConvArgs& a);
+// n_cu: compute units of the device (the kernel runs as persistent work groups)
+hipError_t launch_convolve(hipStream_t s, int fft_n, const float2* twiddle, const ConvArgs& a, int n_cu);
 
 // gains [n_utt][n_src - 1] from the energies and the target SNRs (also copied to gains_out when given)
 // energy: [n_utt][n_src] energies of the reverberated signals

@@ -131,144 +131,298 @@ __device__ inline void multiply_pair(float2 A, float2 B, float2 w, float2 Hk, fl
     ZNk = make_float2(Ye.x + Yo.y, Yo.x - Ye.y);     // conj(Ye) + i conj(Yo)
 }
 
-constexpr int kXcds = 8;
-
 // two consecutive samples; only their 4-byte alignment is promised (global accesses of two dwords need no more)
 struct __attribute__((aligned(4))) SamplePair { float x, y; };
 
-// MULTI: the response has several partitions.
+// Accesses at a per-lane 32-bit byte offset from a wave-uniform base: the address is then a scalar register
+// pair plus one vector register, with no 64-bit vector arithmetic per access.
+__device__ inline SamplePair load_pair(const float* base, uint32_t byte_off) {
+    return *reinterpret_cast<const SamplePair*>(reinterpret_cast<const char*>(base) + byte_off);
+}
+__device__ inline float load_sample(const float* base, uint32_t byte_off) {
+    return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(base) + byte_off);
+}
+__device__ inline float2 load_bin(const float2* base, uint32_t byte_off) {
+    return *reinterpret_cast<const float2*>(reinterpret_cast<const char*>(base) + byte_off);
+}
+
+// One block of one (utterance, source): everything here is the same for all lanes.
+struct ConvBlock {
+    const float* x;          // the source's signal, first sample of the utterance
+    const float2* H;         // the response's spectra, partition 0
+    float* y;                // reverberated signal, first sample of the utterance
+    double* energy;          // E[u][j]
+    int len;                 // samples of the utterance
+    int first;               // first non-zero tap of the response
+    int b;                   // block index: outputs [b N, (b+1) N)
+};
+
+// The window of block wb, samples [(wb-1) N, (wb+1) N) of the utterance, as the inputs of the column step:
+// v[n1] = (x[2n], x[2n+1]), n = tid + M n1.  Block wb - 1 is a whole block of the utterance or (wb = 0) lies
+// before its start; block wb is whole except at the utterance's end.  Whole blocks are read with two-sample
+// loads and nothing to test, the same for every thread of the group.
+template <int N>
+__device__ inline void load_window(float2 (&v)[16], const float* x, int len, int wb, int tid) {
+    constexpr int M = N / 16;
+    const uint32_t lane_off = 8u * (uint32_t)tid;
+    if (wb >= 1) {
+        const float* blk = x + (size_t)(wb - 1) * N;
+#pragma unroll
+        for (int n1 = 0; n1 < 8; ++n1) {
+            const SamplePair s2 = load_pair(blk + 2 * M * n1, lane_off);
+            v[n1] = make_float2(s2.x, s2.y);
+        }
+    } else {
+#pragma unroll
+        for (int n1 = 0; n1 < 8; ++n1) v[n1] = make_float2(0.f, 0.f);
+    }
+    const float* blk = x + (size_t)wb * N;
+    if ((wb + 1) * (int64_t)N <= len) {
+#pragma unroll
+        for (int n1 = 8; n1 < 16; ++n1) {
+            const SamplePair s2 = load_pair(blk + 2 * M * (n1 - 8), lane_off);
+            v[n1] = make_float2(s2.x, s2.y);
+        }
+    } else {
+        // the utterance ends inside this block: addresses are clamped to its last sample, values past it are zero
+        const int left = len - wb * N;                     // 1 .. N - 1 samples of this block exist
+#pragma unroll
+        for (int n1 = 8; n1 < 16; ++n1) {
+            const int g = 2 * tid + 2 * M * (n1 - 8);
+            const float x0 = load_sample(blk, 4u * (uint32_t)min(g, left - 1));
+            const float x1 = load_sample(blk, 4u * (uint32_t)min(g + 1, left - 1));
+            v[n1] = make_float2(g < left ? x0 : 0.f, g + 1 < left ? x1 : 0.f);
+        }
+    }
+}
+
+// The outputs of a block, v[8 + i] = (y[n], y[n+1]) with n = b N + 2 tid + 2 M i, go to HBM; returns the
+// lane's share of the block's energy.  Samples before the response's first non-zero tap are exact zeros
+// (the transforms leave rounding noise there, which the power law of the front end would magnify).
+template <int N>
+__device__ inline float store_block(const float2 (&v)[16], const ConvBlock& c, int tid) {
+    constexpr int M = N / 16;
+    float* yb = c.y + (size_t)c.b * N;
+    const int first = c.first - c.b * N;                   // first live sample of this block (may be <= 0)
+    const int left = c.len - c.b * N;                      // samples of this block inside the utterance
+    float e = 0.f;
+    if (left >= N && first <= 0) {                         // whole and live: eight two-sample stores
+        char* dst = reinterpret_cast<char*>(yb) + 8u * (uint32_t)tid;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            SamplePair s2;
+            s2.x = v[8 + i].x;
+            s2.y = v[8 + i].y;
+            *reinterpret_cast<SamplePair*>(dst + 8 * M * i) = s2;
+            e += s2.x * s2.x + s2.y * s2.y;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int g = 2 * tid + 2 * M * i;
+            const float s0 = g >= first ? v[8 + i].x : 0.f, s1 = g + 1 >= first ? v[8 + i].y : 0.f;
+            if (g < left) { yb[g] = s0; e += s0 * s0; }
+            if (g + 1 < left) { yb[g + 1] = s1; e += s1 * s1; }
+        }
+    }
+    return e;
+}
+
+// Work groups are persistent: group g takes a contiguous share of the list of all blocks ordered by
+// (utterance, source, block), so it walks along one reverberated signal block after block.  While a block's
+// inverse transform runs, the inputs of the next block are already on their way from HBM, and the response
+// spectrum is requested before the forward row transforms that precede its use: the loads' latency is
+// hidden behind arithmetic instead of being paid at either end of a short-lived group.
+// MULTI: the response has two partitions.  Block b is then the inverse transform of
+// H_0 W_b + H_1 W_{b-1}; W_{b-1} is the window spectrum of the block this group finished just before, and
+// each thread keeps its sixteen bins of it in registers, so a block still costs one forward and one inverse
+// transform (plus one forward transform at the start of a group's share).
 template <int N, int T, bool MULTI>
 __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* __restrict__ tw) {
     extern __shared__ float2 buf[];
     __shared__ double red[T / 64];
     constexpr int M = N / 16;
     static_assert(T == M, "one thread per column of the split transform");
-    const int tid = threadIdx.x;
-    // Groups are dealt to the eight XCDs in turn, each with an L2 of its own.  Group ids that share an XCD
-    // take one contiguous eighth of the work, so that the blocks of an utterance, which read the same response
-    // spectrum and overlapping input windows, meet in one L2.
-    const unsigned per_xcd = gridDim.x / kXcds;
-    const int64_t work = (int64_t)(blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
-    if (work >= a.n_items * a.n_src) return;
-    const int64_t item = work / a.n_src;
-    const int j = (int)(work % a.n_src);
-    const int u = a.items[item].x, b = a.items[item].y;
-    const int64_t start = a.offsets[u];
-    const int len = (int)(a.offsets[u + 1] - start);      // utterances are shorter than 2^30 samples (checked on the host)
-    const float* x = (j == 0 ? a.speech : a.noise + (size_t)(j - 1) * a.total) + start;
-    const float2* H = a.spec + ((size_t)u * a.n_src + j) * a.n_part * (size_t)(N + 1);
-    const int first = a.first_tap[(size_t)u * a.n_src + j];   // first non-zero tap of the response
+    // behind the transform buffer: the row transforms' twiddles with their powers, and the two factors of
+    // the even/odd split's twiddle exp(-i pi (k1 + 16 k2) / N) = split_lo[k1] split_hi[k2]
+    float2* const row_tw = buf + lds_padded_size(N);
+    float2* const split_lo = row_tw + RowTwiddles<M>::kEntries;
+    float2* const split_hi = split_lo + 16;
+    RowTwiddles<M>::template fill<16>(row_tw, tw, threadIdx.x, T);
+    for (int i = threadIdx.x; i < 16 + M / 2; i += T) split_lo[i] = i < 16 ? tw[N + i] : tw[N + N / 2 + 1 + (i - 16)];
+    // (the first barrier of the loop below comes before any of these is read)
+    // With two partitions the kept spectrum takes the registers that the single-partition kernel spends on
+    // loads issued ahead of time; the inputs and the response spectrum are then loaded where they are used.
+    constexpr bool AHEAD = !MULTI;
+    const int tid0 = threadIdx.x;
+    const int64_t total = a.n_items * a.n_src;
+    const int64_t w_begin = total * blockIdx.x / gridDim.x, w_end = total * (blockIdx.x + 1) / gridDim.x;
+    if (w_begin >= w_end) return;
 
-    // Responses longer than N taps: every partition p convolves the window p blocks back with its own
-    // spectrum and the N output samples are summed in registers (eight complex values per thread), which
-    // keeps each pass on the register budget of the single-partition path.
-    float2 out[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) out[i] = make_float2(0.f, 0.f);
+    // where the share starts: utterance u (the one that holds item w / n_src), source j, block b
+    int u = a.items[w_begin / a.n_src].x;
+    int nb = a.first[u + 1] - a.first[u];
+    int j, b;
+    {
+        const int r = (int)(w_begin - (int64_t)a.first[u] * a.n_src);
+        j = r / nb;
+        b = r - j * nb;
+    }
+    auto describe = [&](int uu, int jj, int bb) {
+        ConvBlock c;
+        const int64_t start = a.offsets[uu];
+        const size_t uj = (size_t)uu * a.n_src + jj;
+        c.len = (int)(a.offsets[uu + 1] - start);          // utterances are shorter than 2^30 samples (checked on the host)
+        c.x = (jj == 0 ? a.speech : a.noise + (size_t)(jj - 1) * a.total) + start;
+        c.H = a.spec + uj * a.n_part * (size_t)(N + 1);
+        c.y = a.reverb + (size_t)jj * a.reverb_stride + start;
+        c.energy = a.energy + uj;
+        c.first = a.first_tap[uj];
+        c.b = bb;
+        return c;
+    };
+    ConvBlock cur = describe(u, j, b);
 
     float2 v[16];
-    const int n_part = MULTI ? a.n_part : 1;
-    for (int p = 0; p < n_part; ++p) {
-        const int wb = b - p;                        // input window [(wb-1)N, (wb+1)N)
-        if (wb < 0) break;
+    float2 prev_a[MULTI ? 8 : 1], prev_b[MULTI ? 8 : 1], prev_mid = make_float2(0.f, 0.f);
+    bool have_prev = false;         // prev_* hold the window spectrum of block cur.b - 1 of this signal
+    if (MULTI) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) prev_a[i] = prev_b[i] = make_float2(0.f, 0.f);
+        have_prev = cur.b == 0;     // the window before the first block is all zeros, and so is its spectrum
+    }
+    if (AHEAD) load_window<N>(v, cur.x, cur.len, cur.b, tid0);
+
+    for (int64_t w = w_begin;;) {
         // The thread index is made opaque in every round so that twiddle powers and addresses are not
-        // hoisted out of the partition loop, where they would sit on top of the transforms' registers.
-        int tid_p = tid;
-        asm volatile("" : "+v"(tid_p));
-        const int k2 = tid_p % (M / 2), half = tid_p / (M / 2);
-        const int w0 = (wb - 1) * N + 2 * tid_p;           // first sample of this thread in the window (may be < 0)
-        // The window is block wb - 1 followed by block wb.  The first is a whole block of the utterance or
-        // (wb = 0) lies before its start; the second is whole except at the utterance's end.  Whole blocks
-        // are read with two-sample loads and nothing to test, the same for every thread of the group.
-        const float* xw = x + w0;
-        if (wb >= 1) {
+        // hoisted out of the loop, where they would sit on top of the transforms' registers.
+        int tid = tid0;
+        asm volatile("" : "+v"(tid));
+        const bool warm_up = MULTI && !have_prev;          // this pass only produces the spectrum of window b - 1
+        if (!AHEAD) load_window<N>(v, cur.x, cur.len, warm_up ? cur.b - 1 : cur.b, tid);
+
+        fft_columns_forward<N>(v, tw, tid);
+        fft_columns_store<N, T>(v, buf, tid);
+        __syncthreads();
+
+        // the response spectrum of this thread's bins, requested now, used after the row transforms
+        float2 hk[8], hn[8];
+        if (AHEAD) {
+            const int k2 = tid % (M / 2), half = tid / (M / 2);
 #pragma unroll
-            for (int n1 = 0; n1 < 8; ++n1) {
-                const SamplePair s2 = *reinterpret_cast<const SamplePair*>(xw + 2 * M * n1);
-                v[n1] = make_float2(s2.x, s2.y);
-            }
-        } else {
-#pragma unroll
-            for (int n1 = 0; n1 < 8; ++n1) v[n1] = make_float2(0.f, 0.f);
-        }
-        if ((wb + 1) * (int64_t)N <= len) {
-#pragma unroll
-            for (int n1 = 8; n1 < 16; ++n1) {
-                const SamplePair s2 = *reinterpret_cast<const SamplePair*>(xw + 2 * M * n1);
-                v[n1] = make_float2(s2.x, s2.y);
-            }
-        } else {
-#pragma unroll
-            for (int n1 = 8; n1 < 16; ++n1) {
-                const int g = w0 + 2 * M * n1;                     // >= 0 in this half
-                const float x0 = g < len ? x[g] : 0.f;
-                const float x1 = g + 1 < len ? x[g + 1] : 0.f;
-                v[n1] = make_float2(x0, x1);
+            for (int i = 0; i < 8; ++i) {
+                const PairIndex<N> ix(half * 8 + i, k2);
+                hk[i] = load_bin(cur.H, 8u * (uint32_t)ix.pos);
+                hn[i] = load_bin(cur.H, 8u * (uint32_t)ix.h_partner);
             }
         }
-        fft_columns_forward<N>(v, tw, tid_p);
-        if (MULTI && p > 0) __syncthreads();         // the previous partition's column loads are done
-        fft_columns_store<N, T>(v, buf, tid_p);
+        fft_rows_table<N, false>(buf, row_tw, tid);
         __syncthreads();
-        fft_rows<N, false>(buf, tw, tid_p);
-        __syncthreads();
-        const float2* Hp = H + (size_t)p * (N + 1);
-        auto pair = [&](int i) {
-            const PairIndex<N> ix(i == 8 ? 0 : half * 8 + i, i == 8 ? M / 2 : k2);
+        // (opaque again: bin positions are recomputed here rather than kept in registers across the transform)
+        asm volatile("" : "+v"(tid));
+        const int k2 = tid % (M / 2), half = tid / (M / 2);
+
+        if (warm_up) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const PairIndex<N> ix(half * 8 + i, k2);
+                prev_a[i] = buf[lds_pad(ix.pos)];
+                prev_b[i] = cconj(buf[lds_pad(ix.pos_partner)]);
+            }
+            prev_mid = buf[lds_pad(M / 2)];
+            have_prev = true;
+            __syncthreads();                               // all bins are read before the next column store
+            continue;
+        }
+
+        const float2* H1 = cur.H + (N + 1);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const PairIndex<N> ix(half * 8 + i, k2);
             const float2 A = buf[lds_pad(ix.pos)];
             const float2 B = cconj(buf[lds_pad(ix.pos_partner)]);
-            const float2 w = i == 8 ? tw[N + N / 2] : pair_twiddle<N>(tw, half * 8 + i, k2);
+            const float2 wk = cmul(split_lo[half * 8 + i], split_hi[k2]);
+            if (!AHEAD) {
+                hk[i] = load_bin(cur.H, 8u * (uint32_t)ix.pos);
+                hn[i] = load_bin(cur.H, 8u * (uint32_t)ix.h_partner);
+            }
             float2 Zk, ZNk;
-            multiply_pair(A, B, w, Hp[ix.pos], Hp[ix.h_partner], Zk, ZNk);
-            buf[lds_pad(ix.pos)] = Zk;               // both positions belong to this thread alone
-            if (ix.k != 0 && i < 8) buf[lds_pad(ix.pos_partner)] = ZNk;
-        };
-#pragma unroll
-        for (int i = 0; i < 8; ++i) pair(i);
-        if (tid_p == 0) pair(8);
+            multiply_pair(A, B, wk, hk[i], hn[i], Zk, ZNk);
+            if (MULTI) {
+                float2 Zk1, ZNk1;
+                multiply_pair(prev_a[i], prev_b[i], wk, load_bin(H1, 8u * (uint32_t)ix.pos),
+                              load_bin(H1, 8u * (uint32_t)ix.h_partner), Zk1, ZNk1);
+                Zk = cadd(Zk, Zk1);
+                ZNk = cadd(ZNk, ZNk1);
+                prev_a[i] = A;
+                prev_b[i] = B;
+            }
+            buf[lds_pad(ix.pos)] = Zk;                     // both positions belong to this thread alone
+            if (ix.k != 0) buf[lds_pad(ix.pos_partner)] = ZNk;
+        }
+        if (tid == 0) {                                    // the bin in the middle, k = N / 2, is its own partner
+            const PairIndex<N> ix(0, M / 2);
+            const float2 A = buf[lds_pad(ix.pos)];
+            const float2 wk = tw[N + N / 2];
+            float2 Zk, ZNk;
+            multiply_pair(A, cconj(A), wk, cur.H[ix.pos], cur.H[ix.h_partner], Zk, ZNk);
+            if (MULTI) {
+                float2 Zk1, ZNk1;
+                multiply_pair(prev_mid, cconj(prev_mid), wk, H1[ix.pos], H1[ix.h_partner], Zk1, ZNk1);
+                Zk = cadd(Zk, Zk1);
+                prev_mid = A;
+            }
+            buf[lds_pad(ix.pos)] = Zk;
+        }
         __syncthreads();
-        fft_rows<N, true>(buf, tw, tid_p);
-        __syncthreads();
-        fft_columns_load<N, T>(v, buf, tid_p);
-        fft_columns_inverse<N>(v, tw, tid_p);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) out[i] = cadd(out[i], v[8 + i]);
-    }
 
-    // the last N real samples of the 2N-sample window are this block's outputs: n = tid + M n1 >= N/2
-    float* y = a.reverb + (size_t)j * a.reverb_stride + start;
-    // Before the response's first non-zero tap the exact result is zero; the transforms leave rounding noise
-    // there, which the power law of the front end would turn into a visible feature value.
-    const int out0 = b * N + 2 * tid;
-    float e = 0.f;
-    if ((b + 1) * (int64_t)N <= len) {               // a full block: eight two-sample stores, nothing to test
-        float* yb = y + out0;
+        // the next block of the share: its inputs are requested now and arrive during the inverse transform
+        const bool more = w + 1 < w_end;
+        ConvBlock nxt = cur;
+        asm volatile("" : "+v"(tid));
+        if (more) {
+            if (++b == nb) {
+                b = 0;
+                if (++j == a.n_src) {
+                    j = 0;
+                    do {
+                        ++u;
+                        nb = a.first[u + 1] - a.first[u];
+                    } while (nb == 0);
+                }
+            }
+            nxt = describe(u, j, b);
+            if (AHEAD) load_window<N>(v, nxt.x, nxt.len, nxt.b, tid);
+        } else if (AHEAD) {
+            // (assigned on this path too, so that the old inputs do not stay alive in registers up to here)
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int g = out0 + 2 * M * i;
-            SamplePair s2;
-            s2.x = g >= first ? out[i].x : 0.f;
-            s2.y = g + 1 >= first ? out[i].y : 0.f;
-            *reinterpret_cast<SamplePair*>(yb + 2 * M * i) = s2;
-            e += s2.x * s2.x + s2.y * s2.y;
+            for (int i = 0; i < 16; ++i) v[i] = make_float2(0.f, 0.f);
         }
-    } else {
+
+        fft_rows_table<N, true>(buf, row_tw, tid);
+        __syncthreads();
+        float2 o[16];
+        fft_columns_load<N, T>(o, buf, tid);
+        fft_columns_inverse<N>(o, tw, tid);
+        const float e = store_block<N>(o, cur, tid);
+
+        float es = e;                                      // a wave's 1024 squares in fp32, the rest in fp64
+        for (int off = 32; off > 0; off >>= 1) es += __shfl_down(es, off, 64);
+        if ((tid & 63) == 0) red[tid >> 6] = (double)es;
+        __syncthreads();                                   // also: every thread has read its columns from LDS
+        if (tid == 0) {
+            double tot = 0.0;
+            for (int i = 0; i < T / 64; ++i) tot += red[i];
+            atomicAdd(cur.energy, tot);
+        }
+        if (!more) break;
+        if (MULTI && nxt.b == 0) {                         // a new signal starts: nothing precedes its first window
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int g = out0 + 2 * M * i;
-            const float s0 = g >= first ? out[i].x : 0.f, s1 = g + 1 >= first ? out[i].y : 0.f;
-            if (g < len) { y[g] = s0; e += s0 * s0; }
-            if (g + 1 < len) { y[g + 1] = s1; e += s1 * s1; }
+            for (int i = 0; i < 8; ++i) prev_a[i] = prev_b[i] = make_float2(0.f, 0.f);
+            prev_mid = make_float2(0.f, 0.f);
         }
-    }
-    double es = (double)e;
-    for (int off = 32; off > 0; off >>= 1) es += __shfl_down(es, off, 64);
-    if ((tid & 63) == 0) red[tid >> 6] = es;
-    __syncthreads();
-    if (tid == 0) {
-        double tot = 0.0;
-        for (int i = 0; i < T / 64; ++i) tot += red[i];
-        atomicAdd(&a.energy[(size_t)u * a.n_src + j], tot);
+        cur = nxt;
+        ++w;
     }
 }
 
@@ -324,15 +478,28 @@ hipError_t spectrum_n(hipStream_t s, int n_rir, const float* rir, int rir_len, c
 }
 
 template <int N>
-hipError_t convolve_n(hipStream_t s, const float2* tw, const ConvArgs& a) {
+hipError_t convolve_n(hipStream_t s, const float2* tw, const ConvArgs& a, int n_cu) {
     constexpr int T = conv_threads(N);
-    const size_t lds = sizeof(float2) * lds_padded_size(N);
-    auto k = a.n_part > 1 ? &convolve_kernel<N, T, true> : &convolve_kernel<N, T, false>;
+    const size_t lds = sizeof(float2) * (lds_padded_size(N) + RowTwiddles<N / 16>::kEntries + 16 + N / 32);
+    // responses longer than one partition exist only at the largest transform size (conv_fft_size)
+    void (*k)(ConvArgs, const float2*) = &convolve_kernel<N, T, false>;
+    if (a.n_part > 1) {
+        if constexpr (N == 16384) k = &convolve_kernel<N, T, true>;
+        else return hipErrorInvalidValue;
+        if (a.n_part != 2) return hipErrorInvalidValue;
+    }
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    const int64_t per_xcd = (a.n_items * a.n_src + kXcds - 1) / kXcds;
-    k<<<dim3((unsigned)(per_xcd * kXcds)), dim3(T), lds, s>>>(a, tw);
+    // as many persistent groups as the chip holds at once: per compute unit, what the 160 KB of LDS and
+    // sixteen wavefronts (128 registers each) allow
+    const int by_lds = (int)((160 * 1024) / (lds + 256));
+    const int by_waves = 16 / ((T + 63) / 64);
+    const int per_cu = by_lds < 1 ? 1 : (by_lds < by_waves ? by_lds : by_waves);
+    int64_t groups = (int64_t)n_cu * per_cu;
+    const int64_t total = a.n_items * a.n_src;
+    if (groups > total) groups = total;
+    k<<<dim3((unsigned)groups), dim3(T), lds, s>>>(a, tw);
     return hipGetLastError();
 }
 
@@ -370,9 +537,9 @@ hipError_t launch_rir_spectrum(hipStream_t s, int n_rir, const float* rir, int r
 #undef CALL
 }
 
-hipError_t launch_convolve(hipStream_t s, int fft_n, const float2* twiddle, const ConvArgs& a) {
+hipError_t launch_convolve(hipStream_t s, int fft_n, const float2* twiddle, const ConvArgs& a, int n_cu) {
     if (a.n_items <= 0) return hipSuccess;
-#define CALL(NN) convolve_n<NN>(s, twiddle, a)
+#define CALL(NN) convolve_n<NN>(s, twiddle, a, n_cu)
     AUG_FFT_DISPATCH(fft_n, CALL)
 #undef CALL
 }

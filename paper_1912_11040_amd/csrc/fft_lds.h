@@ -373,6 +373,59 @@ __device__ inline void fft_columns_load(float2 (&v)[16], const float2* buf, int 
     for (int k1 = 0; k1 < 16; ++k1) v[k1] = base[lds_pad(k1 * (N / 16))];
 }
 
+// ---- row-pass twiddles with their powers, held in LDS ---------------------------------------
+// A persistent kernel fills the table once and its row transforms then read every factor they need
+// (pass P of radix R and sub-length NS: exp(-2 pi i k m / (NS R)) at [k][m - 1], k < NS, m = 1..R-1) instead of
+// loading one factor from global memory and forming its powers by chained products.  That removes the
+// products, and it removes global loads from the row transforms, so loads issued ahead of them are not
+// waited for there (a wave's global loads complete in order).
+template <int M>
+struct RowTwiddles {
+    using Plan = FftPlan<M>;
+    static constexpr int offset(int p) {
+        int o = 0;
+        for (int q = 1; q < p; ++q) o += Plan::ns(q) * (Plan::radix(q) - 1);
+        return o;
+    }
+    static constexpr int kEntries = offset(Plan::kPasses);
+    // tw: exp(-2 pi i t / (M TWS)); all threads of the group call, then synchronise
+    template <int TWS, int P = 1>
+    __device__ static inline void fill(float2* tab, const float2* __restrict__ tw, int tid, int n_threads) {
+        if constexpr (P < Plan::kPasses) {
+            constexpr int R = Plan::radix(P), NS = Plan::ns(P);
+            for (int e = tid; e < NS * (R - 1); e += n_threads) {
+                const int k = e / (R - 1), m = e % (R - 1) + 1;
+                tab[offset(P) + e] = tw[k * m * (M / (NS * R)) * TWS];
+            }
+            fill<TWS, P + 1>(tab, tw, tid, n_threads);
+        }
+    }
+};
+
+// fft_passes with every twiddle factor read from a RowTwiddles table in LDS
+template <int M, int T, bool INV, FftSync S, int P = 0>
+__device__ inline void fft_passes_table(float2 (&v)[16], float2* buf, const float2* tab, int tid) {
+    using Plan = FftPlan<M>;
+    constexpr int R = Plan::radix(P), NS = Plan::ns(P);
+#pragma unroll
+    for (int bi = 0; bi < 16 / R; ++bi) {
+        if constexpr (NS > 1) {
+            const float2* e = tab + RowTwiddles<M>::offset(P) + ((tid + bi * T) % NS) * (R - 1);
+#pragma unroll
+            for (int m = 1; m < R; ++m)
+                v[bi * R + m] = INV ? cmul_conj(v[bi * R + m], e[m - 1]) : cmul(v[bi * R + m], e[m - 1]);
+        }
+        SmallDft<R, INV>::run(&v[bi * R]);
+    }
+    if constexpr (P + 1 < Plan::kPasses) {
+        fft_store<M, T, R, NS>(v, buf, tid);
+        fft_sync<S>();
+        fft_load<M, T, Plan::radix(P + 1)>(v, buf, tid);
+        fft_sync<S>();
+        fft_passes_table<M, T, INV, S, P + 1>(v, buf, tab, tid);
+    }
+}
+
 // The 16 row transforms, in place in natural order within each row; wave-level synchronisation only.
 // Thread tid works on row tid / (M/16) as lane tid % (M/16).  Rows must be complete (barrier) before.
 template <int N, bool INV>
@@ -385,6 +438,20 @@ __device__ inline void fft_rows(float2* buf, const float2* __restrict__ tw, int 
     fft_load_natural<M, LANES>(v, row, lane);
     fft_sync<FftSync::Wave>();
     fft_passes<M, LANES, INV, FftSync::Wave, 16>(v, row, tw, lane);
+    fft_store_natural<M, LANES>(v, row, lane);
+}
+
+// the same with the twiddles of a RowTwiddles<N / 16> table
+template <int N, bool INV>
+__device__ inline void fft_rows_table(float2* buf, const float2* tab, int tid) {
+    constexpr int M = N / 16, LANES = M / 16;
+    static_assert(LANES >= 1 && LANES <= 64, "a row is transformed inside one wavefront");
+    float2* row = buf + lds_pad((tid / LANES) * M);
+    const int lane = tid % LANES;
+    float2 v[16];
+    fft_load_natural<M, LANES>(v, row, lane);
+    fft_sync<FftSync::Wave>();
+    fft_passes_table<M, LANES, INV, FftSync::Wave>(v, row, tab, lane);
     fft_store_natural<M, LANES>(v, row, lane);
 }
 
