@@ -90,6 +90,11 @@ __global__ __launch_bounds__(64) void mel_table_kernel(int n_utt, const float* _
 }
 
 constexpr int kMelLanes = 16;                            // lanes per frame
+constexpr int kProg = 32;                                // steps of a lane's band-sum list, at most
+constexpr int kProgStride = kProg + 1;                   // lists start four banks apart
+// A frame's transform buffer in LDS, in complex values: one more than the padded transform, so that the
+// frames of a wavefront start two banks apart.
+template <int NC> constexpr int mel_slot_stride() { return lds_padded_size(NC) + 1; }
 constexpr int kMelSlots = kMelThreads / kMelLanes;       // frames in flight per work group
 
 // K = 512: 256-point complex FFT per frame, 16 lanes per frame, 16 frames per pass of the group.
@@ -104,12 +109,13 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
     const int n_mel = a.cfg.n_mel;
     const int feature = a.cfg.feature;
     const int n_out = feature == AUG_FEAT_MFCC ? a.cfg.n_ceps : n_mel;     // values per output row
-    const int n_seg = n_mel + 2;                         // band sums A[c], B[c] for c = 0..n_mel (+1 pad)
-    float2* fft_buf = reinterpret_cast<float2*>(smem);                       // [slots][padded NC]
-    float2* s_tab = fft_buf + kMelSlots * lds_padded_size(NC);               // [NC + 1]: (c, w) per bin
+    const int n_seg = n_mel + 3;                         // band sums (A, B)[c + 1] for c = -1..n_mel (+1 pad)
+    float2* fft_buf = reinterpret_cast<float2*>(smem);                       // [slots][mel_slot_stride]
+    float4* s_prog = reinterpret_cast<float4*>(fft_buf + kMelSlots * mel_slot_stride<NC>());   // [16][kProgStride]
+    float2* s_tab = reinterpret_cast<float2*>(s_prog + kMelLanes * kProgStride);   // [NC + 1]: (c, w) per bin
     float2* s_tw = s_tab + (NC + 1);                                         // [NC + 1]: exp(-i pi k / NC)
-    float* s_ab = reinterpret_cast<float*>(s_tw + (NC + 1));                 // [slots][2][n_seg]
-    int* s_kstart = reinterpret_cast<int*>(s_ab + kMelSlots * 2 * n_seg);    // [17]
+    float2* s_ab = s_tw + (NC + 1);                                          // [slots][n_seg]
+    int* s_kstart = reinterpret_cast<int*>(s_ab + kMelSlots * n_seg);        // [17]
 
     const int tid = threadIdx.x;
     const int slot = tid / kMelLanes, sub = tid % kMelLanes;
@@ -125,9 +131,9 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
     const int64_t n_frames_u = len >= win ? 1 + (len - win) / hop : 0;
     const float power = a.cfg.power;
     float* feats = a.feats + (size_t)a.frame_offsets[u] * n_out;
-    float2* buf = fft_buf + slot * lds_padded_size(NC);
-    float* A = s_ab + (slot * 2) * n_seg;
-    float* B = A + n_seg;
+    float2* buf = fft_buf + slot * mel_slot_stride<NC>();
+    float* pw = reinterpret_cast<float*>(buf);           // the frame's bin powers P[0..NC], once they are formed
+    float2* AB = s_ab + slot * n_seg;                    // (A, B)[c + 1]; entry 0 takes what belongs to no band
 
     const float2* g_tab = a.mel_tab + (size_t)u * tab_stride;
     for (int k = tid; k <= NC; k += kMelThreads) {
@@ -149,6 +155,33 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
     for (int m = 1; m < 16; ++m) twp[m] = tw[(sub * m) & (NC - 1)];
     __syncthreads();
     const int k_lo = s_kstart[sub], k_hi = s_kstart[sub + 1];
+    // Each lane sums the bins of its own bands by a fixed list of steps, one per bin, that is the same for
+    // every frame of the utterance: (keep, w, 1 - w, where the running sums go).  keep is 0 where a new band
+    // begins, else 1.  The running sums are stored after every bin, so a band's entry ends up holding its
+    // whole sum without any test on the way.  Lists are padded to a common length (a multiple of four,
+    // the same for all lanes) by steps that add nothing; with more than kProg bins in one lane's range
+    // (very wide bands) the plain loop further down is used instead.
+    int n_steps = 0;
+#pragma unroll
+    for (int l = 0; l < kMelLanes; ++l) n_steps = max(n_steps, s_kstart[l + 1] - s_kstart[l]);
+    n_steps = (n_steps + 3) & ~3;
+    const bool listed = n_steps <= kProg;
+    if (listed) {
+        for (int e = tid; e < kMelLanes * kProg; e += kMelThreads) {
+            const int l = e / kProg, i = e - l * kProg;
+            const int lo = s_kstart[l], k = lo + i;
+            float4 step = make_float4(1.f, 0.f, 0.f, __int_as_float(0));      // adds nothing, stores to entry 0
+            if (k < s_kstart[l + 1]) {
+                const float2 cw = s_tab[k];
+                const int c = (int)cw.x;
+                const bool same = i > 0 && (int)s_tab[k - 1].x == c;
+                if (c >= 0) step = make_float4(same ? 1.f : 0.f, cw.y, 1.f - cw.y, __int_as_float(8 * (c + 1)));
+                else step.x = same ? 1.f : 0.f;
+            }
+            s_prog[l * kProgStride + i] = step;
+        }
+        __syncthreads();
+    }
     const bool even_win = (win & 1) == 0;
     const float* extra = MIX ? a.extra + start : nullptr;
     const float* gains = MIX ? a.gains + (size_t)u * a.n_extra : nullptr;
@@ -178,12 +211,19 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
                 for (int j = 0; j < a.n_extra; ++j) {
                     const float g = gains[j];
                     const float* xj = extra + (size_t)j * a.extra_stride;
+                    // all sixteen loads of a source are issued before the first of them is used (the
+                    // scheduler may otherwise pair every load with its wait to save registers)
+                    SamplePair s2[16];
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const int i0 = min(2 * (sub + kMelLanes * i), win - 2);
-                        const SamplePair s2 = *reinterpret_cast<const SamplePair*>(xj + (x0 + i0));
-                        v[i].x += g * s2.x;
-                        v[i].y += g * s2.y;
+                        s2[i] = *reinterpret_cast<const SamplePair*>(xj + (x0 + i0));
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        v[i].x += g * s2[i].x;
+                        v[i].y += g * s2[i].y;
                     }
                 }
             }
@@ -219,17 +259,18 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
         for (int m = 1; m < 16; ++m) v[m] = cmul(v[m], twp[m]);
         SmallDft<16, false>::run(v);
         fft_store_natural<NC, kMelLanes>(v, buf, sub);
-        for (int m = sub; m < 2 * n_seg; m += kMelLanes) A[m] = 0.f;
+        for (int m = sub; m < n_seg; m += kMelLanes) AB[m] = make_float2(0.f, 0.f);
         fft_sync<FftSync::Wave>();                       // a frame's 16 lanes share a wavefront
 
         // Bin powers, two at a time: with E = (Z[k] + conj Z[N-k])/2, O = -(i/2)(Z[k] - conj Z[N-k]) and
         // w = exp(-i pi k / N):  X[k] = E + w O and conj(X[N-k]) = E - w O.
-        // P[k] replaces the real part of slot k (k < N); P[N] goes to the imaginary part of slot 0.
-        // Pair (k, N-k) is read and overwritten by one lane only.
+        // The powers go back into the frame's buffer as a plain array P[0..N] of floats, so every lane reads
+        // all its bins before any lane writes.
+        constexpr int kPairs = NC / 2 / kMelLanes + 1;    // the last one (bin N/2) only for lane 0
+        float p_lo[kPairs], p_hi[kPairs];
 #pragma unroll
-        for (int i = 0; i <= NC / 2 / kMelLanes; ++i) {
-            if (i == NC / 2 / kMelLanes && sub != 0) break;
-            const int k = sub + kMelLanes * i;            // 0..N/2
+        for (int i = 0; i < kPairs; ++i) {
+            const int k = min(sub + kMelLanes * i, NC / 2);   // 0..N/2 (lanes past it repeat bin N/2, unused)
             const int kn = (NC - k) & (NC - 1);
             const float2 Zk = buf[lds_pad(k)];
             const float2 Zn = buf[lds_pad(kn)];
@@ -239,52 +280,72 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
             const float2 wO = cmul(w, O);
             // sums first, then squares: a weak bin next to a strong mirror bin keeps its relative accuracy
             const float2 Xk = cadd(E, wO), Xn = csub(E, wO);
-            const float p_lo = Xk.x * Xk.x + Xk.y * Xk.y, p_hi = Xn.x * Xn.x + Xn.y * Xn.y;
-            if (k == 0) {
-                buf[lds_pad(0)] = make_float2(p_lo, p_hi);
-            } else {
-                buf[lds_pad(k)].x = p_lo;
-                buf[lds_pad(kn)].x = p_hi;
-            }
+            p_lo[i] = Xk.x * Xk.x + Xk.y * Xk.y;
+            p_hi[i] = Xn.x * Xn.x + Xn.y * Xn.y;
+        }
+        fft_sync<FftSync::Wave>();
+#pragma unroll
+        for (int i = 0; i < kPairs; ++i) {
+            if (i == kPairs - 1 && sub != 0) break;
+            const int k = sub + kMelLanes * i;
+            pw[k] = p_lo[i];
+            pw[NC - k] = p_hi[i];                         // k = 0: P[N] (it comes from Z[0] too); k = N/2: itself
         }
         fft_sync<FftSync::Wave>();
 
         // bins [k_lo, k_hi) -> per-band sums; this lane owns every band it meets
-        float run_a = 0.f, run_b = 0.f;
-        int cur = -100;
-        for (int k = k_lo; k < k_hi; ++k) {
-            const float p = k < NC ? buf[lds_pad(k)].x : buf[lds_pad(0)].y;
-            const float2 cw = s_tab[k];
-            const int c = (int)cw.x;
-            if (c != cur) {
-                if (cur >= 0) { A[cur] = run_a; B[cur] = run_b; }
-                cur = c;
-                run_a = 0.f;
-                run_b = 0.f;
+        if (listed) {
+            const float4* step = s_prog + sub * kProgStride;
+            const float* p = pw + k_lo;
+            char* dst = reinterpret_cast<char*>(AB);
+            float run_a = 0.f, run_b = 0.f;
+            for (int i = 0; i < n_steps; i += 4) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float4 s4 = step[i + j];
+                    const float pk = p[i + j];            // (past k_hi: some finite value, times zero)
+                    run_a = fmaf(s4.y, pk, run_a * s4.x);
+                    run_b = fmaf(s4.z, pk, run_b * s4.x);
+                    *reinterpret_cast<float2*>(dst + __float_as_int(s4.w)) = make_float2(run_a, run_b);
+                }
             }
-            run_a += cw.y * p;
-            run_b += (1.f - cw.y) * p;
+        } else {
+            float run_a = 0.f, run_b = 0.f;
+            int cur = -100;
+            for (int k = k_lo; k < k_hi; ++k) {
+                const float pk = pw[k];
+                const float2 cw = s_tab[k];
+                const int c = (int)cw.x;
+                if (c != cur) {
+                    if (cur >= 0) AB[cur + 1] = make_float2(run_a, run_b);
+                    cur = c;
+                    run_a = 0.f;
+                    run_b = 0.f;
+                }
+                run_a += cw.y * pk;
+                run_b += (1.f - cw.y) * pk;
+            }
+            if (cur >= 0) AB[cur + 1] = make_float2(run_a, run_b);
         }
-        if (cur >= 0) { A[cur] = run_a; B[cur] = run_b; }
         fft_sync<FftSync::Wave>();
 
         // channel m collects the rising side of band m and the falling side of band m + 1
         if (feature == AUG_FEAT_POWER_LAW) {
             if (live) {
                 for (int m = sub; m < n_mel; m += kMelLanes) {
-                    const float e = A[m] + B[m + 1];
+                    const float e = AB[m + 1].x + AB[m + 2].y;
                     feats[t * n_mel + m] = e > 0.f ? __powf(e, power) : 0.f;
                 }
             }
         } else {
-            // log-mel; for cepstra the log energies go back to A[m] (read by the lane of channel m only),
-            // then every lane takes the dot products of its coefficients with the whole vector
+            // log-mel; for cepstra the log energies go to the front of the frame's buffer (the bin powers are
+            // no longer needed), then every lane takes the dot products of its coefficients with the whole vector
             for (int m = sub; m < n_mel; m += kMelLanes) {
-                const float le = logf(fmaxf(A[m] + B[m + 1], a.cfg.log_floor));
+                const float le = logf(fmaxf(AB[m + 1].x + AB[m + 2].y, a.cfg.log_floor));
                 if (feature == AUG_FEAT_LOG) {
                     if (live) feats[t * n_mel + m] = le;
                 } else {
-                    A[m] = le;
+                    pw[m] = le;
                 }
             }
             if (feature == AUG_FEAT_MFCC) {
@@ -292,7 +353,7 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
                 for (int q = sub; q < n_out; q += kMelLanes) {
                     const float* row = a.dct + q * n_mel;
                     float acc = 0.f;
-                    for (int m = 0; m < n_mel; ++m) acc += row[m] * A[m];
+                    for (int m = 0; m < n_mel; ++m) acc += row[m] * pw[m];
                     if (live) feats[t * n_out + q] = acc;
                 }
             }
@@ -340,8 +401,9 @@ hipError_t launch_mel(hipStream_t s, const MelArgs& a) {
     if (a.n_items <= 0) return hipSuccess;
     if (a.cfg.nfft != 512) return hipErrorInvalidValue;
     constexpr int NC = 256;
-    const size_t lds = sizeof(float2) * (kMelSlots * lds_padded_size(NC) + 2 * (NC + 1)) +
-                       sizeof(float) * kMelSlots * 2 * (a.cfg.n_mel + 2) + sizeof(int) * 20;
+    const size_t lds = sizeof(float2) * (kMelSlots * mel_slot_stride<NC>() + 2 * (NC + 1)) +
+                       sizeof(float4) * kMelLanes * kProgStride +
+                       sizeof(float2) * kMelSlots * (a.cfg.n_mel + 3) + sizeof(int) * 20;
     const bool mix = a.n_extra > 0;
     auto k = a.cfg.win == 400 ? (mix ? &mel_kernel<NC, 400, true> : &mel_kernel<NC, 400, false>)
                               : (mix ? &mel_kernel<NC, 0, true> : &mel_kernel<NC, 0, false>);
