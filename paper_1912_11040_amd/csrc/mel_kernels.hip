@@ -102,6 +102,15 @@ constexpr int kMelSlots = kMelThreads / kMelLanes;       // frames in flight per
 // two consecutive samples; only their 4-byte alignment is promised (global loads of two dwords need no more)
 struct __attribute__((aligned(4))) SamplePair { float x, y; };
 
+// e^power for e > 0 as exp2(power log2 e) on the hardware's base-2 logarithm and exponential (about one
+// unit in the last place each; the library's pow spends some 150 instructions on its last bit).  The
+// logarithm instruction does not take denormal inputs, so tiny energies are scaled into range first.
+__device__ inline float power_law(float e, float power) {
+    const bool tiny = e < 0x1p-100f;
+    const float l = __builtin_amdgcn_logf(tiny ? e * 0x1p+64f : e) - (tiny ? 64.f : 0.f);
+    return __builtin_amdgcn_exp2f(power * l);
+}
+
 template <int NC, int WIN, bool MIX>
 __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const float2* __restrict__ tw, int tab_stride) {
     static_assert(NC == 256 && NC / 16 == kMelLanes, "two radix-16 passes, sixteen lanes per frame");
@@ -300,13 +309,18 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
             char* dst = reinterpret_cast<char*>(AB);
             float run_a = 0.f, run_b = 0.f;
             for (int i = 0; i < n_steps; i += 4) {
+                float4 s4[4];
+                float pk[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {             // all reads of the four steps before their stores
+                    s4[j] = step[i + j];
+                    pk[j] = p[i + j];                     // (past k_hi: some finite value, times zero)
+                }
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const float4 s4 = step[i + j];
-                    const float pk = p[i + j];            // (past k_hi: some finite value, times zero)
-                    run_a = fmaf(s4.y, pk, run_a * s4.x);
-                    run_b = fmaf(s4.z, pk, run_b * s4.x);
-                    *reinterpret_cast<float2*>(dst + __float_as_int(s4.w)) = make_float2(run_a, run_b);
+                    run_a = fmaf(s4[j].y, pk[j], run_a * s4[j].x);
+                    run_b = fmaf(s4[j].z, pk[j], run_b * s4[j].x);
+                    *reinterpret_cast<float2*>(dst + __float_as_int(s4[j].w)) = make_float2(run_a, run_b);
                 }
             }
         } else {
@@ -334,7 +348,7 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
             if (live) {
                 for (int m = sub; m < n_mel; m += kMelLanes) {
                     const float e = AB[m + 1].x + AB[m + 2].y;
-                    feats[t * n_mel + m] = e > 0.f ? __powf(e, power) : 0.f;
+                    feats[t * n_mel + m] = e > 0.f ? power_law(e, power) : 0.f;
                 }
             }
         } else {
