@@ -316,17 +316,29 @@ __device__ inline void walk_piece_table(const WalkCtx& w, double a, float cxy, c
     // a counter plus an offset)
     typedef const AxisImage __attribute__((address_space(3))) * LdsImages;
     const unsigned int first = (unsigned int)(uintptr_t)(LdsImages)z;
-    for (unsigned int cur = first + (unsigned int)len * (unsigned int)sizeof(AxisImage); cur != first;) {
+    // The entry of the next round is requested before the current one is worked on, so that its LDS latency
+    // passes behind the arithmetic.  The last round requests the entry below the piece: z[-1] exists (the
+    // table has a spare entry in front) and is never used.
+    unsigned int cur = first + (unsigned int)(len - 1) * (unsigned int)sizeof(AxisImage);
+    AxisImage nxt;
+    {
+        const LdsImages p = (LdsImages)(uintptr_t)cur;
+        nxt.key = p->key;
+        nxt.aux = p->aux;
+    }
+    for (;;) {
+        const AxisImage e = nxt;
+        const bool last = cur == first;
         cur -= (unsigned int)sizeof(AxisImage);
         asm("" : "+v"(cur));
         const LdsImages p = (LdsImages)(uintptr_t)cur;
-        AxisImage e;
-        e.key = p->key;
-        e.aux = p->aux;
+        nxt.key = p->key;
+        nxt.aux = p->aux;
         const double d2 = __dadd_rn(a, e.key);
         float y;
         const int slot = tap_slot(w, d2, y);
         deposit<COUNT>(w, slot, (__int_as_float(e.aux) * y) * cxy, hist, hist32);
+        if (last) break;
     }
 }
 
@@ -454,7 +466,8 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
     int32_t* __restrict__ cnt_out, unsigned long long* __restrict__ visits = nullptr) {
     __shared__ unsigned long long hist[(COUNT ? kMaxTaps / 2 : kMaxTaps) + 1];     // slot 0 is never read
     __shared__ float bpow[COUNT ? 1 : kPow];
-    __shared__ AxisImage ztab[2 * kAxisCap];       // z images sorted by dz*dz
+    __shared__ AxisImage ztab_store[2 * kAxisCap + 1];
+    AxisImage* const ztab = ztab_store + 1;        // z images sorted by dz*dz (one spare entry in front)
     __shared__ AxisImage ytab[2 * kAxisCap];       // y images sorted by dy*dy
     __shared__ int row_pfx[2 * kAxisCap];          // per x image: inclusive prefix of live column counts
     __shared__ int s_split[2];
