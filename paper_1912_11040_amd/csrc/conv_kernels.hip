@@ -67,7 +67,7 @@ template <int N> __device__ inline float2 pair_twiddle(const float2* __restrict_
 }
 
 // Spectrum of one response partition, stored in the split order (k at fft_split_pos(k), k = N last)
-// and scaled by 1/N for the unnormalised inverse.
+// and scaled by 1/(4N): 1/N for the unnormalised inverse, 1/4 for the halves that multiply_pair leaves out.
 template <int N, int T>
 __global__ __launch_bounds__(T) void rir_spectrum_kernel(
     const float* __restrict__ rir, int rir_len, int n_part, const float2* __restrict__ tw,
@@ -101,7 +101,7 @@ __global__ __launch_bounds__(T) void rir_spectrum_kernel(
     fft_rows<N, false>(buf, tw, tid);
     __syncthreads();
     float2* out = spec + ((size_t)r * n_part + p) * (N + 1);
-    const float scale = 1.0f / (float)N;             // the inverse transform's normalisation
+    const float scale = 0.25f / (float)N;
     const int k2 = tid % (M / 2), half = tid / (M / 2);
 #pragma unroll
     for (int i = 0; i <= 8; ++i) {
@@ -118,15 +118,18 @@ __global__ __launch_bounds__(T) void rir_spectrum_kernel(
 }
 
 // Z'[k] and Z'[N-k] of the packed output block from Z[k] = A, conj(Z[N-k]) = B and the response
-// spectrum: Y = W H on the 2N-point real transform, repacked for the N-point inverse.
+// spectrum: Y = W H on the 2N-point real transform, repacked for the N-point inverse.  The halves of the
+// even/odd split (two on the way in, two on the way out) are left out here: the stored response spectrum
+// carries the factor 1/4 for them (powers of two: the result is the same bit for bit).
 __device__ inline void multiply_pair(float2 A, float2 B, float2 w, float2 Hk, float2 HNk, float2& Zk, float2& ZNk) {
-    float2 Wk, WNk_conj;
-    unpack_pair(A, B, w, Wk, WNk_conj);
-    const float2 Yk = cmul(Hk, Wk);
-    const float2 YNk_conj = cmul_conj(WNk_conj, HNk);
-    const float2 Ye = make_float2(0.5f * (Yk.x + YNk_conj.x), 0.5f * (Yk.y + YNk_conj.y));
-    const float2 dY = make_float2(0.5f * (Yk.x - YNk_conj.x), 0.5f * (Yk.y - YNk_conj.y));
-    const float2 Yo = cmul_conj(dY, w);              // conj(w) (Y[k] - conj Y[N-k]) / 2
+    const float2 E = cadd(A, B);
+    const float2 d = csub(A, B);
+    const float2 O = make_float2(d.y, -d.x);         // -i (A - B)
+    const float2 wO = cmul(w, O);
+    const float2 Yk = cmul(Hk, cadd(E, wO));
+    const float2 YNk_conj = cmul_conj(csub(E, wO), HNk);
+    const float2 Ye = cadd(Yk, YNk_conj);
+    const float2 Yo = cmul_conj(csub(Yk, YNk_conj), w);      // conj(w) (Y[k] - conj Y[N-k])
     Zk = make_float2(Ye.x - Yo.y, Ye.y + Yo.x);      // Ye + i Yo
     ZNk = make_float2(Ye.x + Yo.y, Yo.x - Ye.y);     // conj(Ye) + i conj(Yo)
 }
