@@ -42,9 +42,9 @@ PER_CONFIG_STEPS = {"tiny": 300, "features": 100, "batch": 300, "varlen": 200, "
 # runs summarised in profiles/hbm_traffic_<workload>.md, scaled there by a 1 GiB copy.  They describe the
 # kernel sources with this digest only; for any other sources `traffic` is reported as null.
 RECORDED_TRAFFIC = {
-    "digest": "0cfbf2ec4f706c26",
-    "varlen": {"rir": 124206024, "rir_spectrum": 202541643, "convolve": 1330361433, "mel": 627087549},
-    "throughput": {"rir": 672419566, "rir_spectrum": 1220132549, "convolve": 5675457889, "mel": 2221217745},
+    "digest": "bcc68c625b9d926f",
+    "varlen": {"rir": 145261747, "rir_spectrum": 202505630, "convolve": 2803489590, "mel": 626351460},
+    "throughput": {"rir": 779108039, "rir_spectrum": 1220056162, "convolve": 13821930089, "mel": 2232389535},
 }
 
 

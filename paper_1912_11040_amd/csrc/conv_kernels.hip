@@ -9,11 +9,12 @@
 // straight from HBM (and, inverse, writes the block straight back); the 16 row transforms
 // run one per wavefront without work-group barriers.
 //
-// One work group produces one output block of one (utterance, source) and adds the
-// block's energy to E[u][j] (fp64 atomics); with several partitions every partition's product goes
-// through its own inverse transform and the outputs are summed in registers.  A small kernel forms the
-// gains g_j = sqrt(E_0 / (E_j 10^(snr_j/10))); the mixture y_0 + sum_j g_j y_j is written by mix_kernel
-// when the caller wants it, and formed by the front end on the fly otherwise.
+// Work groups are persistent and walk along the reverberated signals block after block (see
+// convolve_kernel); each block's energy is added to E[u][j] (fp64 atomics).  A response of two partitions
+// costs one forward and one inverse transform per block as well: the previous window's spectrum stays in
+// registers.  A small kernel forms the gains g_j = sqrt(E_0 / (E_j 10^(snr_j/10))) (zero where an energy is
+// zero); the mixture y_0 + sum_j g_j y_j is written by mix_kernel when the caller wants it, and formed by
+// the front end on the fly otherwise.
 
 #include "aug_internal.h"
 #include "fft_lds.h"
