@@ -71,6 +71,12 @@ __device__ inline double axis_delta(const Axis& a, int q, int n) {
 
 __device__ inline int iabs(int v) { return v < 0 ? -v : v; }
 
+// A value that every lane of the wavefront has computed alike, moved to scalar registers: what an item's
+// geometry determines is the same in all lanes and would otherwise occupy vector registers for the whole item.
+__device__ inline int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ inline float uni(float v) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v))); }
+__device__ inline double uni(double v) { return __hiloint2double(uni(__double2hiint(v)), uni(__double2loint(v))); }
+
 // A usable room has sides of at least 10 cm (else the image lattice is unbounded) and a reflection
 // coefficient in [0, 1] (amplitudes are summed as unsigned fixed point and must not grow with the
 // reflection count); the comparisons are false for values that are not numbers.
@@ -243,12 +249,11 @@ __device__ inline int wave_inclusive_scan(int v, int lane) {
 }
 
 // One image along an axis, as stored in the sorted tables: key = squared distance to the microphone
-// along that axis (reference operation order); aux = beta^reflections as float bits (z axis) or the
-// reflection count (y axis).
+// along that axis (reference operation order); aux = beta^reflections (z axis) or the reflection count
+// (y axis).  Sixteen bytes: one LDS read per entry.
 struct __align__(16) AxisImage {
     double key;
-    int aux;
-    int pad;
+    double aux;
 };
 
 struct WalkCtx {
@@ -257,7 +262,8 @@ struct WalkCtx {
     double guard2;       // estimates whose fraction (after the shift) is below this are redone exactly
     double beta;
     int n0m1;            // n0 - 1
-    unsigned int n_slots;   // taps of the item + 1: slot 0 takes what belongs below the item and is never read
+    unsigned int n_slots;   // taps of the item + 2: slot 0 takes what belongs below the item, the last slot what
+                            // belongs above it; neither is read
 };
 
 // the reference recipe, kept out of line so that the estimate's loop stays short
@@ -266,79 +272,104 @@ __device__ __attribute__((noinline)) int exact_tap(double d2, double k_fs_c) {
     return (int)__dadd_rn(__dmul_rn(d, k_fs_c), 0.5);     // positive: truncation is floor
 }
 
-// Largest reflection count k whose amplitude beta^k / (4 pi d) can still reach one unit of the
-// 2^-56 fixed point at distance d_min or beyond, with a factor-of-two margin and one count of slack;
-// "no limit" when beta is 0, >= 1 (log2_beta == 0 encodes both) or d_min is tiny.
+// Largest reflection count k whose amplitude beta^k / (4 pi d) can still add to a sum in the 2^-56 fixed
+// point at distance d_min or beyond.  Increments are rounded to the nearest unit (or truncated, in the
+// innermost item), so an amplitude below half a unit adds exactly zero; the cut is taken at 2^-57.5, a
+// margin of a factor 1.41 under that, plus one count of slack, which covers the rounding of this estimate
+// for every beta that the limit of 10^6 counts lets through.  "No limit" when beta is 0, >= 1
+// (log2_beta == 0 encodes both) or d_min is tiny.
 __device__ inline int reflection_cut(float log2_beta, float d_min) {
     if (!(log2_beta < 0.f) || !(d_min > 1e-3f)) return 1 << 20;
-    // beta^k >= 4 pi d 2^-57  <=>  k <= (log2(4 pi d) - 57) / log2(beta)
-    const float k = (__log2f(12.566371f * d_min) - 57.f) / log2_beta;
+    // beta^k >= 4 pi d 2^-57.5  <=>  k <= (log2(4 pi d) - 57.5) / log2(beta)
+    const float k = (__log2f(12.566371f * d_min) - 57.5f) / log2_beta;
     return k > 1.0e6f ? (1 << 20) : (int)k + 2;
 }
 
-// Slot (tap - n0 + 1) of an image at squared distance d2, and y ~ 1/sqrt(d2) for its amplitude.
-// The estimate of d fs/c is good to ~2e-9 taps; shifted up by the guard, its fraction falls below
-// 2 guard exactly when the true value may lie within the guard of a rounding boundary, and only then is
-// the reference recipe evaluated.  Images below the item (slot <= 0 after truncation towards zero, or
-// negative) land in slot 0 or fail the range check; both are ignored.
-__device__ inline int tap_slot(const WalkCtx& w, double d2, float& y) {
-    const float d2f = (float)d2;
-    y = __frsqrt_rn(d2f);
-    const double s0 = (double)(d2f * y);                   // sqrt(d2) to ~2e-7
+// Slot (tap - n0 + 1) of an image at squared distance d2, and y ~ 1/sqrt(d2) (the hardware's
+// double-precision estimate, good to 2^-24: enough for the amplitude) for its amplitude.
+// One Newton step on the root leaves d fs/c good to ~1e-10 taps; shifted up by the guard, its fraction
+// falls below 2 guard exactly when the true value may lie within the guard of a rounding boundary, and only
+// then is the reference recipe evaluated.
+__device__ inline int tap_slot(const WalkCtx& w, double d2, double& y) {
+    y = __builtin_amdgcn_rsq(d2);
+    const double s0 = __dmul_rn(d2, y);                    // sqrt(d2) to 2^-24
     const double res = fma(-s0, s0, d2);                   // exact residual
-    const double s1 = fma(res, (double)(0.5f * y), s0);    // one Newton step: ~1e-13 relative
+    const double s1 = fma(__dmul_rn(res, y), 0.5, s0);     // one Newton step: ~4e-15 relative
     const double t = fma(s1, w.k_fs_c, w.shift);
     int slot = (int)t;
     if (__builtin_amdgcn_fract(t) < w.guard2) slot = exact_tap(d2, w.k_fs_c) - w.n0m1;
     return slot;
 }
 
-template <bool COUNT>
-__device__ inline void deposit(const WalkCtx& w, int slot, float x, unsigned long long* hist, unsigned int* hist32) {
-    if ((unsigned int)slot >= w.n_slots) return;
+// amp2 = amplitude * 2^56, rounded to an integer, goes to the tap's 64-bit integer sum.  Below 2^51 (every
+// image farther than 2.55 m) adding 1.5 * 2^52 rounds the exact product to an integer in the sum's own
+// mantissa, whose low 51 bits are then the increment; larger ones are rounded and split in two exact steps
+// (amp2 < 2^64: images at least a third of a millimetre away).  Which of the two an image takes depends on
+// its own amplitude only, so a response does not depend on how the batch was cut into items.
+// FAR: every image of the item lies beyond 2.6 m, the test is not needed.
+// CHECKED: the caller may pass slots outside the item (they are dropped); the table walk never does.
+template <bool COUNT, bool FAR, bool CHECKED>
+__device__ inline void deposit(const WalkCtx& w, int slot, double a, double y, unsigned long long* hist,
+                               unsigned int* hist32) {
+    if (CHECKED && (unsigned int)slot >= w.n_slots) return;
     if (COUNT) {
         atomicAdd(&hist32[slot], 1u);
-    } else {
-        // x = amplitude * 2^24; amplitude * 2^56 as a 64-bit integer from two exact fp32 scalings
-        const float fr = __builtin_amdgcn_fractf(x);
-        const unsigned int hi = (unsigned int)x;
-        const unsigned int lo = (unsigned int)(fr * 4294967296.0f);
-        atomicAdd(&hist[slot], ((unsigned long long)hi << 32) | lo);
+        return;
     }
+    unsigned int hi, lo;
+    if (FAR || __dmul_rn(a, y) < 0x1p51) {
+        const double m = fma(a, y, 0x1.8p52);
+        hi = (unsigned int)__double2hiint(m) & 0x7ffffu;
+        lo = (unsigned int)__double2loint(m);
+    } else {
+        const double amp2 = rint(__dmul_rn(a, y));
+        hi = (unsigned int)__dmul_rn(amp2, 0x1p-32);
+        lo = (unsigned int)fma(-(double)hi, 0x1p32, amp2);
+    }
+    atomicAdd(&hist[slot], ((unsigned long long)hi << 32) | lo);
 }
 
-template <bool COUNT>
-__device__ inline void walk_piece_table(const WalkCtx& w, double a, float cxy, const AxisImage* z, int len,
+// Every entry of a piece lies inside the item's shell up to the slack of the closed-form table positions
+// (a relative 1e-9: a few 1e-5 taps), so its slot is one of 0 .. taps + 1 and needs no test.
+template <bool COUNT, bool FAR>
+__device__ inline void walk_piece_table(const WalkCtx& w, double a, double cxy, const AxisImage* z, int len,
                                         unsigned long long* hist, unsigned int* hist32) {
     // walked from the far end so that one register is both the address and the loop condition
     // (the sums are integers: the order does not matter)
     // (the LDS address itself is the loop variable, opaque to the compiler so that it is not split into
     // a counter plus an offset)
     typedef const AxisImage __attribute__((address_space(3))) * LdsImages;
-    const unsigned int first = (unsigned int)(uintptr_t)(LdsImages)z;
     // The entry of the next round is requested before the current one is worked on, so that its LDS latency
-    // passes behind the arithmetic.  The last round requests the entry below the piece: z[-1] exists (the
-    // table has a spare entry in front) and is never used.
-    unsigned int cur = first + (unsigned int)(len - 1) * (unsigned int)sizeof(AxisImage);
-    AxisImage nxt;
-    {
-        const LdsImages p = (LdsImages)(uintptr_t)cur;
-        nxt.key = p->key;
-        nxt.aux = p->aux;
-    }
+    // passes behind the arithmetic; two rounds per turn of the loop, each with its own pair of registers, so
+    // that no entry is copied.  The last round requests the entry below the piece: z[-1] exists (the table
+    // has a spare entry in front) and is never used.
+    const unsigned int stop = (unsigned int)(uintptr_t)(LdsImages)z - (unsigned int)sizeof(AxisImage);
+    unsigned int cur = stop + (unsigned int)len * (unsigned int)sizeof(AxisImage);
+    auto step = [&](const AxisImage& e) {
+        const double d2 = __dadd_rn(a, e.key);
+        double y;
+        const int slot = tap_slot(w, d2, y);
+        deposit<COUNT, FAR, false>(w, slot, COUNT ? 0.0 : __dmul_rn(e.aux, cxy), y, hist, hist32);
+    };
+    auto entry_at = [](unsigned int lds_address) {
+        const LdsImages p = (LdsImages)(uintptr_t)lds_address;
+        AxisImage e;
+        e.key = p->key;
+        e.aux = p->aux;
+        return e;
+    };
+    AxisImage e0 = entry_at(cur), e1;
     for (;;) {
-        const AxisImage e = nxt;
-        const bool last = cur == first;
         cur -= (unsigned int)sizeof(AxisImage);
         asm("" : "+v"(cur));
-        const LdsImages p = (LdsImages)(uintptr_t)cur;
-        nxt.key = p->key;
-        nxt.aux = p->aux;
-        const double d2 = __dadd_rn(a, e.key);
-        float y;
-        const int slot = tap_slot(w, d2, y);
-        deposit<COUNT>(w, slot, (__int_as_float(e.aux) * y) * cxy, hist, hist32);
-        if (last) break;
+        e1 = entry_at(cur);
+        step(e0);
+        if (cur == stop) break;
+        cur -= (unsigned int)sizeof(AxisImage);
+        asm("" : "+v"(cur));
+        e0 = entry_at(cur);
+        step(e1);
+        if (cur == stop) break;
     }
 }
 
@@ -348,17 +379,17 @@ __device__ __attribute__((noinline)) float beta_pow_slow(double beta, int k) { r
 
 // (out of line for the same reason: only rooms too flat or narrow for the tables come here)
 template <bool COUNT>
-__device__ __attribute__((noinline)) void walk_column_direct(const WalkCtx w, const Axis az, double a, float cxy, int nmz,
+__device__ __attribute__((noinline)) void walk_column_direct(const WalkCtx w, const Axis az, double a, double cxy, int nmz,
                                                              unsigned long long* hist, unsigned int* hist32) {
     for (int q = 0; q < 2; ++q)
         for (int n = -nmz; n <= nmz; ++n) {
             const double dz = axis_delta(az, q, n);
             const double d2 = __dadd_rn(a, __dmul_rn(dz, dz));
-            float y;
+            double y;
             const int slot = tap_slot(w, d2, y);
-            float bz = 0.f;
-            if (!COUNT) bz = beta_pow_slow(w.beta, iabs(n - q) + iabs(n));
-            deposit<COUNT>(w, slot, (bz * y) * cxy, hist, hist32);
+            double bz = 0.0;
+            if (!COUNT) bz = (double)beta_pow_slow(w.beta, iabs(n - q) + iabs(n));
+            deposit<COUNT, false, true>(w, slot, __dmul_rn(bz, cxy), y, hist, hist32);
         }
 }
 
@@ -403,7 +434,6 @@ __device__ inline void build_sorted_images(const Axis& ax, int nm, int* s_split,
         AxisImage e;
         e.key = key;
         e.aux = aux(q, t - nm);
-        e.pad = 0;
         out[rank] = e;
     }
     __syncthreads();
@@ -419,7 +449,7 @@ struct AxisCount {
 };
 
 __device__ inline AxisCount axis_count(const Axis& a, int nm) {
-    return AxisCount{a.src - a.mic, -a.src - a.mic, 1.0 / (2.0 * a.room), (double)nm};
+    return AxisCount{uni(a.src - a.mic), uni(-a.src - a.mic), uni(1.0 / (2.0 * a.room)), uni((double)nm)};
 }
 
 __device__ inline int count_within(const AxisCount& a, double s) {
@@ -464,7 +494,7 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
     const float* __restrict__ geom, int rir_len, double k_fs_c, const Item* __restrict__ items,
     int* __restrict__ ctrl, const float* __restrict__ pow_table, float* __restrict__ rir_out,
     int32_t* __restrict__ cnt_out, unsigned long long* __restrict__ visits = nullptr) {
-    __shared__ unsigned long long hist[(COUNT ? kMaxTaps / 2 : kMaxTaps) + 1];     // slot 0 is never read
+    __shared__ unsigned long long hist[(COUNT ? kMaxTaps / 2 : kMaxTaps) + 2];     // first and last slot are never read
     __shared__ float bpow[COUNT ? 1 : kPow];
     __shared__ AxisImage ztab_store[2 * kAxisCap + 1];
     AxisImage* const ztab = ztab_store + 1;        // z images sorted by dz*dz (one spare entry in front)
@@ -482,37 +512,37 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
     for (;;) {
         if (tid == 0) s_item = atomicAdd(&ctrl[1], 1);
         __syncthreads();
-        const int it = s_item;
+        const int it = uni(s_item);
         if (it >= n_items) break;
         const Item item = items[it];
         const int n0 = item.n0, n1 = item.n1, n_taps = n1 - n0;
         const float* g = geom + (size_t)item.rir * 10;
 
         if (COUNT) {
-            for (int i = tid; i <= n_taps; i += kThreads) hist32[i] = 0u;
+            for (int i = tid; i <= n_taps + 1; i += kThreads) hist32[i] = 0u;
         } else {
-            for (int i = tid; i <= n_taps; i += kThreads) hist[i] = 0ull;
+            for (int i = tid; i <= n_taps + 1; i += kThreads) hist[i] = 0ull;
             for (int i = tid; i < kPow; i += kThreads) bpow[i] = pow_table[(size_t)item.rir * kPow + i];
         }
         __syncthreads();
 
         if (room_ok(g)) {
-            const Axis ax{(double)g[0], (double)g[3], (double)g[6]};
-            const Axis ay{(double)g[1], (double)g[4], (double)g[7]};
-            const Axis az{(double)g[2], (double)g[5], (double)g[8]};
-            const double beta = (double)g[9];
+            const Axis ax{uni((double)g[0]), uni((double)g[3]), uni((double)g[6])};
+            const Axis ay{uni((double)g[1]), uni((double)g[4]), uni((double)g[7])};
+            const Axis az{uni((double)g[2]), uni((double)g[5]), uni((double)g[8])};
+            const double beta = uni((double)g[9]);
             // every image of this item lies in r_in <= d < r_out (half a tap of slack on either side)
-            const double r_out = (double)n1 / k_fs_c;
-            const double r_in = n0 > 0 ? (double)(n0 - 1) / k_fs_c : 0.0;
-            const double r_out2 = r_out * r_out, r_in2 = r_in * r_in;
-            // An image reflected k times adds beta^k / (4 pi d) * 2^56, truncated to an integer, to its
+            const double r_out = uni((double)n1 / k_fs_c);
+            const double r_in = n0 > 0 ? uni((double)(n0 - 1) / k_fs_c) : 0.0;
+            const double r_out2 = uni(r_out * r_out), r_in2 = uni(r_in * r_in);
+            // An image reflected k times adds beta^k / (4 pi d) * 2^56, rounded to an integer, to its
             // tap; once beta^k < 2 pi d 2^-56 that is exactly zero, so such images are never visited.
             // log2_beta < 0 enables the cut (amplitude sums only; tap counts visit every image).
-            const float log2_beta = (!COUNT && g[9] > 0.f && g[9] < 1.f) ? __log2f(g[9]) : 0.f;
-            const int k_cut_item = reflection_cut(log2_beta, (float)r_in);
-            int nmx = (int)ceil(r_out / (2.0 * ax.room)) + 1;
-            int nmy = (int)ceil(r_out / (2.0 * ay.room)) + 1;
-            const int nmz = (int)ceil(r_out / (2.0 * az.room)) + 1;
+            const float log2_beta = (!COUNT && g[9] > 0.f && g[9] < 1.f) ? uni(__log2f(g[9])) : 0.f;
+            const int k_cut_item = uni(reflection_cut(log2_beta, (float)r_in));
+            int nmx = uni((int)ceil(r_out / (2.0 * ax.room)) + 1);
+            int nmy = uni((int)ceil(r_out / (2.0 * ay.room)) + 1);
+            const int nmz = uni((int)ceil(r_out / (2.0 * az.room)) + 1);
             nmx = min(nmx, k_cut_item / 2 + 1);          // |n - q| + |n| >= 2 |n| - 1
             nmy = min(nmy, k_cut_item / 2 + 1);
             const int nix = 2 * (2 * nmx + 1), niy = 2 * (2 * nmy + 1), niz = 2 * (2 * nmz + 1);
@@ -521,14 +551,16 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
             WalkCtx wctx;
             wctx.k_fs_c = k_fs_c;
             const double guard = 1e-12 * (double)(n1 + 1) + 1e-13;
-            wctx.shift = (0.5 + guard) - (double)(n0 - 1);
-            wctx.guard2 = 2.0 * guard;
+            wctx.shift = (0.5 + guard) - (double)(n0 - 1);      // (a vector register: the index step's other factor is scalar)
+            wctx.guard2 = uni(2.0 * guard);
             wctx.n0m1 = n0 - 1;
-            wctx.n_slots = (unsigned int)n_taps + 1u;
+            wctx.n_slots = (unsigned int)n_taps + 2u;
+            // beyond 2.6 m every amplitude is below 2^-5 (see deposit)
+            const bool far_item = r_in >= 2.6;
             wctx.beta = beta;
-            const float y0_max = fmaxf(fabsf((float)(ay.src - ay.mic)), fabsf((float)(ay.src + ay.mic)));
-            const float z0_max = fmaxf(fabsf((float)(az.src - az.mic)), fabsf((float)(az.src + az.mic)));
-            const float lyf = (float)ay.room, lzf = (float)az.room;
+            const float y0_max = uni(fmaxf(fabsf((float)(ay.src - ay.mic)), fabsf((float)(ay.src + ay.mic))));
+            const float z0_max = uni(fmaxf(fabsf((float)(az.src - az.mic)), fabsf((float)(az.src + az.mic))));
+            const float lyf = uni((float)ay.room), lzf = uni((float)az.room);
             // every image with at most k reflections along an axis lies within max|c_q| + (k + 1) L of the
             // microphone on that axis; squared, with a little slack, this bounds the table range to visit
             auto reach2 = [](float c_max, float room, int k) {
@@ -541,11 +573,11 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
             int n_cand;
             if (fast) {
                 build_sorted_images(az, nmz, s_split, ztab, tid, [&](int q, int n) {
-                    if (COUNT) return 0;
+                    if (COUNT) return 0.0;
                     const int k = iabs(n - q) + iabs(n);
-                    return __float_as_int(k < kPow ? bpow[k] : beta_pow_slow(beta, k));
+                    return (double)(k < kPow ? bpow[k] : beta_pow_slow(beta, k));
                 });
-                build_sorted_images(ay, nmy, s_split, ytab, tid, [&](int q, int n) { return iabs(n - q) + iabs(n); });
+                build_sorted_images(ay, nmy, s_split, ytab, tid, [&](int q, int n) { return (double)(iabs(n - q) + iabs(n)); });
                 // live columns of x image ix: the y images with dy^2 <= r_out^2 - dx^2 that the reflection
                 // cut can still reach -- a prefix of the sorted y table
                 for (int ix = tid; ix < nix; ix += kThreads) {
@@ -594,7 +626,7 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
                         const AxisImage ye = ytab[cand - (ix ? row_pfx[ix - 1] : 0)];
                         const double dx = axis_delta(ax, qx, nx);
                         col.a = __dadd_rn(__dmul_rn(dx, dx), ye.key);
-                        col.kxy = (unsigned short)(iabs(nx - qx) + iabs(nx) + ye.aux);
+                        col.kxy = (unsigned short)(iabs(nx - qx) + iabs(nx) + (int)ye.aux);
                     } else {
                         const int ix = cand / niy, iy = cand - ix * niy;
                         const int qx = ix & 1, nx = (ix >> 1) - nmx;
@@ -643,13 +675,14 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
                         if (wc[slot + s - 1].pfx <= p) slot += s;
                     const Column c = wc[slot];
                     const int local = p - (slot ? wc[slot - 1].pfx : 0);
-                    float cxy = 0.f;       // beta^kxy / (4 pi) * 2^24
+                    double cxy = 0.0;      // beta^kxy / (4 pi) * 2^56
                     if (!COUNT)
-                        cxy = (c.kxy < kPow ? bpow[c.kxy] : beta_pow_slow(beta, c.kxy)) * (0.07957747154594767f * 16777216.0f);
+                        cxy = (double)(c.kxy < kPow ? bpow[c.kxy] : beta_pow_slow(beta, c.kxy)) * (0.07957747154594767 * 0x1p56);
                     if (fast) {
                         const int first = (int)c.start + local * kPiece;
                         const int len = min(kPiece, (int)c.len - local * kPiece);
-                        walk_piece_table<COUNT>(wctx, c.a, cxy, ztab + first, len, hist, hist32);
+                        if (far_item) walk_piece_table<COUNT, true>(wctx, c.a, cxy, ztab + first, len, hist, hist32);
+                        else walk_piece_table<COUNT, false>(wctx, c.a, cxy, ztab + first, len, hist, hist32);
                         if (VISITS) walked += (unsigned long long)len;
                     } else {
                         walk_column_direct<COUNT>(wctx, az, c.a, cxy, nmz, hist, hist32);
