@@ -46,6 +46,7 @@ constexpr int kMinTaps = 64;
 constexpr int kPow = 1024;                // beta^k table entries held in LDS
 constexpr int kAxisCap = 320;             // y or z images per q held in the sorted LDS tables 
 constexpr int kPiece = 12;                // images per piece
+constexpr int kStartWords = 32;           // pieces are dealt in chunks of 32 * kStartWords (one bit each in LDS)
 // Work per item, in image visits (see item_cost): the batch's estimated work divided by the number of
 // persistent groups and by kItemsPerGroup, within limits.  Thick shells visit fewer (x, y) columns per image
 // (every shell sets up all columns inside its outer radius), thin ones even out the groups' finishing
@@ -234,10 +235,16 @@ __global__ void rir_sort_items_kernel(const Item* __restrict__ unsorted, Item* _
 struct __align__(8) Column {
     double a;                    // dx*dx + dy*dy
     unsigned short kxy;          // reflections along x and y
-    unsigned short pfx;          // inclusive prefix of piece counts within the wave's batch
+    unsigned short pfx;          // the column's first piece within the wave's batch
     unsigned short start, len;   // range of the sorted z table that can fall inside the shell
 };
 static_assert(sizeof(Column) == 16, "column records are packed");
+
+__device__ inline void wave_sync_lds() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 
 __device__ inline int wave_inclusive_scan(int v, int lane) {
 #pragma unroll
@@ -290,15 +297,22 @@ __device__ inline int reflection_cut(float log2_beta, float d_min) {
 // One Newton step on the root leaves d fs/c good to ~1e-10 taps; shifted up by the guard, its fraction
 // falls below 2 guard exactly when the true value may lie within the guard of a rounding boundary, and only
 // then is the reference recipe evaluated.
-__device__ inline int tap_slot(const WalkCtx& w, double d2, double& y) {
+// (in two parts, so that a caller with several images in hand can run their estimates side by side
+// before any of the rare exact evaluations)
+__device__ inline double tap_estimate(const WalkCtx& w, double d2, double& y) {
     y = __builtin_amdgcn_rsq(d2);
     const double s0 = __dmul_rn(d2, y);                    // sqrt(d2) to 2^-24
     const double res = fma(-s0, s0, d2);                   // exact residual
     const double s1 = fma(__dmul_rn(res, y), 0.5, s0);     // one Newton step: ~4e-15 relative
-    const double t = fma(s1, w.k_fs_c, w.shift);
+    return fma(s1, w.k_fs_c, w.shift);
+}
+__device__ inline int tap_settle(const WalkCtx& w, double d2, double t) {
     int slot = (int)t;
     if (__builtin_amdgcn_fract(t) < w.guard2) slot = exact_tap(d2, w.k_fs_c) - w.n0m1;
     return slot;
+}
+__device__ inline int tap_slot(const WalkCtx& w, double d2, double& y) {
+    return tap_settle(w, d2, tap_estimate(w, d2, y));
 }
 
 // amp2 = amplitude * 2^56, rounded to an integer, goes to the tap's 64-bit integer sum.  Below 2^51 (every
@@ -339,18 +353,13 @@ __device__ inline void walk_piece_table(const WalkCtx& w, double a, double cxy, 
     // (the LDS address itself is the loop variable, opaque to the compiler so that it is not split into
     // a counter plus an offset)
     typedef const AxisImage __attribute__((address_space(3))) * LdsImages;
-    // The entry of the next round is requested before the current one is worked on, so that its LDS latency
-    // passes behind the arithmetic; two rounds per turn of the loop, each with its own pair of registers, so
-    // that no entry is copied.  The last round requests the entry below the piece: z[-1] exists (the table
-    // has a spare entry in front) and is never used.
-    const unsigned int stop = (unsigned int)(uintptr_t)(LdsImages)z - (unsigned int)sizeof(AxisImage);
-    unsigned int cur = stop + (unsigned int)len * (unsigned int)sizeof(AxisImage);
-    auto step = [&](const AxisImage& e) {
-        const double d2 = __dadd_rn(a, e.key);
-        double y;
-        const int slot = tap_slot(w, d2, y);
-        deposit<COUNT, FAR, false>(w, slot, COUNT ? 0.0 : __dmul_rn(e.aux, cxy), y, hist, hist32);
-    };
+    // Two images at a time, so that each lane has two independent chains of arithmetic in flight; the pair
+    // of the next round is requested before the current one is worked on.  A piece of odd length takes the
+    // entry above it as a partner whose distance is made not-a-number: every comparison on it fails and it
+    // lands in slot 0, which is never read.  The last round requests the two entries below the piece, and
+    // an odd piece reads one entry above it: the table has two spare entries in front and one behind.
+    const unsigned int first = (unsigned int)(uintptr_t)(LdsImages)z;
+    unsigned int cur = first + (unsigned int)((len - 1) & ~1) * (unsigned int)sizeof(AxisImage);    // lower entry of the pair
     auto entry_at = [](unsigned int lds_address) {
         const LdsImages p = (LdsImages)(uintptr_t)lds_address;
         AxisImage e;
@@ -358,18 +367,36 @@ __device__ inline void walk_piece_table(const WalkCtx& w, double a, double cxy, 
         e.aux = p->aux;
         return e;
     };
-    AxisImage e0 = entry_at(cur), e1;
+    auto step = [&](const AxisImage& eu, const AxisImage& el) {
+        const double d2u = __dadd_rn(a, eu.key), d2l = __dadd_rn(a, el.key);
+        double yu, yl;
+        const double tu = tap_estimate(w, d2u, yu), tl = tap_estimate(w, d2l, yl);
+        int su = (int)tu, sl = (int)tl;
+        // (one test for both, so that both estimates are complete before the branch)
+        if ((__builtin_amdgcn_fract(tu) < w.guard2) | (__builtin_amdgcn_fract(tl) < w.guard2)) {
+            su = tap_settle(w, d2u, tu);
+            sl = tap_settle(w, d2l, tl);
+        }
+        deposit<COUNT, FAR, false>(w, su, COUNT ? 0.0 : __dmul_rn(eu.aux, cxy), yu, hist, hist32);
+        deposit<COUNT, FAR, false>(w, sl, COUNT ? 0.0 : __dmul_rn(el.aux, cxy), yl, hist, hist32);
+    };
+    AxisImage u0 = entry_at(cur + (unsigned int)sizeof(AxisImage)), l0 = entry_at(cur), u1, l1;
+    if (len & 1) u0.key = __longlong_as_double(0x7ff8000000000000ll);
     for (;;) {
-        cur -= (unsigned int)sizeof(AxisImage);
+        const bool last0 = cur == first;
+        cur -= 2u * (unsigned int)sizeof(AxisImage);
         asm("" : "+v"(cur));
-        e1 = entry_at(cur);
-        step(e0);
-        if (cur == stop) break;
-        cur -= (unsigned int)sizeof(AxisImage);
+        u1 = entry_at(cur + (unsigned int)sizeof(AxisImage));
+        l1 = entry_at(cur);
+        step(u0, l0);
+        if (last0) break;
+        const bool last1 = cur == first;
+        cur -= 2u * (unsigned int)sizeof(AxisImage);
         asm("" : "+v"(cur));
-        e0 = entry_at(cur);
-        step(e1);
-        if (cur == stop) break;
+        u0 = entry_at(cur + (unsigned int)sizeof(AxisImage));
+        l0 = entry_at(cur);
+        step(u1, l1);
+        if (last1) break;
     }
 }
 
@@ -496,12 +523,13 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
     int32_t* __restrict__ cnt_out, unsigned long long* __restrict__ visits = nullptr) {
     __shared__ unsigned long long hist[(COUNT ? kMaxTaps / 2 : kMaxTaps) + 2];     // first and last slot are never read
     __shared__ float bpow[COUNT ? 1 : kPow];
-    __shared__ AxisImage ztab_store[2 * kAxisCap + 1];
-    AxisImage* const ztab = ztab_store + 1;        // z images sorted by dz*dz (one spare entry in front)
+    __shared__ AxisImage ztab_store[2 * kAxisCap + 3];
+    AxisImage* const ztab = ztab_store + 2;        // z images sorted by dz*dz (two spare entries in front, one behind)
     __shared__ AxisImage ytab[2 * kAxisCap];       // y images sorted by dy*dy
     __shared__ int row_pfx[2 * kAxisCap];          // per x image: inclusive prefix of live column counts
     __shared__ int s_split[2];
     __shared__ Column cols[kWaves][64];
+    __shared__ __align__(8) unsigned int piece_starts[kWaves][kStartWords];
     __shared__ int s_item;
     unsigned int* hist32 = reinterpret_cast<unsigned int*>(hist);
 
@@ -660,38 +688,54 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
                     }
                 }
                 const int pfx = wave_inclusive_scan(pieces, lane);
-                col.pfx = (unsigned short)pfx;
+                const int my_first = pfx - pieces;             // this column's first piece
+                col.pfx = (unsigned short)my_first;
                 const int n_pieces = __shfl(pfx, 63, 64);
-                wc[lane] = col;
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                // columns with pieces, packed in order
+                const unsigned long long live = __ballot(pieces > 0);
+                if (pieces > 0)
+                    wc[__builtin_amdgcn_mbcnt_hi((unsigned int)(live >> 32), __builtin_amdgcn_mbcnt_lo((unsigned int)live, 0u))] = col;
 
                 // ---- pieces are dealt to lanes ----
-                for (int p = lane; p < n_pieces; p += 64) {
-                    int slot = 0;                               // smallest slot with pfx > p
-#pragma unroll
-                    for (int s = 32; s > 0; s >>= 1)
-                        if (wc[slot + s - 1].pfx <= p) slot += s;
-                    const Column c = wc[slot];
-                    const int local = p - (slot ? wc[slot - 1].pfx : 0);
-                    double cxy = 0.0;      // beta^kxy / (4 pi) * 2^56
-                    if (!COUNT)
-                        cxy = (double)(c.kxy < kPow ? bpow[c.kxy] : beta_pow_slow(beta, c.kxy)) * (0.07957747154594767 * 0x1p56);
-                    if (fast) {
-                        const int first = (int)c.start + local * kPiece;
-                        const int len = min(kPiece, (int)c.len - local * kPiece);
-                        if (far_item) walk_piece_table<COUNT, true>(wctx, c.a, cxy, ztab + first, len, hist, hist32);
-                        else walk_piece_table<COUNT, false>(wctx, c.a, cxy, ztab + first, len, hist, hist32);
-                        if (VISITS) walked += (unsigned long long)len;
-                    } else {
-                        walk_column_direct<COUNT>(wctx, az, c.a, cxy, nmz, hist, hist32);
-                        if (VISITS) walked += (unsigned long long)niz;
+                // Piece p belongs to the last column that starts at or before it.  Every column sets the bit of
+                // its first piece in a bit map; a piece's column is then a count of bits, not a search.
+                unsigned int* starts = piece_starts[wave];
+                constexpr int kChunk = 32 * kStartWords;
+                for (int chunk = 0; chunk < n_pieces; chunk += kChunk) {
+                    if (lane < kStartWords) starts[lane] = 0u;
+                    wave_sync_lds();
+                    if (pieces > 0 && my_first >= chunk && my_first < chunk + kChunk)
+                        atomicOr(&starts[(my_first - chunk) >> 5], 1u << (my_first & 31));
+                    int before = __popcll(__ballot(pieces > 0 && my_first < chunk));     // columns begun in earlier chunks
+                    wave_sync_lds();
+                    const int chunk_end = min(n_pieces, chunk + kChunk);
+                    for (int p0 = chunk; p0 < chunk_end; p0 += 64) {
+                        const uint2 m = *reinterpret_cast<const uint2*>(&starts[(p0 - chunk) >> 5]);   // pieces p0 .. p0 + 63
+                        // starts in [p0, p0 + lane]: bit 0, and the bits below this lane of the map moved down by one
+                        const unsigned int s_lo = (m.x >> 1) | (m.y << 31), s_hi = m.y >> 1;
+                        const int upto = (int)(m.x & 1u) + (int)__builtin_amdgcn_mbcnt_hi(s_hi, __builtin_amdgcn_mbcnt_lo(s_lo, 0u));
+                        const int p = p0 + lane;
+                        if (p < chunk_end) {
+                            const Column c = wc[before + upto - 1];
+                            const int local = p - (int)c.pfx;
+                            double cxy = 0.0;      // beta^kxy / (4 pi) * 2^56
+                            if (!COUNT)
+                                cxy = (double)(c.kxy < kPow ? bpow[c.kxy] : beta_pow_slow(beta, c.kxy)) * (0.07957747154594767 * 0x1p56);
+                            if (fast) {
+                                const int first = (int)c.start + local * kPiece;
+                                const int len = min(kPiece, (int)c.len - local * kPiece);
+                                if (far_item) walk_piece_table<COUNT, true>(wctx, c.a, cxy, ztab + first, len, hist, hist32);
+                                else walk_piece_table<COUNT, false>(wctx, c.a, cxy, ztab + first, len, hist, hist32);
+                                if (VISITS) walked += (unsigned long long)len;
+                            } else {
+                                walk_column_direct<COUNT>(wctx, az, c.a, cxy, nmz, hist, hist32);
+                                if (VISITS) walked += (unsigned long long)niz;
+                            }
+                        }
+                        before += __popc(m.x) + __popc(m.y);
                     }
+                    wave_sync_lds();
                 }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             }
         }
         __syncthreads();
