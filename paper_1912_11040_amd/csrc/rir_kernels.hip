@@ -46,6 +46,7 @@ constexpr int kMinTaps = 64;
 constexpr int kPow = 1024;                // beta^k table entries held in LDS
 constexpr int kAxisCap = 320;             // y or z images per q held in the sorted LDS tables 
 constexpr int kPiece = 12;                // images per piece
+constexpr int kWalkGroup = 2;             // images a lane works on side by side (three or four measured no better)
 constexpr int kStartWords = 32;           // pieces are dealt in chunks of 32 * kStartWords (one bit each in LDS)
 // Work per item, in image visits (see item_cost): the batch's estimated work divided by the number of
 // persistent groups and by kItemsPerGroup, within limits.  Thick shells visit fewer (x, y) columns per image
@@ -353,13 +354,17 @@ __device__ inline void walk_piece_table(const WalkCtx& w, double a, double cxy, 
     // (the LDS address itself is the loop variable, opaque to the compiler so that it is not split into
     // a counter plus an offset)
     typedef const AxisImage __attribute__((address_space(3))) * LdsImages;
-    // Two images at a time, so that each lane has two independent chains of arithmetic in flight; the pair
-    // of the next round is requested before the current one is worked on.  A piece of odd length takes the
-    // entry above it as a partner whose distance is made not-a-number: every comparison on it fails and it
-    // lands in slot 0, which is never read.  The last round requests the two entries below the piece, and
-    // an odd piece reads one entry above it: the table has two spare entries in front and one behind.
+    // kGroup images at a time, so that each lane has as many independent chains of arithmetic in flight; the
+    // group of the next round is requested before the current one is worked on.  A piece whose length is
+    // not a multiple of kGroup takes the entries above it as partners whose distance is made not-a-number:
+    // every comparison on them fails and they land in slot 0, which is never read.  The last round requests
+    // the kGroup entries below the piece, and a ragged piece reads up to kGroup - 1 entries above it: the
+    // table has spare entries in front and behind.
+    constexpr int kGroup = kWalkGroup;
+    constexpr unsigned int kE = (unsigned int)sizeof(AxisImage);
     const unsigned int first = (unsigned int)(uintptr_t)(LdsImages)z;
-    unsigned int cur = first + (unsigned int)((len - 1) & ~1) * (unsigned int)sizeof(AxisImage);    // lower entry of the pair
+    const int groups = (len + kGroup - 1) / kGroup;
+    unsigned int cur = first + (unsigned int)((groups - 1) * kGroup) * kE;      // lowest entry of the top group
     auto entry_at = [](unsigned int lds_address) {
         const LdsImages p = (LdsImages)(uintptr_t)lds_address;
         AxisImage e;
@@ -367,35 +372,51 @@ __device__ inline void walk_piece_table(const WalkCtx& w, double a, double cxy, 
         e.aux = p->aux;
         return e;
     };
-    auto step = [&](const AxisImage& eu, const AxisImage& el) {
-        const double d2u = __dadd_rn(a, eu.key), d2l = __dadd_rn(a, el.key);
-        double yu, yl;
-        const double tu = tap_estimate(w, d2u, yu), tl = tap_estimate(w, d2l, yl);
-        int su = (int)tu, sl = (int)tl;
-        // (one test for both, so that both estimates are complete before the branch)
-        if ((__builtin_amdgcn_fract(tu) < w.guard2) | (__builtin_amdgcn_fract(tl) < w.guard2)) {
-            su = tap_settle(w, d2u, tu);
-            sl = tap_settle(w, d2l, tl);
-        }
-        deposit<COUNT, FAR, false>(w, su, COUNT ? 0.0 : __dmul_rn(eu.aux, cxy), yu, hist, hist32);
-        deposit<COUNT, FAR, false>(w, sl, COUNT ? 0.0 : __dmul_rn(el.aux, cxy), yl, hist, hist32);
+    struct Group { AxisImage e[kGroup]; };
+    auto load = [&](unsigned int at) {
+        Group g;
+#pragma unroll
+        for (int i = 0; i < kGroup; ++i) g.e[i] = entry_at(at + (unsigned int)i * kE);
+        return g;
     };
-    AxisImage u0 = entry_at(cur + (unsigned int)sizeof(AxisImage)), l0 = entry_at(cur), u1, l1;
-    if (len & 1) u0.key = __longlong_as_double(0x7ff8000000000000ll);
+    auto step = [&](const Group& g) {
+        double d2[kGroup], y[kGroup], t[kGroup];
+        int slot[kGroup];
+        bool redo = false;
+#pragma unroll
+        for (int i = 0; i < kGroup; ++i) {
+            d2[i] = __dadd_rn(a, g.e[i].key);
+            t[i] = tap_estimate(w, d2[i], y[i]);
+            slot[i] = (int)t[i];
+            redo |= __builtin_amdgcn_fract(t[i]) < w.guard2;
+        }
+        if (redo) {       // (one test for all, so that the estimates are complete before the branch)
+#pragma unroll
+            for (int i = 0; i < kGroup; ++i) slot[i] = tap_settle(w, d2[i], t[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < kGroup; ++i)
+            deposit<COUNT, FAR, false>(w, slot[i], COUNT ? 0.0 : __dmul_rn(g.e[i].aux, cxy), y[i], hist, hist32);
+    };
+    Group g0 = load(cur), g1;
+    {
+        const int top = len - 1 - (groups - 1) * kGroup;       // index of the piece's last entry within the top group
+        const double nan = __longlong_as_double(0x7ff8000000000000ll);
+#pragma unroll
+        for (int i = 1; i < kGroup; ++i) if (i > top) g0.e[i].key = nan;
+    }
     for (;;) {
         const bool last0 = cur == first;
-        cur -= 2u * (unsigned int)sizeof(AxisImage);
+        cur -= (unsigned int)kGroup * kE;
         asm("" : "+v"(cur));
-        u1 = entry_at(cur + (unsigned int)sizeof(AxisImage));
-        l1 = entry_at(cur);
-        step(u0, l0);
+        g1 = load(cur);
+        step(g0);
         if (last0) break;
         const bool last1 = cur == first;
-        cur -= 2u * (unsigned int)sizeof(AxisImage);
+        cur -= (unsigned int)kGroup * kE;
         asm("" : "+v"(cur));
-        u0 = entry_at(cur + (unsigned int)sizeof(AxisImage));
-        l0 = entry_at(cur);
-        step(u1, l1);
+        g0 = load(cur);
+        step(g1);
         if (last1) break;
     }
 }
@@ -470,34 +491,35 @@ __device__ inline void build_sorted_images(const Axis& ax, int nm, int* s_split,
 // q in {0,1}, |n| <= nm, ordered by squared distance, so the number of entries within distance s of the
 // microphone is the number of terms of the two arithmetic progressions that lie in [-s, s].
 struct AxisCount {
-    double c0, c1;       // (1 - 2q) src - mic
+    double k0, k1;       // -c_q / (2 L), c_q = (1 - 2q) src - mic
     double inv2l;        // 1 / (2 L)
     double nm;
 };
 
 __device__ inline AxisCount axis_count(const Axis& a, int nm) {
-    return AxisCount{uni(a.src - a.mic), uni(-a.src - a.mic), uni(1.0 / (2.0 * a.room)), uni((double)nm)};
+    const double inv2l = 1.0 / (2.0 * a.room);
+    return AxisCount{uni(-(a.src - a.mic) * inv2l), uni(-(-a.src - a.mic) * inv2l), uni(inv2l), uni((double)nm)};
 }
 
+// terms n of c_q + 2 n L, |n| <= nm, within [-s, s]: (-s - c_q) / 2L <= n <= (s - c_q) / 2L
 __device__ inline int count_within(const AxisCount& a, double s) {
     int total = 0;
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
-        const double c = q ? a.c1 : a.c0;
-        const double hi = fmin(floor((s - c) * a.inv2l), a.nm);
-        const double lo = fmax(ceil((-s - c) * a.inv2l), -a.nm);
+        const double k = q ? a.k1 : a.k0;
+        const double hi = fmin(floor(fma(s, a.inv2l, k)), a.nm);
+        const double lo = fmax(ceil(fma(-s, a.inv2l, k)), -a.nm);
         total += max((int)hi - (int)lo + 1, 0);
     }
     return total;
 }
 
-// sqrt(b) to about 1e-13 relative for b > 0 (fp32 rsq and one fp64 Newton step), 0 for b <= 0
+// sqrt(b) to a few 1e-15 relative for b > 0 (the hardware's estimate of 1/sqrt and one Newton step), 0 for b <= 0
 __device__ inline double quick_sqrt(double b) {
     if (!(b > 1e-30)) return 0.0;
-    const float bf = (float)b;
-    const float y = __frsqrt_rn(bf);
-    const double s0 = (double)(bf * y);
-    return fma(fma(-s0, s0, b), (double)(0.5f * y), s0);
+    const double y = __builtin_amdgcn_rsq(b);
+    const double s0 = __dmul_rn(b, y);
+    return fma(__dmul_rn(fma(-s0, s0, b), y), 0.5, s0);
 }
 
 // The table's keys and these counts round differently, so a bound is widened (or narrowed) by far more
@@ -523,8 +545,8 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
     int32_t* __restrict__ cnt_out, unsigned long long* __restrict__ visits = nullptr) {
     __shared__ unsigned long long hist[(COUNT ? kMaxTaps / 2 : kMaxTaps) + 2];     // first and last slot are never read
     __shared__ float bpow[COUNT ? 1 : kPow];
-    __shared__ AxisImage ztab_store[2 * kAxisCap + 3];
-    AxisImage* const ztab = ztab_store + 2;        // z images sorted by dz*dz (two spare entries in front, one behind)
+    __shared__ AxisImage ztab_store[2 * kAxisCap + 2 * kWalkGroup - 1];
+    AxisImage* const ztab = ztab_store + kWalkGroup;       // z images sorted by dz*dz (spare entries in front and behind)
     __shared__ AxisImage ytab[2 * kAxisCap];       // y images sorted by dy*dy
     __shared__ int row_pfx[2 * kAxisCap];          // per x image: inclusive prefix of live column counts
     __shared__ int s_split[2];
@@ -633,22 +655,20 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
             }
             const int n_batch = (n_cand + 63) / 64;
 
+            int row_lo = 0;          // row of the batch's first candidate: it only moves up from batch to batch
             for (int batch = wave; batch < n_batch; batch += kWaves) {
                 // ---- each lane describes one candidate column ----
                 const int cand = batch * 64 + lane;
+                if (fast)
+                    while (row_pfx[row_lo] <= batch * 64) ++row_lo;       // (the same in every lane; batch * 64 < n_cand)
                 Column col;
                 col.a = 0.0; col.kxy = 0; col.start = 0; col.len = 0;
                 int pieces = 0;
                 if (cand < n_cand) {
                     if (fast) {
-                        // smallest row with row_pfx > cand: found once for the batch's first column (the same
-                        // in every lane), then a short walk, since 64 consecutive columns span few rows
-                        int lo = 0, hi = nix - 1;
-                        const int cand0 = batch * 64;
-                        while (lo < hi) {
-                            const int mid = (lo + hi) >> 1;
-                            if (row_pfx[mid] <= cand0) lo = mid + 1; else hi = mid;
-                        }
+                        // smallest row with row_pfx > cand: a short walk from the row of the batch's first
+                        // column, since 64 consecutive columns span few rows
+                        int lo = row_lo;
                         while (row_pfx[lo] <= cand) ++lo;
                         const int ix = lo, qx = ix & 1, nx = (ix >> 1) - nmx;
                         const AxisImage ye = ytab[cand - (ix ? row_pfx[ix - 1] : 0)];
