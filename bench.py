@@ -42,9 +42,9 @@ PER_CONFIG_STEPS = {"tiny": 300, "features": 100, "batch": 300, "varlen": 200, "
 # runs summarised in profiles/hbm_traffic_<workload>.md, scaled there by a 1 GiB copy.  They describe the
 # kernel sources with this digest only; for any other sources `traffic` is reported as null.
 RECORDED_TRAFFIC = {
-    "digest": "bcc68c625b9d926f",
-    "varlen": {"rir": 145261747, "rir_spectrum": 202505630, "convolve": 2803489590, "mel": 626351460},
-    "throughput": {"rir": 779108039, "rir_spectrum": 1220056162, "convolve": 13821930089, "mel": 2232389535},
+    "digest": "ae2169c35367e195",
+    "varlen": {"rir": 154922760, "rir_spectrum": 202481919, "convolve": 2803568558, "mel": 626413661},
+    "throughput": {"rir": 861668451, "rir_spectrum": 1220086069, "convolve": 13820158887, "mel": 2232413517},
 }
 
 
