@@ -232,8 +232,8 @@ __device__ inline float store_block(const float2 (&v)[16], const ConvBlock& c, i
     return e;
 }
 
-// Work groups are persistent: group g takes a contiguous share of the list of all blocks ordered by
-// (utterance, source, block), so it walks along one reverberated signal block after block.  While a block's
+// Work groups are persistent and take their blocks from the list of all blocks ordered by (utterance,
+// source, block), either a contiguous share or every 32nd block of an eighth of the list (see the kernel).  While a block's
 // inverse transform runs, the inputs of the next block are already on their way from HBM, and the response
 // spectrum is requested before the forward row transforms that precede its use: the loads' latency is
 // hidden behind arithmetic instead of being paid at either end of a short-lived group.
@@ -260,18 +260,37 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
     constexpr bool AHEAD = !MULTI;
     const int tid0 = threadIdx.x;
     const int64_t total = a.n_items * a.n_src;
-    const int64_t w_begin = total * blockIdx.x / gridDim.x, w_end = total * (blockIdx.x + 1) / gridDim.x;
+    // Shares.  With two partitions a group needs consecutive blocks of a signal, so it takes one contiguous
+    // range of the list.  Otherwise the groups that share an L2 (the hardware deals group ids round-robin to
+    // the eight XCDs) take one contiguous eighth of the list together and go through it side by side, group
+    // s of the 32 on blocks s, s + 32, ...: at any time they are on a few neighbouring signals, so a
+    // response spectrum and the halves that neighbouring windows have in common are fetched from HBM once
+    // and found in L2 by the other groups, not re-read by one group a whole block later.
+    constexpr bool STRIDED = !MULTI;
+    int64_t w_begin, w_end, w_step;
+    if (STRIDED) {
+        const int teams = gridDim.x % 8 == 0 ? 8 : 1;
+        const int team = blockIdx.x % teams, slot = blockIdx.x / teams;
+        w_begin = total * team / teams + slot;
+        w_end = total * (team + 1) / teams;
+        w_step = gridDim.x / teams;
+    } else {
+        w_begin = total * blockIdx.x / gridDim.x;
+        w_end = total * (blockIdx.x + 1) / gridDim.x;
+        w_step = 1;
+    }
     if (w_begin >= w_end) return;
 
-    // where the share starts: utterance u (the one that holds item w / n_src), source j, block b
-    int u = a.items[w_begin / a.n_src].x;
-    int nb = a.first[u + 1] - a.first[u];
-    int j, b;
-    {
-        const int r = (int)(w_begin - (int64_t)a.first[u] * a.n_src);
+    // block w of the list: utterance u (the one that holds item w / n_src), source j, block b
+    int u, nb, j, b;
+    auto locate = [&](int64_t at) {
+        u = a.items[at / a.n_src].x;
+        nb = a.first[u + 1] - a.first[u];
+        const int r = (int)(at - (int64_t)a.first[u] * a.n_src);
         j = r / nb;
         b = r - j * nb;
-    }
+    };
+    locate(w_begin);
     auto describe = [&](int uu, int jj, int bb) {
         ConvBlock c;
         const int64_t start = a.offsets[uu];
@@ -381,11 +400,13 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
         __syncthreads();
 
         // the next block of the share: its inputs are requested now and arrive during the inverse transform
-        const bool more = w + 1 < w_end;
+        const bool more = w + w_step < w_end;
         ConvBlock nxt = cur;
         asm volatile("" : "+v"(tid));
         if (more) {
-            if (++b == nb) {
+            if (STRIDED) {
+                locate(w + w_step);
+            } else if (++b == nb) {
                 b = 0;
                 if (++j == a.n_src) {
                     j = 0;
@@ -426,7 +447,7 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
             prev_mid = make_float2(0.f, 0.f);
         }
         cur = nxt;
-        ++w;
+        w += w_step;
     }
 }
 
