@@ -191,6 +191,9 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
         }
         __syncthreads();
     }
+    // Band sums are stored, never added to: an entry that some bin's band owns is rewritten for every frame,
+    // and the others (bands without a bin, the padding) keep the zero they get here.
+    for (int m = sub; m < n_seg; m += kMelLanes) AB[m] = make_float2(0.f, 0.f);
     const bool even_win = (win & 1) == 0;
     const float* extra = MIX ? a.extra + start : nullptr;
     const float* gains = MIX ? a.gains + (size_t)u * a.n_extra : nullptr;
@@ -268,7 +271,6 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
         for (int m = 1; m < 16; ++m) v[m] = cmul(v[m], twp[m]);
         SmallDft<16, false>::run(v);
         fft_store_natural<NC, kMelLanes>(v, buf, sub);
-        for (int m = sub; m < n_seg; m += kMelLanes) AB[m] = make_float2(0.f, 0.f);
         fft_sync<FftSync::Wave>();                       // a frame's 16 lanes share a wavefront
 
         // Bin powers, two at a time: with E = (Z[k] + conj Z[N-k])/2, O = -(i/2)(Z[k] - conj Z[N-k]) and
