@@ -42,9 +42,9 @@ PER_CONFIG_STEPS = {"tiny": 300, "features": 100, "batch": 300, "varlen": 200, "
 # runs summarised in profiles/hbm_traffic_<workload>.md, scaled there by a 1 GiB copy.  They describe the
 # kernel sources with this digest only; for any other sources `traffic` is reported as null.
 RECORDED_TRAFFIC = {
-    "digest": "ae2169c35367e195",
-    "varlen": {"rir": 154922760, "rir_spectrum": 202481919, "convolve": 2803568558, "mel": 626413661},
-    "throughput": {"rir": 861668451, "rir_spectrum": 1220086069, "convolve": 13820158887, "mel": 2232413517},
+    "digest": "3c91bb27db1188d6",
+    "varlen": {"rir": 154882759, "rir_spectrum": 202501682, "convolve": 1257351329, "mel": 622387774},
+    "throughput": {"rir": 866698690, "rir_spectrum": 1219902156, "convolve": 13821346700, "mel": 2214346834},
 }
 
 
