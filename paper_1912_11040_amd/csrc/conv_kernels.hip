@@ -492,14 +492,16 @@ template <int N>
 hipError_t spectrum_n(hipStream_t s, int n_rir, const float* rir, int rir_len, const float2* tw,
                       float2* spec, int* first_tap) {
     constexpr int T = conv_threads(N);
-    const int n_part = (rir_len + N - 1) / N;
+    int n_part = (rir_len + N - 1) / N;
     const size_t lds = sizeof(float2) * lds_padded_size(N);
     auto k = &rir_spectrum_kernel<N, T>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    k<<<dim3((unsigned)(n_rir * n_part)), dim3(T), lds, s>>>(rir, rir_len, n_part, tw, spec, first_tap);
-    return hipGetLastError();
+    // (launched by address, not called through the pointer: the call form is what undefined-behaviour
+    // sanitizers of the host code instrument, and with them it was seen to launch nothing)
+    void* args[] = {&rir, &rir_len, &n_part, &tw, &spec, &first_tap};
+    return hipLaunchKernel(reinterpret_cast<const void*>(k), dim3((unsigned)(n_rir * n_part)), dim3(T), args, lds, s);
 }
 
 template <int N>
@@ -524,8 +526,9 @@ hipError_t convolve_n(hipStream_t s, const float2* tw, const ConvArgs& a, int n_
     int64_t groups = (int64_t)n_cu * per_cu;
     const int64_t total = a.n_items * a.n_src;
     if (groups > total) groups = total;
-    k<<<dim3((unsigned)groups), dim3(T), lds, s>>>(a, tw);
-    return hipGetLastError();
+    ConvArgs by_value = a;
+    void* args[] = {&by_value, &tw};
+    return hipLaunchKernel(reinterpret_cast<const void*>(k), dim3((unsigned)groups), dim3(T), args, lds, s);
 }
 
 }  // namespace

@@ -423,8 +423,12 @@ hipError_t launch_mel(hipStream_t s, const MelArgs& a) {
     const bool mix = a.n_extra > 0;
     auto k = a.cfg.win == 400 ? (mix ? &mel_kernel<NC, 400, true> : &mel_kernel<NC, 400, false>)
                               : (mix ? &mel_kernel<NC, 0, true> : &mel_kernel<NC, 0, false>);
-    k<<<dim3((unsigned)a.n_items), dim3(kMelThreads), lds, s>>>(a, a.twiddle, mel_table_stride(a.cfg.nfft));
-    return hipGetLastError();
+    // (launched by address, not called through the pointer: see the convolution's launcher)
+    MelArgs by_value = a;
+    const float2* tw = a.twiddle;
+    int tab_stride = mel_table_stride(a.cfg.nfft);
+    void* args[] = {&by_value, &tw, &tab_stride};
+    return hipLaunchKernel(reinterpret_cast<const void*>(k), dim3((unsigned)a.n_items), dim3(kMelThreads), args, lds, s);
 }
 
 }  // namespace aug
