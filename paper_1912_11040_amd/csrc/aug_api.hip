@@ -279,6 +279,18 @@ int sync_packing(aug_ctx* ctx, int n_utt, const int64_t* offsets, const int64_t*
     return AUG_OK;
 }
 
+// Output rows per work group of the front end (an upper bound: the kernel shares an utterance's rows evenly
+// among its groups).  A group sets up its utterance's tables once, so larger groups are cheaper per frame
+// as long as the launch still has several times more groups than the chip runs at once (three per compute
+// unit); measured on 4096 utterances of 798 frames: 1.70 ms with 64 rows, 1.55 with 160, 1.51 with 400.
+int frontend_rows_per_group(const aug_ctx* ctx, int n_utt, const int64_t* frame_offsets) {
+    const int base = aug::mel_frames_per_group();
+    const int64_t rows = n_utt > 0 ? frame_offsets[n_utt] : 0;
+    const int64_t wanted = 8LL * 3 * ctx->n_cu;
+    const int64_t fit = rows / wanted / 16 * 16;
+    return (int)std::min<int64_t>(std::max<int64_t>(fit, base), 8 * base);
+}
+
 int ensure_twiddle(aug_ctx* ctx, int n, const float2** out) {
     int lg = 0;
     while ((1 << lg) < n) ++lg;
@@ -685,7 +697,7 @@ int aug_vtlp_mel_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, const fl
     AUG_TRY(check_frame_offsets(ctx, n_utt, offsets, frame_offsets, cfg));
     if ((!wave && offsets[n_utt] > 0) || (!alpha && n_utt > 0) || (!feats_out && frame_offsets[n_utt] > 0))
         return fail(ctx, AUG_ERR_INVALID_ARG, "wave, alpha or feats_out is null");
-    AUG_TRY(sync_packing(ctx, n_utt, offsets, frame_offsets, 0, aug::mel_frames_per_group()));
+    AUG_TRY(sync_packing(ctx, n_utt, offsets, frame_offsets, 0, frontend_rows_per_group(ctx, n_utt, frame_offsets)));
     return run_mel(ctx, n_utt, wave, alpha, cfg, feats_out);
 }
 
@@ -805,7 +817,7 @@ int aug_pipeline_batch(aug_ctx* ctx, int n_utt, const int64_t* offsets, const fl
     if ((int64_t)n_utt * n_src * aug::rir_items_per_response(rir_len) > 0x7fffffffLL)
         return fail(ctx, AUG_ERR_UNSUPPORTED, "too many responses in one call");
     AUG_TRY(sync_packing(ctx, n_utt, offsets, frame_offsets, aug::conv_fft_size(rir_len),
-                         aug::mel_frames_per_group()));
+                         frontend_rows_per_group(ctx, n_utt, frame_offsets)));
     const int64_t total = offsets[n_utt];
     float* rir = rir_out;
     if (!rir) {

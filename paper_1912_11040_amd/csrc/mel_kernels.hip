@@ -128,8 +128,13 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
 
     const int tid = threadIdx.x;
     const int slot = tid / kMelLanes, sub = tid % kMelLanes;
-    const int u = a.items[blockIdx.x].x;
-    const int first = a.items[blockIdx.x].y;
+    // Group ids are dealt round-robin to the eight XCDs.  XCD x takes the x-th contiguous eighth of the item
+    // list, so that every XCD gets the same mix of full and nearly empty groups whatever the period of the
+    // list (equal utterances of four groups each would otherwise leave two XCDs with the short groups only),
+    // and groups that read neighbouring frames of an utterance share an L2.
+    const unsigned int xcd = blockIdx.x % 8u, nth = blockIdx.x / 8u;
+    const unsigned int item = xcd * (gridDim.x / 8u) + min(xcd, gridDim.x % 8u) + nth;
+    const int u = a.items[item].x;
     const int64_t start = a.offsets[u];
     const float* x = a.wave + start;
     const int win = WIN ? WIN : a.cfg.win, hop = a.cfg.hop;
@@ -138,6 +143,11 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
     const int64_t len = a.offsets[u + 1] - start;
     const int64_t rows_u = a.frame_offsets[u + 1] - a.frame_offsets[u];
     const int64_t n_frames_u = len >= win ? 1 + (len - win) / hop : 0;
+    // The utterance's rows are shared evenly among its groups, ceil(rows / frames_per_group) of them (as the
+    // item table counts them), in multiples of the frames a group has in flight: no group is left with a few rows.
+    const int groups_u = (int)((rows_u + a.frames_per_group - 1) / a.frames_per_group);
+    const int rows_per_group = (int)(((rows_u + groups_u - 1) / groups_u + kMelSlots - 1) / kMelSlots) * kMelSlots;
+    const int first = (a.items[item].y / a.frames_per_group) * rows_per_group;
     const float power = a.cfg.power;
     float* feats = a.feats + (size_t)a.frame_offsets[u] * n_out;
     float2* buf = fft_buf + slot * mel_slot_stride<NC>();
@@ -198,7 +208,7 @@ __global__ __launch_bounds__(kMelThreads, 3) void mel_kernel(MelArgs a, const fl
     const float* extra = MIX ? a.extra + start : nullptr;
     const float* gains = MIX ? a.gains + (size_t)u * a.n_extra : nullptr;
 
-    for (int it = 0; it < a.frames_per_group / kMelSlots; ++it) {
+    for (int it = 0; it < rows_per_group / kMelSlots; ++it) {
         const int64_t t = (int64_t)first + it * kMelSlots + slot;
         if ((int64_t)first + it * kMelSlots >= n_frames_u) {      // only padding rows are left in this group
             if (t < rows_u)
