@@ -42,9 +42,9 @@ PER_CONFIG_STEPS = {"tiny": 300, "features": 100, "batch": 300, "varlen": 200, "
 # runs summarised in profiles/hbm_traffic_<workload>.md, scaled there by a 1 GiB copy.  They describe the
 # kernel sources with this digest only; for any other sources `traffic` is reported as null.
 RECORDED_TRAFFIC = {
-    "digest": "9c9deac47ecf3eb2",
-    "varlen": {"rir": 155596298, "rir_spectrum": 202512304, "convolve": 1255325139, "mel": 622369972},
-    "throughput": {"rir": 860431182, "rir_spectrum": 1220066195, "convolve": 13821401500, "mel": 2214200826},
+    "digest": "f2801a51add8d6f1",
+    "varlen": {"rir": 155811140, "rir_spectrum": 202526246, "convolve": 1257154984, "mel": 617806448},
+    "throughput": {"rir": 860494675, "rir_spectrum": 1219945873, "convolve": 13821995428, "mel": 2201839969},
 }
 
 
