@@ -407,7 +407,7 @@ int run_convolve_mix(aug_ctx* ctx, int n_utt, int n_noise, const float* speech, 
                                   (int64_t)n_utt * n_src), "energy and first-tap reset");
     AUG_TRY(mark(ctx, AUG_STAGE_OTHER));
     AUG_HIP(aug::launch_rir_spectrum(ctx->stream, n_utt * n_src, rir, rir_len, fft_n, tw, ctx->rir_spec.as<float2>(),
-                                     ctx->first_tap.as<int>()),
+                                     ctx->first_tap.as<int>(), ctx->n_cu),
             "spectrum kernel");
     AUG_TRY(mark(ctx, AUG_STAGE_RIR_SPECTRUM));
     aug::ConvArgs ca;

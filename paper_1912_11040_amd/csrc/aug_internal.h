@@ -120,7 +120,7 @@ int conv_fft_size(int rir_len);
 // Spectra of the zero-padded partitions of each response: spec float2 [n_rir][n_part][P+1], P = fft_n;
 // the index of every response's first non-zero tap is taken into first_tap[n_rir] (INT_MAX on entry).
 hipError_t launch_rir_spectrum(hipStream_t s, int n_rir, const float* rir, int rir_len, int fft_n,
-                               const float2* twiddle, float2* spec, int* first_tap);
+                               const float2* twiddle, float2* spec, int* first_tap, int n_cu);
 
 // Overlap-save convolution of every (utterance, source) with its response; adds the block's energy
 // to energy[u][j] (double, must be zero on entry).  src_base[j] points at source j's packed signal.

@@ -67,54 +67,77 @@ template <int N> __device__ inline float2 pair_twiddle(const float2* __restrict_
     return cmul(tw[N + k1], tw[N + N / 2 + 1 + k2]);           // exp(-i pi (k1 + 16 k2) / N)
 }
 
-// Spectrum of one response partition, stored in the split order (k at fft_split_pos(k), k = N last)
+// Spectra of the response partitions, stored in the split order (k at fft_split_pos(k), k = N last)
 // and scaled by 1/(4N): 1/N for the unnormalised inverse, 1/4 for the halves that multiply_pair leaves out.
-template <int N, int T>
-__global__ __launch_bounds__(T) void rir_spectrum_kernel(
-    const float* __restrict__ rir, int rir_len, int n_part, const float2* __restrict__ tw,
-    float2* __restrict__ spec, int* __restrict__ first_tap) {
-    extern __shared__ float2 buf[];
+// Work groups are persistent: each takes every gridDim.x-th partition and requests the taps of its next one
+// before the row transforms of the current one, whose twiddles come from a table in LDS (no global load of
+// theirs then stands between the requested taps and the arithmetic).
+template <int N>
+__device__ inline int load_taps(float2 (&v)[8], const float* __restrict__ h, int rir_len, int p, int tid) {
     constexpr int M = N / 16;
-    const int tid = threadIdx.x;
-    const int r = blockIdx.x / n_part, p = blockIdx.x % n_part;
-    const float* h = rir + (size_t)r * rir_len;
-    float2 v[16];
     int first = 0x7fffffff;                          // index of this thread's first non-zero tap
 #pragma unroll
-    for (int n1 = 15; n1 >= 0; --n1) {
-        const int n = tid + M * n1;
-        const int t = p * N + 2 * n;                 // taps of this partition: [pN, (p+1)N), then N zeros
-        float a = 0.f, b = 0.f;
-        if (2 * n < N) {
-            if (t < rir_len) a = h[t];
-            if (t + 1 < rir_len) b = h[t + 1];
-        }
+    for (int n1 = 7; n1 >= 0; --n1) {                // taps of this partition: [pN, (p+1)N), then N zeros
+        const int t = p * N + 2 * (tid + M * n1);
+        const float a = t < rir_len ? h[t] : 0.f, b = t + 1 < rir_len ? h[t + 1] : 0.f;
         v[n1] = make_float2(a, b);
         if (b != 0.f) first = t + 1;
         if (a != 0.f) first = t;
     }
-    // the response is zero before its first non-zero tap, and so is everything convolved with it
-    for (int off = 32; off > 0; off >>= 1) first = min(first, __shfl_down(first, off, 64));
-    if ((tid & 63) == 0 && first != 0x7fffffff) atomicMin(&first_tap[r], first);
-    fft_columns_forward<N>(v, tw, tid);
-    fft_columns_store<N, T>(v, buf, tid);
-    __syncthreads();
-    fft_rows<N, false>(buf, tw, tid);
-    __syncthreads();
-    float2* out = spec + ((size_t)r * n_part + p) * (N + 1);
-    const float scale = 0.25f / (float)N;
-    const int k2 = tid % (M / 2), half = tid / (M / 2);
+    return first;
+}
+
+template <int N, int T>
+__global__ __launch_bounds__(T) void rir_spectrum_kernel(
+    const float* __restrict__ rir, int rir_len, int n_part, int n_work, const float2* __restrict__ tw,
+    float2* __restrict__ spec, int* __restrict__ first_tap) {
+    extern __shared__ float2 buf[];
+    constexpr int M = N / 16;
+    float2* const row_tw = buf + lds_padded_size(N);
+    RowTwiddles<M>::template fill<16>(row_tw, tw, threadIdx.x, T);
+    const int tid0 = threadIdx.x;
+    int work = blockIdx.x;
+    if (work >= n_work) return;
+    float2 taps[8];
+    int first = load_taps<N>(taps, rir + (size_t)(work / n_part) * rir_len, rir_len, work % n_part, tid0);
+    __syncthreads();                                 // the twiddle table is complete
+    for (;;) {
+        int tid = tid0;
+        asm volatile("" : "+v"(tid));
+        const int r = work / n_part, p = work % n_part;
+        // the response is zero before its first non-zero tap, and so is everything convolved with it
+        for (int off = 32; off > 0; off >>= 1) first = min(first, __shfl_down(first, off, 64));
+        if ((tid & 63) == 0 && first != 0x7fffffff) atomicMin(&first_tap[r], first);
+        float2 v[16];
 #pragma unroll
-    for (int i = 0; i <= 8; ++i) {
-        if (i == 8 && tid != 0) break;
-        const PairIndex<N> ix(i == 8 ? 0 : half * 8 + i, i == 8 ? M / 2 : k2);
-        const float2 A = buf[lds_pad(ix.pos)];
-        const float2 B = cconj(buf[lds_pad(ix.pos_partner)]);
-        const float2 w = i == 8 ? tw[N + N / 2] : pair_twiddle<N>(tw, half * 8 + i, k2);
-        float2 Hk, HNk_conj;
-        unpack_pair(A, B, w, Hk, HNk_conj);
-        out[ix.pos] = make_float2(Hk.x * scale, Hk.y * scale);
-        if (i < 8) out[ix.h_partner] = make_float2(HNk_conj.x * scale, -HNk_conj.y * scale);
+        for (int i = 0; i < 16; ++i) v[i] = i < 8 ? taps[i] : make_float2(0.f, 0.f);
+        fft_columns_forward<N>(v, tw, tid);
+        fft_columns_store<N, T>(v, buf, tid);
+        __syncthreads();
+        const int next = work + (int)gridDim.x;
+        if (next < n_work)
+            first = load_taps<N>(taps, rir + (size_t)(next / n_part) * rir_len, rir_len, next % n_part, tid);
+        fft_rows_table<N, false>(buf, row_tw, tid);
+        __syncthreads();
+        asm volatile("" : "+v"(tid));
+        float2* out = spec + ((size_t)r * n_part + p) * (N + 1);
+        const float scale = 0.25f / (float)N;
+        const int k2 = tid % (M / 2), half = tid / (M / 2);
+#pragma unroll
+        for (int i = 0; i <= 8; ++i) {
+            if (i == 8 && tid != 0) break;
+            const PairIndex<N> ix(i == 8 ? 0 : half * 8 + i, i == 8 ? M / 2 : k2);
+            const float2 A = buf[lds_pad(ix.pos)];
+            const float2 B = cconj(buf[lds_pad(ix.pos_partner)]);
+            const float2 w = i == 8 ? tw[N + N / 2] : pair_twiddle<N>(tw, half * 8 + i, k2);
+            float2 Hk, HNk_conj;
+            unpack_pair(A, B, w, Hk, HNk_conj);
+            out[ix.pos] = make_float2(Hk.x * scale, Hk.y * scale);
+            if (i < 8) out[ix.h_partner] = make_float2(HNk_conj.x * scale, -HNk_conj.y * scale);
+        }
+        if (next >= n_work) break;
+        work = next;
+        __syncthreads();                             // every bin is read before the next column store
     }
 }
 
@@ -490,18 +513,25 @@ __global__ __launch_bounds__(256) void mix_kernel(
 
 template <int N>
 hipError_t spectrum_n(hipStream_t s, int n_rir, const float* rir, int rir_len, const float2* tw,
-                      float2* spec, int* first_tap) {
+                      float2* spec, int* first_tap, int n_cu) {
     constexpr int T = conv_threads(N);
     int n_part = (rir_len + N - 1) / N;
-    const size_t lds = sizeof(float2) * lds_padded_size(N);
+    int n_work = n_rir * n_part;
+    const size_t lds = sizeof(float2) * (lds_padded_size(N) + RowTwiddles<N / 16>::kEntries);
     auto k = &rir_spectrum_kernel<N, T>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
+    // as many persistent groups as the chip holds at once (see convolve_n)
+    const int by_lds = (int)((160 * 1024) / (lds + 256));
+    const int by_waves = 16 / ((T + 63) / 64);
+    const int per_cu = by_lds < 1 ? 1 : (by_lds < by_waves ? by_lds : by_waves);
+    int groups = n_cu * per_cu;
+    if (groups > n_work) groups = n_work;
     // (launched by address, not called through the pointer: the call form is what undefined-behaviour
     // sanitizers of the host code instrument, and with them it was seen to launch nothing)
-    void* args[] = {&rir, &rir_len, &n_part, &tw, &spec, &first_tap};
-    return hipLaunchKernel(reinterpret_cast<const void*>(k), dim3((unsigned)(n_rir * n_part)), dim3(T), args, lds, s);
+    void* args[] = {&rir, &rir_len, &n_part, &n_work, &tw, &spec, &first_tap};
+    return hipLaunchKernel(reinterpret_cast<const void*>(k), dim3((unsigned)groups), dim3(T), args, lds, s);
 }
 
 template <int N>
@@ -558,9 +588,9 @@ hipError_t launch_twiddle(hipStream_t s, int n, float2* tw) {
     }
 
 hipError_t launch_rir_spectrum(hipStream_t s, int n_rir, const float* rir, int rir_len, int fft_n,
-                               const float2* twiddle, float2* spec, int* first_tap) {
+                               const float2* twiddle, float2* spec, int* first_tap, int n_cu) {
     if (n_rir <= 0) return hipSuccess;
-#define CALL(NN) spectrum_n<NN>(s, n_rir, rir, rir_len, twiddle, spec, first_tap)
+#define CALL(NN) spectrum_n<NN>(s, n_rir, rir, rir_len, twiddle, spec, first_tap, n_cu)
     AUG_FFT_DISPATCH(fft_n, CALL)
 #undef CALL
 }
