@@ -42,9 +42,9 @@ PER_CONFIG_STEPS = {"tiny": 300, "features": 100, "batch": 300, "varlen": 200, "
 # runs summarised in profiles/hbm_traffic_<workload>.md, scaled there by a 1 GiB copy.  They describe the
 # kernel sources with this digest only; for any other sources `traffic` is reported as null.
 RECORDED_TRAFFIC = {
-    "digest": "f2801a51add8d6f1",
-    "varlen": {"rir": 155811140, "rir_spectrum": 202526246, "convolve": 1257154984, "mel": 617806448},
-    "throughput": {"rir": 860494675, "rir_spectrum": 1219945873, "convolve": 13821995428, "mel": 2201839969},
+    "digest": "98cbc68166af7086",
+    "varlen": {"rir": 155087662, "rir_spectrum": 201851975, "convolve": 1256451650, "mel": 617686604},
+    "throughput": {"rir": 859753607, "rir_spectrum": 1213510534, "convolve": 13821103776, "mel": 2201625372},
 }
 
 
