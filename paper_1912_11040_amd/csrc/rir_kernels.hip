@@ -9,9 +9,9 @@
 // The tap index is integer work decided by floating point, so it follows one fixed
 // fp64 recipe with no contraction:
 //     d2 = (dx*dx + dy*dy) + dz*dz;  idx = floor(sqrt(d2) * (fs/c) + 0.5)
-// A cheap estimate of sqrt (fp32 rsq + one fp64 Newton step) decides the index
-// whenever the result is farther from a rounding boundary than the estimate's error
-// bound; the rare remaining images take the exact correctly-rounded sqrt.
+// A cheap estimate of sqrt (the hardware's double-precision rsq + one Newton step) decides
+// the index whenever the result is farther from a rounding boundary than the estimate's
+// error bound; the rare remaining images take the exact correctly-rounded sqrt.
 //
 // Layout of the work
 //   * plan kernels: one thread per response cuts its taps into shells [n0, n1) of about
@@ -27,12 +27,13 @@
 //     The y images are sorted the same way, so the live columns of an x image are a prefix of the
 //     y table; a prefix sum over the x images numbers the live columns and dead ones are never seen.
 //     A wave takes 64 live columns at a time; their z ranges are cut into pieces of at most kPiece
-//     images, a wave scan numbers the pieces, lanes take pieces by binary search and walk them.
+//     images, a wave scan numbers the pieces, and lanes take pieces 64 at a time (a piece finds its column by
+//     counting bits in a map of the columns' first pieces) and walk them, two images side by side.
 //     Rooms so flat or narrow that an axis has more images than the tables hold take a plain path
 //     (all columns of the bounding box, every z image of a live column).
-//   * amplitudes accumulate as 64-bit fixed point (2^-56) with integer LDS atomics:
-//     gfx950 executes float LDS atomics about thirty times slower than integer ones, and
-//     integer sums do not depend on the order of arrival.
+//   * amplitudes accumulate as 64-bit fixed point (2^-56, each increment rounded to the nearest unit)
+//     with integer LDS atomics: gfx950 executes float LDS atomics about thirty times slower than integer
+//     ones, and integer sums do not depend on the order of arrival nor on how a batch is cut into items.
 
 #include "aug_internal.h"
 
