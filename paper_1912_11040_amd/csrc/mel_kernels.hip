@@ -20,7 +20,7 @@ namespace aug {
 namespace {
 
 constexpr int kMelThreads = 256;
-constexpr int kFramesPerGroup = 64;
+constexpr int kFramesPerGroup = 64;        // smallest target of output rows per work group (the host picks up to 8 times as many)
 
 __global__ void window_kernel(int win, float* w) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
