@@ -62,6 +62,40 @@ def test_features_config_full_size_sampled(aug):
         assert err <= FEAT_TOL
 
 
+def test_large_batch_of_mixed_lengths_with_spare_rows(aug):
+    # Many utterances of very different lengths in one call: enough output rows that the library gives its
+    # work groups more than the smallest share of rows, so an utterance's rows are divided among several
+    # groups of a size that depends on the utterance (none, one, a few, dozens of groups), with spare rows
+    # behind some utterances.  Sampled utterances are checked frame by frame, spare rows must be zero.
+    import torch
+    rng = np.random.default_rng(11)
+    n_utt = 3000
+    lens = rng.integers(0, 6 * 16000, n_utt)
+    lens[:6] = [0, 399, 400, 401, 560, 95999]
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    wave = rng.standard_normal(int(offsets[-1]), dtype=np.float32)
+    alpha = rng.uniform(0.8, 1.2, n_utt).astype(np.float32)
+    frames = np.where(lens >= FE.win, 1 + (lens - FE.win) // FE.hop, 0)
+    spare = rng.integers(0, 3, n_utt) * (rng.random(n_utt) < 0.3)
+    foff = np.concatenate([[0], np.cumsum(frames + spare)]).astype(np.int64)
+    print(f"case: {n_utt} utterances of 0-6 s, {int(foff[-1])} output rows", flush=True)
+    assert foff[-1] > 8 * 3 * 256 * 80          # more than the smallest group size can cover with eight rounds
+    feats = torch.full((int(foff[-1]), FE.feature_dim), float("nan"), dtype=torch.float32, device="cuda")
+    aug.aug_vtlp_mel_batch(offsets, dev(wave), dev(alpha), FE, foff, feats)
+    torch.cuda.synchronize()
+    f = feats.cpu().numpy()
+    assert not np.isnan(f).any()
+    picks = list(range(6)) + [int(np.argmax(lens))] + [int(u) for u in rng.integers(0, n_utt, 9)]
+    for u in picks:
+        a, b = int(offsets[u]), int(offsets[u + 1])
+        ref = O.vtlp_mel_batch(np.array([0, b - a]), wave[a:b], alpha[u:u + 1], FE, method="fft")
+        got = f[foff[u]:foff[u] + frames[u]]
+        assert got.shape == ref.shape
+        if frames[u]:
+            assert feat_err(got, ref) <= FEAT_TOL, u
+        assert not f[foff[u] + frames[u]:foff[u + 1]].any()          # spare rows
+
+
 def test_ragged_short_and_empty_utterances(aug):
     rng = np.random.default_rng(0)
     lens = [0, 399, 400, 559, 560, 12345, 1, 400 + 160 * 63, 400 + 160 * 64, 400 + 160 * 65]
