@@ -59,9 +59,10 @@ __device__ inline float2 mel_bin_entry(const aug_frontend_cfg& cfg, float alpha_
 // Cut the bins of one utterance into 16 contiguous lane ranges that end on changes of the band
 // index c, so that every (c, utterance) sum is formed by one lane alone.  Range i ends at the band
 // change nearest to (i + 1) bins / 16; the ends are non-decreasing because the targets are.
-// One work group of 64 threads per utterance writes the utterance's table, then threads 0..14 each place
-// one boundary.
-__global__ __launch_bounds__(64) void mel_table_kernel(int n_utt, const float* __restrict__ alpha, aug_frontend_cfg cfg,
+// One work group per utterance writes the utterance's table (a thread per bin at K = 512: the entry is a
+// chain of double-precision library calls), then threads 0..14 each place one boundary.
+constexpr int kMelTableThreads = 320;
+__global__ __launch_bounds__(kMelTableThreads) void mel_table_kernel(int n_utt, const float* __restrict__ alpha, aug_frontend_cfg cfg,
                                                        int stride, float2* __restrict__ tab) {
     __shared__ float band[2050];
     const int bins = cfg.nfft / 2 + 1;
@@ -69,7 +70,7 @@ __global__ __launch_bounds__(64) void mel_table_kernel(int n_utt, const float* _
     float2* t = tab + (size_t)u * stride;
     int* kstart = reinterpret_cast<int*>(tab + (size_t)u * stride + bins);
     const float alpha_u = alpha[u];
-    for (int k = threadIdx.x; k < bins; k += 64) {
+    for (int k = threadIdx.x; k < bins; k += kMelTableThreads) {
         const float2 e = mel_bin_entry(cfg, alpha_u, k);
         t[k] = e;
         band[k] = e.x;
@@ -419,7 +420,7 @@ int mel_table_stride(int nfft) { return nfft / 2 + 1 + 9; }   // (c, w) per bin,
 hipError_t launch_mel_table(hipStream_t s, int n_utt, const float* alpha, const aug_frontend_cfg& cfg,
                             float2* tab) {
     if (n_utt <= 0) return hipSuccess;
-    mel_table_kernel<<<dim3((unsigned)n_utt), dim3(64), 0, s>>>(n_utt, alpha, cfg, mel_table_stride(cfg.nfft), tab);
+    mel_table_kernel<<<dim3((unsigned)n_utt), dim3(kMelTableThreads), 0, s>>>(n_utt, alpha, cfg, mel_table_stride(cfg.nfft), tab);
     return hipGetLastError();
 }
 

@@ -55,7 +55,9 @@ constexpr int kStartWords = 32;           // pieces are dealt in chunks of 32 * 
 // times; every response yields at least one item, so the groups still get several items each.  Measured:
 // 16000-tap batch 0.89 -> 0.80 ms, 32768-tap batch 12.8 -> 7.6 ms against a fixed 600000.
 constexpr float kItemsPerGroup = 1.25f;
-constexpr float kMinTargetWork = 300000.f, kMaxTargetWork = 8000000.f;
+// (the lower limit matters for small batches only, where items must be small for all groups to get one:
+// 64 utterances with 8000-tap responses take 0.122 ms at 300000, 0.080 ms at 50000)
+constexpr float kMinTargetWork = 50000.f, kMaxTargetWork = 8000000.f;
 constexpr float kWorkUnit = 4096.f;       // the batch total is summed in integers of this many visits
 constexpr int kMaxShells = 96;            // volume-balanced shells per response, at most
 
@@ -193,7 +195,15 @@ __global__ void rir_classify_kernel(const float* __restrict__ geom, int rir_len,
     if ((int)blockIdx.x >= item_groups) {
         const int g = blockIdx.x - item_groups;
         const int r = g / (kPow / 256), k = (g % (kPow / 256)) * 256 + threadIdx.x;
-        pow_table[(size_t)r * kPow + k] = (float)pow((double)geom[(size_t)r * 10 + 9], (double)k);
+        // beta^k by squaring (k < 1024: ten steps, a few units in the last place of the double, far inside the
+        // float it is stored as; the library pow is some ten times the instructions)
+        double b = (double)geom[(size_t)r * 10 + 9], acc = 1.0;
+#pragma unroll
+        for (int bit = 0; bit < 10; ++bit) {
+            if ((k >> bit) & 1) acc *= b;
+            b *= b;
+        }
+        pow_table[(size_t)r * kPow + k] = (float)acc;
         return;
     }
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
