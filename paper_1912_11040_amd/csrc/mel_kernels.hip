@@ -59,8 +59,10 @@ __device__ inline float2 mel_bin_entry(const aug_frontend_cfg& cfg, float alpha_
 // Cut the bins of one utterance into 16 contiguous lane ranges that end on changes of the band
 // index c, so that every (c, utterance) sum is formed by one lane alone.  Range i ends at the band
 // change nearest to (i + 1) bins / 16; the ends are non-decreasing because the targets are.
-// One work group per utterance writes the utterance's table (a thread per bin at K = 512: the entry is a
-// chain of double-precision library calls), then threads 0..14 each place one boundary.
+// One work group per utterance writes the utterance's table, then threads 0..14 each place one boundary.
+// An entry is a chain of double-precision library calls: with few utterances a group has a thread per bin
+// (K = 512) so that the chains run side by side, with many a single wavefront, which fills the chip anyway
+// and measured twice as fast there.
 constexpr int kMelTableThreads = 320;
 __global__ __launch_bounds__(kMelTableThreads) void mel_table_kernel(int n_utt, const float* __restrict__ alpha, aug_frontend_cfg cfg,
                                                        int stride, float2* __restrict__ tab) {
@@ -70,7 +72,7 @@ __global__ __launch_bounds__(kMelTableThreads) void mel_table_kernel(int n_utt, 
     float2* t = tab + (size_t)u * stride;
     int* kstart = reinterpret_cast<int*>(tab + (size_t)u * stride + bins);
     const float alpha_u = alpha[u];
-    for (int k = threadIdx.x; k < bins; k += kMelTableThreads) {
+    for (int k = threadIdx.x; k < bins; k += (int)blockDim.x) {
         const float2 e = mel_bin_entry(cfg, alpha_u, k);
         t[k] = e;
         band[k] = e.x;
@@ -420,7 +422,8 @@ int mel_table_stride(int nfft) { return nfft / 2 + 1 + 9; }   // (c, w) per bin,
 hipError_t launch_mel_table(hipStream_t s, int n_utt, const float* alpha, const aug_frontend_cfg& cfg,
                             float2* tab) {
     if (n_utt <= 0) return hipSuccess;
-    mel_table_kernel<<<dim3((unsigned)n_utt), dim3(kMelTableThreads), 0, s>>>(n_utt, alpha, cfg, mel_table_stride(cfg.nfft), tab);
+    const int threads = n_utt >= 1024 ? 64 : kMelTableThreads;
+    mel_table_kernel<<<dim3((unsigned)n_utt), dim3(threads), 0, s>>>(n_utt, alpha, cfg, mel_table_stride(cfg.nfft), tab);
     return hipGetLastError();
 }
 
