@@ -206,27 +206,37 @@ __global__ void rir_classify_kernel(const float* __restrict__ geom, int rir_len,
         pow_table[(size_t)r * kPow + k] = (float)acc;
         return;
     }
+    // (the census is taken per work group in LDS first: one global atomic per class and group, not per item)
+    __shared__ int census[kClasses];
+    if (threadIdx.x < kClasses) census[threadIdx.x] = 0;
+    __syncthreads();
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= ctrl[0]) return;
-    Item it = unsorted[i];
-    const float* g = geom + (size_t)it.rir * 10;
-    int cls = kClasses - 1;
-    if (room_ok(g)) {
-        const double radius = (double)rir_len / k_fs_c;
-        const float est = 4.18879f * (float)(radius * radius * radius) / (g[0] * g[1] * g[2]);
-        const float log2_beta = (g[9] > 0.f && g[9] < 1.f) ? __log2f(g[9]) : 0.f;
-        const float cost = item_cost(g, log2_beta, est, (float)rir_len, (float)it.n0, (float)it.n1, (float)(1.0 / k_fs_c));
-        cls = min(max((int)(2.5f * __log2f(3.2e7f / fmaxf(cost, 1.f))), 0), kClasses - 1);
+    if (i < ctrl[0]) {
+        Item it = unsorted[i];
+        const float* g = geom + (size_t)it.rir * 10;
+        int cls = kClasses - 1;
+        if (room_ok(g)) {
+            const double radius = (double)rir_len / k_fs_c;
+            const float est = 4.18879f * (float)(radius * radius * radius) / (g[0] * g[1] * g[2]);
+            const float log2_beta = (g[9] > 0.f && g[9] < 1.f) ? __log2f(g[9]) : 0.f;
+            const float cost = item_cost(g, log2_beta, est, (float)rir_len, (float)it.n0, (float)it.n1, (float)(1.0 / k_fs_c));
+            cls = min(max((int)(2.5f * __log2f(3.2e7f / fmaxf(cost, 1.f))), 0), kClasses - 1);
+        }
+        unsorted[i].cls = cls;
+        atomicAdd(&census[cls], 1);
     }
-    unsorted[i].cls = cls;
-    atomicAdd(&ctrl[2 + cls], 1);
+    __syncthreads();
+    if (threadIdx.x < kClasses && census[threadIdx.x]) atomicAdd(&ctrl[2 + threadIdx.x], census[threadIdx.x]);
 }
 
 // Items move to their class's stretch of the sorted table, heaviest class first: persistent groups then take
 // the heaviest items first and finish on the light ones, which evens out their finishing times.
 // ctrl[2 + c] is the census of class c, ctrl[2 + kClasses + c] the cursor within its stretch.
 __global__ void rir_sort_items_kernel(const Item* __restrict__ unsorted, Item* __restrict__ sorted, int* __restrict__ ctrl) {
-    __shared__ int first_slot[kClasses];
+    // (a work group numbers its items of a class in LDS and takes their places in the class's stretch with
+    // one global atomic per class)
+    __shared__ int first_slot[kClasses], mine[kClasses];
+    if (threadIdx.x < kClasses) mine[threadIdx.x] = 0;
     if (threadIdx.x == 0) {
         int at = 0;
         for (int c = 0; c < kClasses; ++c) {
@@ -236,9 +246,18 @@ __global__ void rir_sort_items_kernel(const Item* __restrict__ unsorted, Item* _
     }
     __syncthreads();
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= ctrl[0]) return;
-    const Item it = unsorted[i];
-    sorted[first_slot[it.cls] + atomicAdd(&ctrl[2 + kClasses + it.cls], 1)] = it;
+    const bool have = i < ctrl[0];
+    Item it;
+    int rank = 0;
+    if (have) {
+        it = unsorted[i];
+        rank = atomicAdd(&mine[it.cls], 1);
+    }
+    __syncthreads();
+    if (threadIdx.x < kClasses && mine[threadIdx.x])
+        first_slot[threadIdx.x] += atomicAdd(&ctrl[2 + kClasses + threadIdx.x], mine[threadIdx.x]);
+    __syncthreads();
+    if (have) sorted[first_slot[it.cls] + rank] = it;
 }
 
 // per-column record shared through LDS between the lane that built it and the lanes that walk its pieces
