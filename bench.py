@@ -42,9 +42,9 @@ PER_CONFIG_STEPS = {"tiny": 300, "features": 100, "batch": 300, "varlen": 200, "
 # runs summarised in profiles/hbm_traffic_<workload>.md, scaled there by a 1 GiB copy.  They describe the
 # kernel sources with this digest only; for any other sources `traffic` is reported as null.
 RECORDED_TRAFFIC = {
-    "digest": "4f9df675b75c2687",
-    "varlen": {"rir": 155949994, "rir_spectrum": 201881314, "convolve": 1256701330, "mel": 617658791},
-    "throughput": {"rir": 869533060, "rir_spectrum": 1213399991, "convolve": 13821076013, "mel": 2201626796},
+    "digest": "f902a8a8a2b1871d",
+    "varlen": {"rir": 154971692, "rir_spectrum": 201808386, "convolve": 1256270711, "mel": 617800642},
+    "throughput": {"rir": 861308393, "rir_spectrum": 1213501645, "convolve": 13821917376, "mel": 2202291281},
 }
 
 

@@ -142,9 +142,10 @@ __device__ inline float response_work(const float* g, int rir_len, double k_fs_c
 __global__ void rir_work_kernel(int n_rir, const float* __restrict__ geom, int rir_len, double k_fs_c,
                                 int* __restrict__ ctrl) {
     const int r = blockIdx.x * blockDim.x + threadIdx.x;
-    if (r >= n_rir) return;
-    const float work = response_work(geom + (size_t)r * 10, rir_len, k_fs_c);
-    atomicAdd(&ctrl[kCtrlWork], (int)fminf(work / kWorkUnit, 500000.f) + 1);
+    int units = 0;
+    if (r < n_rir) units = (int)fminf(response_work(geom + (size_t)r * 10, rir_len, k_fs_c) / kWorkUnit, 500000.f) + 1;
+    for (int off = 32; off > 0; off >>= 1) units += __shfl_down(units, off, 64);      // one atomic per wavefront
+    if ((threadIdx.x & 63) == 0 && units) atomicAdd(&ctrl[kCtrlWork], units);
 }
 
 // One thread per response: cut its taps into shells of about equal image count (equal volume), at most
