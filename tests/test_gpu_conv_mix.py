@@ -136,6 +136,26 @@ def test_whole_blocks_and_odd_starts_at_the_largest_transform(aug):
     _check(aug, offsets, speech, noise, rir, snr)
 
 
+def test_more_blocks_than_work_groups_at_a_small_transform(aug):
+    # Many short utterances with short responses: the block list (about 4500 blocks of 1024 samples) is longer
+    # than the launch has work groups, so each group takes one or two blocks, a stride apart, of its XCD's
+    # eighth of the list; some eighths are not a multiple of the stride long.  Every utterance is checked.
+    rng = np.random.default_rng(12)
+    n_utt, n_noise, L = 500, 2, 700
+    lens = rng.integers(2100, 3100, n_utt)
+    lens[:3] = [1, 1024, 3072]
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    total = int(offsets[-1])
+    speech = rng.standard_normal(total).astype(np.float32)
+    noise = rng.standard_normal((n_noise, total)).astype(np.float32)
+    rir = _decaying_rirs(rng, n_utt, 1 + n_noise, L)
+    snr = rng.uniform(0, 20, (n_utt, n_noise)).astype(np.float32)
+    blocks = int(np.sum((lens + 1023) // 1024)) * (1 + n_noise)
+    print(f"case: {n_utt} utterances, L={L}, {blocks} blocks of 1024 samples", flush=True)
+    assert blocks > 4096
+    _check(aug, offsets, speech, noise, rir, snr, method="fft")
+
+
 def test_most_noise_sources_the_interface_takes(aug):
     rng = np.random.default_rng(12)
     lens = [1500, 0, 2600, 700]
