@@ -282,7 +282,7 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
     // loads issued ahead of time; the inputs and the response spectrum are then loaded where they are used.
     constexpr bool AHEAD = !MULTI;
     const int tid0 = threadIdx.x;
-    const int64_t total = a.n_items * a.n_src;
+    const int total = (int)(a.n_items * a.n_src);          // (the launcher refuses lists of 2^31 blocks or more)
     // Shares.  With two partitions a group needs consecutive blocks of a signal, so it takes one contiguous
     // range of the list.  Otherwise the groups that share an L2 (the hardware deals group ids round-robin to
     // the eight XCDs) take one contiguous eighth of the list together and go through it side by side, group
@@ -290,28 +290,28 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
     // response spectrum and the halves that neighbouring windows have in common are fetched from HBM once
     // and found in L2 by the other groups, not re-read by one group a whole block later.
     constexpr bool STRIDED = !MULTI;
-    int64_t w_begin, w_end, w_step;
+    int w_begin, w_end, w_step;
     if (STRIDED) {
         const int teams = gridDim.x % 8 == 0 ? 8 : 1;
         const int team = blockIdx.x % teams, slot = blockIdx.x / teams;
-        w_begin = total * team / teams + slot;
-        w_end = total * (team + 1) / teams;
-        w_step = gridDim.x / teams;
+        w_begin = (int)((int64_t)total * team / teams) + slot;
+        w_end = (int)((int64_t)total * (team + 1) / teams);
+        w_step = (int)gridDim.x / teams;
     } else {
-        w_begin = total * blockIdx.x / gridDim.x;
-        w_end = total * (blockIdx.x + 1) / gridDim.x;
+        w_begin = (int)((int64_t)total * blockIdx.x / gridDim.x);
+        w_end = (int)((int64_t)total * (blockIdx.x + 1) / gridDim.x);
         w_step = 1;
     }
     if (w_begin >= w_end) return;
 
     // block w of the list: utterance u (the one that holds item w / n_src), source j, block b
     int u, nb, j, b;
-    auto locate = [&](int64_t at) {
-        u = a.items[at / a.n_src].x;
+    auto locate = [&](int at) {
+        u = a.items[(unsigned int)at / (unsigned int)a.n_src].x;
         nb = a.first[u + 1] - a.first[u];
-        const int r = (int)(at - (int64_t)a.first[u] * a.n_src);
-        j = r / nb;
-        b = r - j * nb;
+        const unsigned int r = (unsigned int)(at - a.first[u] * a.n_src);
+        j = (int)(r / (unsigned int)nb);
+        b = (int)r - j * nb;
     };
     locate(w_begin);
     auto describe = [&](int uu, int jj, int bb) {
@@ -339,7 +339,7 @@ __global__ __launch_bounds__(T) void convolve_kernel(ConvArgs a, const float2* _
     }
     if (AHEAD) load_window<N>(v, cur.x, cur.len, cur.b, tid0);
 
-    for (int64_t w = w_begin;;) {
+    for (int w = w_begin;;) {
         // The thread index is made opaque in every round so that twiddle powers and addresses are not
         // hoisted out of the loop, where they would sit on top of the transforms' registers.
         int tid = tid0;
@@ -555,6 +555,7 @@ hipError_t convolve_n(hipStream_t s, const float2* tw, const ConvArgs& a, int n_
     const int per_cu = by_lds < 1 ? 1 : (by_lds < by_waves ? by_lds : by_waves);
     int64_t groups = (int64_t)n_cu * per_cu;
     const int64_t total = a.n_items * a.n_src;
+    if (total > 0x7fffffffLL) return hipErrorInvalidValue;
     if (groups > total) groups = total;
     ConvArgs by_value = a;
     void* args[] = {&by_value, &tw};
