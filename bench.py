@@ -42,9 +42,9 @@ PER_CONFIG_STEPS = {"tiny": 300, "features": 100, "batch": 300, "varlen": 200, "
 # runs summarised in profiles/hbm_traffic_<workload>.md, scaled there by a 1 GiB copy.  They describe the
 # kernel sources with this digest only; for any other sources `traffic` is reported as null.
 RECORDED_TRAFFIC = {
-    "digest": "f902a8a8a2b1871d",
-    "varlen": {"rir": 154971692, "rir_spectrum": 201808386, "convolve": 1256270711, "mel": 617800642},
-    "throughput": {"rir": 861308393, "rir_spectrum": 1213501645, "convolve": 13821917376, "mel": 2202291281},
+    "digest": "fd94d88fd501c379",
+    "varlen": {"rir": 155582260, "rir_spectrum": 201862652, "convolve": 1255010107, "mel": 617665341},
+    "throughput": {"rir": 863734658, "rir_spectrum": 1213654572, "convolve": 13820696832, "mel": 2201899672},
 }
 
 
