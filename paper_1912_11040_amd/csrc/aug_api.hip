@@ -328,7 +328,6 @@ int prepare_rir(aug_ctx* ctx, int n_rir, int rir_len) {
     AUG_TRY(grow(ctx, ctx->rir_items, 2 * aug::rir_item_bytes() * (size_t)n_rir * aug::rir_items_per_response(rir_len),
                  "response item table"));
     AUG_TRY(grow(ctx, ctx->rir_ctrl, aug::rir_ctrl_ints() * sizeof(int), "response item counter"));
-    AUG_TRY(grow(ctx, ctx->rir_pow, sizeof(float) * (size_t)n_rir * aug::rir_pow_entries(), "reflection table"));
     return AUG_OK;
 }
 
@@ -364,14 +363,14 @@ int run_rir(aug_ctx* ctx, int n_rir, const float* geom, int rir_len, float fs, f
     const int n_groups = 2 * ctx->n_cu;
     AUG_TRY(mark(ctx, -1));
     AUG_HIP(aug::launch_rir_plan(ctx->stream, n_groups, n_rir, geom, rir_len, k, ctx->rir_items.ptr,
-                                 ctx->rir_ctrl.as<int>(), ctx->rir_pow.as<float>()), "rir plan kernel");
+                                 ctx->rir_ctrl.as<int>()), "rir plan kernel");
     AUG_TRY(mark(ctx, AUG_STAGE_OTHER));
     AUG_HIP(aug::launch_rir(ctx->stream, n_groups, n_rir, geom, rir_len, k, ctx->rir_items.ptr,
-                            ctx->rir_ctrl.as<int>(), ctx->rir_pow.as<float>(), rir_out, nullptr, false), "rir kernel");
+                            ctx->rir_ctrl.as<int>(), rir_out, nullptr, false), "rir kernel");
     AUG_TRY(mark(ctx, AUG_STAGE_RIR));
     if (tap_count_out) {
         AUG_HIP(aug::launch_rir(ctx->stream, n_groups, n_rir, geom, rir_len, k, ctx->rir_items.ptr,
-                                ctx->rir_ctrl.as<int>(), ctx->rir_pow.as<float>(), nullptr, tap_count_out, true),
+                                ctx->rir_ctrl.as<int>(), nullptr, tap_count_out, true),
                 "rir count kernel");
         AUG_TRY(mark(ctx, AUG_STAGE_OTHER));
     }
@@ -565,7 +564,7 @@ int aug_destroy(aug_ctx* ctx) {
     }
     DeviceBuffer* bufs[] = {&ctx->d_offsets, &ctx->d_frame_offsets, &ctx->d_conv_items, &ctx->d_frame_items,
                             &ctx->d_conv_first, &ctx->d_frame_first,
-                            &ctx->rir_items, &ctx->rir_ctrl, &ctx->rir_pow, &ctx->mic_rows, &ctx->visits, &ctx->rir, &ctx->rir_spec, &ctx->reverb, &ctx->energy, &ctx->gains, &ctx->first_tap, &ctx->vtlp_tab, &ctx->dct, &ctx->mel_tab,
+                            &ctx->rir_items, &ctx->rir_ctrl, &ctx->mic_rows, &ctx->visits, &ctx->rir, &ctx->rir_spec, &ctx->reverb, &ctx->energy, &ctx->gains, &ctx->first_tap, &ctx->vtlp_tab, &ctx->dct, &ctx->mel_tab,
                             &ctx->window};
     for (DeviceBuffer* b : bufs) b->release();
     for (DeviceBuffer& b : ctx->twiddle) b.release();
@@ -643,9 +642,9 @@ int aug_rir_visited_images(aug_ctx* ctx, int n_rir, const float* geom, int rir_l
     const int n_groups = 2 * ctx->n_cu;
     AUG_HIP(aug::launch_fill_u32(ctx->stream, ctx->visits.ptr, 0u, 2), "visit counter clear");
     AUG_HIP(aug::launch_rir_plan(ctx->stream, n_groups, n_rir, geom, rir_len, k, ctx->rir_items.ptr,
-                                 ctx->rir_ctrl.as<int>(), ctx->rir_pow.as<float>()), "rir plan kernel");
+                                 ctx->rir_ctrl.as<int>()), "rir plan kernel");
     AUG_HIP(aug::launch_rir(ctx->stream, n_groups, n_rir, geom, rir_len, k, ctx->rir_items.ptr, ctx->rir_ctrl.as<int>(),
-                            ctx->rir_pow.as<float>(), rir_out, nullptr, false, ctx->visits.as<unsigned long long>()),
+                            rir_out, nullptr, false, ctx->visits.as<unsigned long long>()),
             "rir kernel");
     unsigned long long v = 0;
     AUG_HIP(hipMemcpyAsync(&v, ctx->visits.ptr, sizeof v, hipMemcpyDeviceToHost, ctx->stream), "visit counter copy");

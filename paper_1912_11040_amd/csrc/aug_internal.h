@@ -65,7 +65,6 @@ struct aug_ctx {
     int n_cu = 0;                        // compute units of the device
     aug::DeviceBuffer rir_items;         // Item [n_rir * items_per_response]
     aug::DeviceBuffer rir_ctrl;          // int [rir_ctrl_ints()]: item count, next item, class counters
-    aug::DeviceBuffer rir_pow;           // float [n_rir][pow entries]: beta^k
     aug::DeviceBuffer visits;            // one 64-bit counter (aug_rir_visited_images)
     aug::DeviceBuffer mic_rows;          // float [n_rir * n_mic][10]: one geometry row per microphone
 
@@ -94,7 +93,7 @@ namespace aug {
 // ---- kernels' host launchers (each checks nothing; arguments are validated by the API layer) ----
 
 // Image-method impulse responses.  launch_rir_plan cuts every response into items (tap ranges of
-// about equal image count) ordered heaviest first, fills the beta^k tables and resets ctrl (item count,
+// about equal image count) ordered heaviest first and resets ctrl (item count,
 // next item, class counters: rir_ctrl_ints() ints); `items` needs room for 2 n_rir rir_items_per_response items;
 // launch_rir then runs n_groups persistent work groups over the items (restart: once more over the
 // same plan), writing either
@@ -104,11 +103,10 @@ namespace aug {
 int rir_items_per_response(int rir_len);
 size_t rir_item_bytes();
 int rir_ctrl_ints();
-int rir_pow_entries();
 hipError_t launch_rir_plan(hipStream_t s, int n_groups, int n_rir, const float* geom, int rir_len, double fs_over_c,
-                           void* items, int* ctrl, float* pow_table);
+                           void* items, int* ctrl);
 hipError_t launch_rir(hipStream_t s, int n_groups, int n_rir, const float* geom, int rir_len, double fs_over_c,
-                      const void* items, int* ctrl, const float* pow_table, float* rir_out, int32_t* cnt_out,
+                      const void* items, int* ctrl, float* rir_out, int32_t* cnt_out,
                       bool restart, unsigned long long* visits = nullptr);
 
 // rows float [n_rir * n_mic][10]: geometry row r / n_mic with microphone mics[r] (float [n_rir][n_mic][3]).

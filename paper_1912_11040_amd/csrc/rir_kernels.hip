@@ -92,6 +92,22 @@ __device__ inline bool room_ok(const float* g) {
 
 struct Item { int rir, n0, n1, cls; };
 
+__device__ inline void wave_sync_lds() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ inline int wave_inclusive_scan(int v, int lane) {
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int t = __shfl_up(v, off, 64);
+        if (lane >= off) v += t;
+    }
+    return v;
+}
+
+
 constexpr int kClasses = 32;            // cost classes for the order in which items are handed out
 // ctrl: [0] number of items, [1] next item to hand out, [2 .. 2+kClasses) items per class,
 // [2+kClasses .. 2+2 kClasses) next free slot of each class in the sorted table, then the batch's
@@ -148,23 +164,22 @@ __global__ void rir_work_kernel(int n_rir, const float* __restrict__ geom, int r
     if ((threadIdx.x & 63) == 0 && units) atomicAdd(&ctrl[kCtrlWork], units);
 }
 
-// One thread per response: cut its taps into shells of about equal image count (equal volume), at most
-// kMaxTaps wide, and append them to the unsorted item table.
-__global__ void rir_plan_kernel(int n_rir, const float* __restrict__ geom, int rir_len, double k_fs_c,
-                                Item* __restrict__ unsorted, int items_per_rir, int* __restrict__ ctrl, int n_groups) {
-    const int r = blockIdx.x * blockDim.x + threadIdx.x;
-    if (r >= n_rir) return;
-    const float* g = geom + (size_t)r * 10;
-    const float target = fminf(fmaxf(kWorkUnit * (float)ctrl[kCtrlWork] / ((float)n_groups * kItemsPerGroup),
-                                     kMinTargetWork), kMaxTargetWork);
-    const float work = response_work(g, rir_len, k_fs_c);
+// Work per item that a batch of `units` work units (kWorkUnit visits each) aims at.
+__device__ inline float item_target(int units, int n_groups) {
+    return fminf(fmaxf(kWorkUnit * (float)units / ((float)n_groups * kItemsPerGroup), kMinTargetWork), kMaxTargetWork);
+}
+
+constexpr int kMaxBounds = kMaxShells + AUG_MAX_RIR_LEN / kMaxTaps + 4;
+
+// Cut the taps of a response of estimated work `work` into shells of about equal image count (equal volume), at most kMaxTaps wide:
+// bounds[i] is the lower bound of shell i, outermost shell first; returns their number.
+// Shells are cut from the outside in: every shell sets up all (x, y) columns inside its outer radius, so
+// where the tap limit, not the work, decides the width it is the inner shells, with few columns, that
+// should be the many and the narrow ones, and the left-over sliver belongs at the centre.
+__device__ inline int cut_shells(float work, int rir_len, float target, int items_per_rir, int (&bounds)[kMaxBounds]) {
     const float shells = fminf(fmaxf(ceilf(work / target), 1.f), (float)kMaxShells);
     const double L3 = (double)rir_len * rir_len * rir_len;
     const double step = L3 / (double)shells;
-    // Shells are cut from the outside in: every shell sets up all (x, y) columns inside its outer radius, so
-    // where the tap limit, not the work, decides the width it is the inner shells, with few columns, that
-    // should be the many and the narrow ones, and the left-over sliver belongs at the centre.
-    int bounds[kMaxShells + AUG_MAX_RIR_LEN / kMaxTaps + 4];      // lower bounds, outermost shell first
     int count = 0, hi = rir_len;
     while (hi > 0 && count < items_per_rir - 1) {
         const double h3 = (double)hi * hi * hi;
@@ -180,6 +195,28 @@ __global__ void rir_plan_kernel(int n_rir, const float* __restrict__ geom, int r
         bounds[count++] = lo;
         hi = lo;
     }
+    return count;
+}
+
+// cost class of an item (0 = heaviest)
+__device__ inline int item_class(const float* g, int rir_len, double k_fs_c, int n0, int n1) {
+    if (!room_ok(g)) return kClasses - 1;
+    const double radius = (double)rir_len / k_fs_c;
+    const float est = 4.18879f * (float)(radius * radius * radius) / (g[0] * g[1] * g[2]);
+    const float log2_beta = (g[9] > 0.f && g[9] < 1.f) ? __log2f(g[9]) : 0.f;
+    const float cost = item_cost(g, log2_beta, est, (float)rir_len, (float)n0, (float)n1, (float)(1.0 / k_fs_c));
+    return min(max((int)(2.5f * __log2f(3.2e7f / fmaxf(cost, 1.f))), 0), kClasses - 1);
+}
+
+// One thread per response: cut its taps into shells and append them to the unsorted item table.
+__global__ void rir_plan_kernel(int n_rir, const float* __restrict__ geom, int rir_len, double k_fs_c,
+                                Item* __restrict__ unsorted, int items_per_rir, int* __restrict__ ctrl, int n_groups) {
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= n_rir) return;
+    const float* g = geom + (size_t)r * 10;
+    int bounds[kMaxBounds];
+    const int count = cut_shells(response_work(g, rir_len, k_fs_c), rir_len, item_target(ctrl[kCtrlWork], n_groups),
+                                 items_per_rir, bounds);
     const int base = atomicAdd(&ctrl[0], count);
     int top = rir_len;
     for (int i = 0; i < count; ++i) {
@@ -188,41 +225,84 @@ __global__ void rir_plan_kernel(int n_rir, const float* __restrict__ geom, int r
     }
 }
 
-// one thread per item: its cost class (0 = heaviest), and the class census; the groups past
-// `item_groups` fill the beta^k tables instead (kPow / 256 groups per response)
-__global__ void rir_classify_kernel(const float* __restrict__ geom, int rir_len, double k_fs_c,
-                                    Item* __restrict__ unsorted, int* __restrict__ ctrl, int item_groups,
-                                    float* __restrict__ pow_table) {
-    if ((int)blockIdx.x >= item_groups) {
-        const int g = blockIdx.x - item_groups;
-        const int r = g / (kPow / 256), k = (g % (kPow / 256)) * 256 + threadIdx.x;
-        // beta^k by squaring (k < 1024: ten steps, a few units in the last place of the double, far inside the
-        // float it is stored as; the library pow is some ten times the instructions)
-        double b = (double)geom[(size_t)r * 10 + 9], acc = 1.0;
-#pragma unroll
-        for (int bit = 0; bit < 10; ++bit) {
-            if ((k >> bit) & 1) acc *= b;
-            b *= b;
-        }
-        pow_table[(size_t)r * kPow + k] = (float)acc;
-        return;
+// The whole plan in one work group, for batches of at most kPlanThreads responses (four launches and a clear
+// cost more than the work there): a thread per response for the batch's work and the shells (their places in
+// the table by a scan, not by atomics), then all threads over the items for their classes and the counting
+// sort.  Leaves ctrl[0] = number of items, ctrl[1] = 0.
+constexpr int kPlanThreads = 1024;
+__global__ __launch_bounds__(kPlanThreads) void rir_plan_all_kernel(
+    int n_rir, const float* __restrict__ geom, int rir_len, double k_fs_c, Item* __restrict__ sorted,
+    Item* __restrict__ unsorted, int items_per_rir, int* __restrict__ ctrl, int n_groups) {
+    __shared__ int part[kPlanThreads / 64];
+    __shared__ int census[kClasses], first_slot[kClasses], cursor[kClasses];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid < kClasses) census[tid] = cursor[tid] = 0;
+    const int r = tid;                                 // this thread's response, if any
+    const float* g = geom + (size_t)min(r, n_rir - 1) * 10;
+
+    const float work = r < n_rir ? response_work(g, rir_len, k_fs_c) : 0.f;
+    int units = r < n_rir ? (int)fminf(work / kWorkUnit, 500000.f) + 1 : 0;
+    for (int off = 32; off > 0; off >>= 1) units += __shfl_down(units, off, 64);
+    if (lane == 0) part[wave] = units;
+    __syncthreads();
+    int total_units = 0;
+    for (int w = 0; w < kPlanThreads / 64; ++w) total_units += part[w];
+    const float target = item_target(total_units, n_groups);
+    __syncthreads();
+
+    int bounds[kMaxBounds];
+    const int count = r < n_rir ? cut_shells(work, rir_len, target, items_per_rir, bounds) : 0;
+    const int incl = wave_inclusive_scan(count, lane);
+    if (lane == 63) part[wave] = incl;
+    __syncthreads();
+    int before = 0, n_items = 0;
+    for (int w = 0; w < kPlanThreads / 64; ++w) {
+        if (w < wave) before += part[w];
+        n_items += part[w];
     }
+    {
+        const int base = before + incl - count;
+        int top = rir_len;
+        for (int i = 0; i < count; ++i) {
+            unsorted[base + i] = Item{r, bounds[i], top, kClasses - 1};
+            top = bounds[i];
+        }
+    }
+    __syncthreads();                                   // the group's writes to `unsorted` are visible to it
+    for (int i = tid; i < n_items; i += kPlanThreads) {
+        const Item it = unsorted[i];
+        const int cls = item_class(geom + (size_t)it.rir * 10, rir_len, k_fs_c, it.n0, it.n1);
+        unsorted[i].cls = cls;                         // (read back by this same thread below)
+        atomicAdd(&census[cls], 1);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int at = 0;
+        for (int c = 0; c < kClasses; ++c) {
+            first_slot[c] = at;
+            at += census[c];
+        }
+        ctrl[0] = n_items;
+        ctrl[1] = 0;
+    }
+    __syncthreads();
+    for (int i = tid; i < n_items; i += kPlanThreads) {
+        const Item it = unsorted[i];
+        sorted[first_slot[it.cls] + atomicAdd(&cursor[it.cls], 1)] = it;
+    }
+}
+
+// one thread per item: its cost class (0 = heaviest), and the class census
+__global__ void rir_classify_kernel(const float* __restrict__ geom, int rir_len, double k_fs_c,
+                                    Item* __restrict__ unsorted, int* __restrict__ ctrl) {
     // (the census is taken per work group in LDS first: one global atomic per class and group, not per item)
     __shared__ int census[kClasses];
     if (threadIdx.x < kClasses) census[threadIdx.x] = 0;
     __syncthreads();
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < ctrl[0]) {
-        Item it = unsorted[i];
-        const float* g = geom + (size_t)it.rir * 10;
-        int cls = kClasses - 1;
-        if (room_ok(g)) {
-            const double radius = (double)rir_len / k_fs_c;
-            const float est = 4.18879f * (float)(radius * radius * radius) / (g[0] * g[1] * g[2]);
-            const float log2_beta = (g[9] > 0.f && g[9] < 1.f) ? __log2f(g[9]) : 0.f;
-            const float cost = item_cost(g, log2_beta, est, (float)rir_len, (float)it.n0, (float)it.n1, (float)(1.0 / k_fs_c));
-            cls = min(max((int)(2.5f * __log2f(3.2e7f / fmaxf(cost, 1.f))), 0), kClasses - 1);
-        }
+        const Item it = unsorted[i];
+        const int cls = item_class(geom + (size_t)it.rir * 10, rir_len, k_fs_c, it.n0, it.n1);
         unsorted[i].cls = cls;
         atomicAdd(&census[cls], 1);
     }
@@ -271,21 +351,6 @@ struct __align__(8) Column {
     unsigned short start, len;   // range of the sorted z table that can fall inside the shell
 };
 static_assert(sizeof(Column) == 16, "column records are packed");
-
-__device__ inline void wave_sync_lds() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-__device__ inline int wave_inclusive_scan(int v, int lane) {
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int t = __shfl_up(v, off, 64);
-        if (lane >= off) v += t;
-    }
-    return v;
-}
 
 // One image along an axis, as stored in the sorted tables: key = squared distance to the microphone
 // along that axis (reference operation order); aux = beta^reflections (z axis) or the reflection count
@@ -572,7 +637,7 @@ __device__ inline int count_below(const AxisCount& a, double bound) {
 template <bool COUNT, bool VISITS = false>
 __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
     const float* __restrict__ geom, int rir_len, double k_fs_c, const Item* __restrict__ items,
-    int* __restrict__ ctrl, const float* __restrict__ pow_table, float* __restrict__ rir_out,
+    int* __restrict__ ctrl, float* __restrict__ rir_out,
     int32_t* __restrict__ cnt_out, unsigned long long* __restrict__ visits = nullptr) {
     __shared__ unsigned long long hist[(COUNT ? kMaxTaps / 2 : kMaxTaps) + 2];     // first and last slot are never read
     __shared__ float bpow[COUNT ? 1 : kPow];
@@ -603,7 +668,17 @@ __global__ __launch_bounds__(kThreads, 4) void rir_image_kernel(
             for (int i = tid; i <= n_taps + 1; i += kThreads) hist32[i] = 0u;
         } else {
             for (int i = tid; i <= n_taps + 1; i += kThreads) hist[i] = 0ull;
-            for (int i = tid; i < kPow; i += kThreads) bpow[i] = pow_table[(size_t)item.rir * kPow + i];
+            // beta^k by squaring (k < 1024: ten steps, a few units in the last place of the double, far inside
+            // the float it is kept as; the library pow is some ten times the instructions)
+            for (int i = tid; i < kPow; i += kThreads) {
+                double b = (double)g[9], acc = 1.0;
+#pragma unroll
+                for (int bit = 0; bit < 10; ++bit) {
+                    if ((i >> bit) & 1) acc *= b;
+                    b *= b;
+                }
+                bpow[i] = (float)acc;
+            }
         }
         __syncthreads();
 
@@ -859,19 +934,23 @@ hipError_t launch_rir_mic_rows(hipStream_t s, int n_rir, int n_mic, const float*
 
 int rir_items_per_response(int rir_len) { return kMaxShells + rir_len / kMaxTaps + 2; }
 size_t rir_item_bytes() { return sizeof(Item); }
-int rir_pow_entries() { return kPow; }
 
 int rir_ctrl_ints() { return kCtrlInts; }
 
 hipError_t launch_rir_plan(hipStream_t s, int n_groups, int n_rir, const float* geom, int rir_len, double fs_over_c,
-                           void* items, int* ctrl, float* pow_table) {
+                           void* items, int* ctrl) {
     if (n_rir <= 0) return hipSuccess;
-    hipError_t e = launch_fill_u32(s, ctrl, 0u, kCtrlInts);
-    if (e != hipSuccess) return e;
     // `items` holds the sorted table followed by the unsorted one
     const int per_rir = rir_items_per_response(rir_len);
     Item* sorted = static_cast<Item*>(items);
     Item* unsorted = sorted + (size_t)n_rir * per_rir;
+    if (n_rir <= kPlanThreads) {                             // one launch instead of five
+        rir_plan_all_kernel<<<dim3(1), dim3(kPlanThreads), 0, s>>>(n_rir, geom, rir_len, fs_over_c, sorted, unsorted,
+                                                                    per_rir, ctrl, n_groups);
+        return hipGetLastError();
+    }
+    hipError_t e = launch_fill_u32(s, ctrl, 0u, kCtrlInts);
+    if (e != hipSuccess) return e;
     rir_work_kernel<<<dim3((n_rir + 127) / 128), dim3(128), 0, s>>>(n_rir, geom, rir_len, fs_over_c, ctrl);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -881,8 +960,7 @@ hipError_t launch_rir_plan(hipStream_t s, int n_groups, int n_rir, const float* 
     if (e != hipSuccess) return e;
     const size_t max_items = (size_t)n_rir * per_rir;
     const int item_groups = (int)((max_items + 255) / 256);
-    rir_classify_kernel<<<dim3((unsigned)(item_groups + n_rir * (kPow / 256))), dim3(256), 0, s>>>(
-        geom, rir_len, fs_over_c, unsorted, ctrl, item_groups, pow_table);
+    rir_classify_kernel<<<dim3((unsigned)item_groups), dim3(256), 0, s>>>(geom, rir_len, fs_over_c, unsorted, ctrl);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     rir_sort_items_kernel<<<dim3((unsigned)item_groups), dim3(256), 0, s>>>(unsorted, sorted, ctrl);
@@ -890,7 +968,7 @@ hipError_t launch_rir_plan(hipStream_t s, int n_groups, int n_rir, const float* 
 }
 
 hipError_t launch_rir(hipStream_t s, int n_groups, int n_rir, const float* geom, int rir_len, double fs_over_c,
-                      const void* items, int* ctrl, const float* pow_table, float* rir_out, int32_t* cnt_out,
+                      const void* items, int* ctrl, float* rir_out, int32_t* cnt_out,
                       bool restart, unsigned long long* visits) {
     if (n_rir <= 0) return hipSuccess;
     hipError_t e = hipSuccess;
@@ -901,13 +979,13 @@ hipError_t launch_rir(hipStream_t s, int n_groups, int n_rir, const float* geom,
     const Item* it = static_cast<const Item*>(items);
     if (rir_out && visits)
         rir_image_kernel<false, true><<<dim3((unsigned)n_groups), dim3(kThreads), 0, s>>>(
-            geom, rir_len, fs_over_c, it, ctrl, pow_table, rir_out, nullptr, visits);
+            geom, rir_len, fs_over_c, it, ctrl, rir_out, nullptr, visits);
     else if (rir_out)
         rir_image_kernel<false><<<dim3((unsigned)n_groups), dim3(kThreads), 0, s>>>(
-            geom, rir_len, fs_over_c, it, ctrl, pow_table, rir_out, nullptr);
+            geom, rir_len, fs_over_c, it, ctrl, rir_out, nullptr);
     else
         rir_image_kernel<true><<<dim3((unsigned)n_groups), dim3(kThreads), 0, s>>>(
-            geom, rir_len, fs_over_c, it, ctrl, pow_table, nullptr, cnt_out);
+            geom, rir_len, fs_over_c, it, ctrl, nullptr, cnt_out);
     return hipGetLastError();
 }
 
