@@ -42,9 +42,9 @@ PER_CONFIG_STEPS = {"tiny": 300, "features": 100, "batch": 300, "varlen": 200, "
 # runs summarised in profiles/hbm_traffic_<workload>.md, scaled there by a 1 GiB copy.  They describe the
 # kernel sources with this digest only; for any other sources `traffic` is reported as null.
 RECORDED_TRAFFIC = {
-    "digest": "fd94d88fd501c379",
-    "varlen": {"rir": 155582260, "rir_spectrum": 201862652, "convolve": 1255010107, "mel": 617665341},
-    "throughput": {"rir": 863734658, "rir_spectrum": 1213654572, "convolve": 13820696832, "mel": 2201899672},
+    "digest": "b10178e637ae96d5",
+    "varlen": {"rir": 144776913, "rir_spectrum": 201797926, "convolve": 1254849701, "mel": 617857198},
+    "throughput": {"rir": 782242713, "rir_spectrum": 1213474671, "convolve": 13819990189, "mel": 2201970965},
 }
 
 
